@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched pipeline-schedule evaluation on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input that is already
+resident in HBM: adaptra_eval (feasibility pre-pass, max-plus recurrence for every pair,
+makespan + per-stage bubbles + flag byte) followed by adaptra_best (pre-pass, recurrence over
+the feasible pairs, per-scenario argmin, winner's bubbles, histogram if the configuration
+asks for one).  `value` counts each (candidate, scenario) pair once per step.
+
+Prints ONE JSON line (see the fields below).  `roofline` prices the dominant kernel (the
+recurrence kernel of adaptra_eval) against the integer-VALU peak: 3 int32 operations per
+resolved op (add the link delay, max with the stage frontier, add the duration), divided by
+the kernel's duration measured with HIP events recorded by the library on its own stream.
+`cpu_baseline` is the CPU oracle timed on a bounded sample of the same pairs.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT32_VALU_PEAK = 256 * 64 * 2.4e9          # CUs x lanes/clk x clock = 39.32e12 int32 lane-ops/s
+
+
+class HipEvents:
+    """Raw hipEvent_t handles (the library records them; torch events cannot be handed over)."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        ev = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(ev))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate failed ({rc})")
+        return ev
+
+    def elapsed_ms(self, a, b) -> float:
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed ({rc})")
+        return float(ms.value)
+
+    def destroy(self, ev):
+        self.hip.hipEventDestroy(ev)
+
+
+def cpu_baseline(wl, target_seconds: float = 15.0) -> dict:
+    """The oracle as it stands, on the host cores, on a seeded sample of this workload's pairs."""
+    from oracle import oracle
+    from paper_2504_19232_amd import workloads
+    threads = oracle.default_threads()
+    n = 512
+    pc, ps = workloads.sample_pairs(4242, wl.n_cand, wl.n_scen, 1 << 22)
+    t0 = time.perf_counter()
+    oracle.eval_workload(wl, pair_cand=pc[:n], pair_scen=ps[:n], threads=threads)
+    probe = time.perf_counter() - t0
+    n = int(min(len(pc), max(n, n * target_seconds / max(probe, 1e-3))))
+    t0 = time.perf_counter()
+    r = oracle.eval_workload(wl, pair_cand=pc[:n], pair_scen=ps[:n], threads=threads)
+    dt = time.perf_counter() - t0
+    live = int(((r["flag"] & 2) == 0).sum())
+    return {"value": n / dt, "unit": "evaluations/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n} seeded random pairs of the workload ({live} not deadlocked), "
+                      f"event-driven simulation incl. bubbles, {dt:.1f} s",
+            "resolved_ops_per_s": live * 2.0 * wl.S * wl.M / dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=3, help="workload index 0..4 (default 3: S=32, M=128, 2^26 pairs)")
+    ap.add_argument("--no-bubble", action="store_true", help="skip adaptra_eval's [S][K][C] bubble output")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-mode", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); nothing here is distributed.",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2504_19232_amd import binding, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    binding.load()
+    binding.adaptra_set_kernel_mode(args.kernel_mode)
+
+    wl = workloads.config(args.config)
+    S, M, C, K = wl.S, wl.M, wl.n_cand, wl.n_scen
+    w_bound = int(wl.w.max())                      # known to whoever generated the candidates
+    prob = binding.Problem.from_workload(wl, w_bound=w_bound)
+    dev = prob.device
+    ws = binding.alloc_workspace(prob)
+    mk = torch.empty((K, C), dtype=torch.int32, device=dev)
+    fl = torch.empty((K, C), dtype=torch.uint8, device=dev)
+    bub = None if args.no_bubble else torch.empty((S, K, C), dtype=torch.int32, device=dev)
+    bidx = torch.empty(K, dtype=torch.int32, device=dev)
+    bmk = torch.empty(K, dtype=torch.int32, device=dev)
+    bbub = torch.empty((K, S), dtype=torch.int32, device=dev)
+    hist = torch.empty((S, wl.hist_bins), dtype=torch.int64, device=dev) if wl.hist_bins else None
+
+    def step():
+        binding.adaptra_eval(prob, mk, bub, fl, want_bubble=bub is not None, workspace=ws)
+        binding.adaptra_best(prob, bidx, bmk, bbub, hist, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # per-step timing of adaptra_eval's recurrence kernel, through events the library records
+    evs = HipEvents()
+    pairs = [(evs.create(), evs.create()) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        binding.adaptra_set_resolve_events(pairs[i][0], pairs[i][1])
+        binding.adaptra_eval(prob, mk, bub, fl, want_bubble=bub is not None, workspace=ws)
+        binding.adaptra_set_resolve_events(None, None)
+        binding.adaptra_best(prob, bidx, bmk, bbub, hist, workspace=ws)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kernel_ms = [evs.elapsed_ms(a, b) for a, b in pairs]
+    for a, b in pairs:
+        evs.destroy(a)
+        evs.destroy(b)
+
+    # separate timings of the two entry points (outside the timed region)
+    def timed(fn, n=3):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / n
+
+    t_eval = timed(lambda: binding.adaptra_eval(prob, mk, bub, fl, want_bubble=bub is not None, workspace=ws))
+    t_best = timed(lambda: binding.adaptra_best(prob, bidx, bmk, bbub, hist, workspace=ws))
+
+    flags = fl[0].cpu().numpy()                    # the flag depends on the candidate only
+    n_live = int(((flags & 2) == 0).sum())
+    n_feasible = int((flags == 1).sum())
+    ops_per_pair = 2 * S * M
+    ops_eval = n_live * K * ops_per_pair           # ops resolved by adaptra_eval's kernel per launch
+    ops_best = n_feasible * K * ops_per_pair
+    ms_step = dt / args.steps * 1e3
+    kernel_avg_ms = float(np.mean(kernel_ms))
+    achieved = 3.0 * ops_eval / (kernel_avg_ms * 1e-3)
+
+    out = {
+        "metric": "schedule_evaluations_per_sec",
+        "value": C * K / (dt / args.steps),
+        "unit": "evaluations/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {wl.name}: S={S}, M={M}, {C} candidates x {K} scenarios "
+                               f"= {C * K} pairs; step = adaptra_eval (makespan"
+                               f"{'' if args.no_bubble else ' + bubbles'} + flags) + adaptra_best",
+                   "pairs": C * K, "not_deadlocked_candidates": n_live, "feasible_candidates": n_feasible,
+                   "w_bound": w_bound, "kernel_mode": args.kernel_mode, "inputs_sha256": wl.sha256()},
+        "resolved_ops_per_s": (ops_eval + ops_best) / (dt / args.steps),
+        "eval": {"ms": t_eval * 1e3, "evaluations_per_s": C * K / t_eval, "resolved_ops_per_s": ops_eval / t_eval},
+        "best": {"ms": t_best * 1e3, "evaluations_per_s": C * K / t_best, "resolved_ops_per_s": ops_best / t_best},
+        "roofline": {"bound": "alu", "kernel": f"k_resolve_scen_lanes<{S}, eval>",
+                     "achieved": achieved / 1e12, "peak": INT32_VALU_PEAK / 1e12, "unit": "Tint32op/s",
+                     "frac": achieved / INT32_VALU_PEAK, "traffic": None,
+                     "kernel_ms": kernel_avg_ms, "resolved_ops_per_launch": ops_eval,
+                     "algorithmic_ops_per_resolved_op": 3},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

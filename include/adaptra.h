@@ -1,0 +1,167 @@
+/*
+ * adaptra.h -- C ABI of the batched pipeline-schedule evaluator for MI355X (gfx950).
+ *
+ * The library evaluates the paper's analytical pipeline model for many
+ * (schedule candidate, straggler scenario) pairs at once and searches, for each
+ * scenario, the candidate with the smallest pipeline execution time.
+ *
+ * Model (Adaptra paper):
+ *   - A candidate is a 1F1B-family schedule of S stages and M micro-batches,
+ *     fixed by the warm-up forward count of every stage (Section 4.1, the three
+ *     phases; Section 4.3, the warm-up quota).  Here w[s] counts warm-up
+ *     forwards with the last stage of plain 1F1B at 0, so the paper's
+ *     x_s = w[s] + 1 (Algorithm 2 starts from x_{S-1} = 1).  Stage s executes, in
+ *     this order, one op at a time:  F(0..w-1);  then F(w+k), B(k) for
+ *     k = 0..M-w-1;  then B(M-w..M-1).  w is clamped into [0, M-1] first.
+ *   - A scenario gives the delay of every inter-stage link, forward and backward
+ *     direction separately (Section 3.1: c_i is added on the link S_i <-> S_{i+1}).
+ *   - Dependencies (Section 3.1): F(s,m) starts after F(s-1,m) has finished plus
+ *     c_fwd[s-1]; B(s,m) starts after B(s+1,m) has finished plus c_bwd[s];
+ *     B(S-1,m) follows F(S-1,m); every stage runs its ops in the order above.
+ *     Links are pure latencies (Section 4 assumes no head-of-line blocking).
+ *   - Results per pair: makespan = pipeline execution time T (Table 1);
+ *     bubble[s] = idle time of stage s inside [0, T] = T - M (t_f[s] + t_b[s])
+ *     (Section 1: bubbles are GPU idle periods); a flag byte:
+ *         1  feasible
+ *         2  deadlock: the warm-up counts increase somewhere, w[s] < w[s+1]
+ *            (Lemma 1, monotonic warm-up) -- the fixed order can never complete
+ *         4  memory cap exceeded: w[s] + 1 > mem_cap[s] for some s (Algorithm 1:
+ *            at most x_max activations are held per device)
+ *         6  both
+ *     A deadlocked pair reports INT32_MAX for makespan and every bubble.  A pair
+ *     that only exceeds the memory cap still reports its real times (Section 4.2
+ *     lifts the cap by host offloading) but is never chosen by adaptra_best.
+ *
+ * All times are int32 microseconds.  Precondition (see adaptra_check_inputs):
+ * 2 * M * S * (max time + max delay) < 2^31, which bounds every path in the
+ * dependency graph.
+ *
+ * Conventions for every entry point:
+ *   - The three structs live in HOST memory; every pointer inside them, every
+ *     out_* pointer and the workspace are DEVICE pointers owned by the caller.
+ *     The library allocates no device memory and keeps no state between calls
+ *     except the option set by adaptra_set_kernel_mode.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     adaptra_eval and adaptra_best only enqueue work on it and return; they do
+ *     not synchronise.  Outputs are valid once the stream has drained.
+ *   - Return value: ADAPTRA_OK or one of the error codes below.  Per-pair
+ *     conditions (deadlock, memory cap) are data, not errors.
+ */
+#ifndef ADAPTRA_H
+#define ADAPTRA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ADAPTRA_OK          0
+#define ADAPTRA_EINVAL      1   /* null pointer, S/M/n out of range, bad histogram spec      */
+#define ADAPTRA_EWORKSPACE  2   /* workspace missing, misaligned (256 B) or too small         */
+#define ADAPTRA_EHIP        3   /* a HIP call failed; see adaptra_last_hip_error              */
+#define ADAPTRA_ERANGE      4   /* adaptra_check_inputs: a negative time, delay or w          */
+#define ADAPTRA_EOVERFLOW   5   /* adaptra_check_inputs: 2 M S (max t + max c) >= 2^31        */
+
+#define ADAPTRA_FLAG_FEASIBLE 1
+#define ADAPTRA_FLAG_DEADLOCK 2
+#define ADAPTRA_FLAG_MEMCAP   4
+
+#define ADAPTRA_MAX_STAGES  64
+#define ADAPTRA_MAX_MICROBATCHES 32768
+
+/* Problem shared by all pairs (inputs of Algorithm 2 / Algorithm 4: S, N, t^F_i, t^B_i). */
+typedef struct adaptra_params {
+    int32_t S;               /* stages, 1..ADAPTRA_MAX_STAGES                              */
+    int32_t M;               /* micro-batches (the paper's N), 1..ADAPTRA_MAX_MICROBATCHES */
+    const int32_t *t_f;      /* DEVICE [S] forward time of a stage, >= 0                   */
+    const int32_t *t_b;      /* DEVICE [S] backward time of a stage, >= 0                  */
+    const int32_t *mem_cap;  /* DEVICE [S] max in-flight micro-batches (x_max); NULL = none */
+    int32_t hist_bins;       /* adaptra_best: bins per stage of the bubble histogram, 0 = off */
+    int32_t hist_shift;      /* adaptra_best: bin = min(hist_bins-1, bubble >> hist_shift), 0..30 */
+} adaptra_params_t;
+
+/* Warm-up vectors, structure of arrays: w[s * n + c] is w_s of candidate c. */
+typedef struct adaptra_candidates {
+    int64_t n;               /* 1..2^31-1 */
+    const int32_t *w;        /* DEVICE [S][n] */
+    int32_t w_bound;         /* optional promise: no w exceeds this value; -1 = unknown.
+                              * It only sizes the on-chip ring of the register/LDS kernel
+                              * (one launch instead of one per ring depth).  Candidates
+                              * that break the promise are still evaluated correctly,
+                              * by the general kernel. */
+} adaptra_candidates_t;
+
+/* Link delays, structure of arrays: c_fwd[l * n + k] is the delay of link l -> l+1 in
+ * scenario k, c_bwd[l * n + k] that of link l+1 -> l.  Both may be NULL when S == 1. */
+typedef struct adaptra_scenarios {
+    int64_t n;               /* 1..2^31-1 */
+    const int32_t *c_fwd;    /* DEVICE [S-1][n], >= 0 */
+    const int32_t *c_bwd;    /* DEVICE [S-1][n], >= 0 */
+} adaptra_scenarios_t;
+
+/* Bytes of device scratch adaptra_eval / adaptra_best / adaptra_check_inputs need for
+ * this problem size (reads only S and M of params; touches no device memory).
+ * Returns 0 if the sizes are out of range. */
+size_t adaptra_workspace_bytes(const adaptra_params_t *params, int64_t n_cand, int64_t n_scen);
+
+/* SYNCHRONOUS validation of the device data: enqueues a scan on `stream`, waits for
+ * it and returns ADAPTRA_ERANGE if any time, delay or w is negative,
+ * ADAPTRA_EOVERFLOW if 2 M S (max time + max delay) >= 2^31, else ADAPTRA_OK.
+ * Optional: the other entry points do not call it. */
+int adaptra_check_inputs(const adaptra_params_t *params, const adaptra_candidates_t *cands,
+                         const adaptra_scenarios_t *scens,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* Evaluate every pair (Section 3.1 recurrence over the Section 4.1 stage order).
+ *   out_makespan  DEVICE int32 [n_scen][n_cand]
+ *   out_bubble    DEVICE int32 [S][n_scen][n_cand], or NULL to skip
+ *   out_feasible  DEVICE uint8 [n_scen][n_cand] flag byte (see above)
+ * Asynchronous on `stream`. */
+int adaptra_eval(const adaptra_params_t *params, const adaptra_candidates_t *cands,
+                 const adaptra_scenarios_t *scens,
+                 int32_t *out_makespan, int32_t *out_bubble, uint8_t *out_feasible,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* Per-scenario search: instead of the single analytic pick of Algorithm 2, take the
+ * exact minimum of the makespan over all feasible (flag == 1) candidates, ties to the
+ * lowest candidate index.
+ *   out_best_idx       DEVICE int32 [n_scen]; -1 if no candidate is feasible
+ *   out_best_makespan  DEVICE int32 [n_scen]; INT32_MAX if none
+ *   out_best_bubble    DEVICE int32 [n_scen][S] bubbles of the winner (INT32_MAX if
+ *                      none), or NULL
+ *   out_hist           DEVICE uint64 [S][hist_bins]: per stage, how many feasible pairs
+ *                      fall into each bubble bin; required iff params->hist_bins > 0.
+ *                      It is overwritten, not accumulated.
+ * Asynchronous on `stream`. */
+int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *cands,
+                 const adaptra_scenarios_t *scens,
+                 int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
+                 uint64_t *out_hist,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* Kernel selection, process-wide; for tests and measurements.
+ *   0  automatic (default): register/LDS kernel where S and the scenario count suit
+ *      it, the general kernel otherwise
+ *   1  general kernel only (any S, M, warm-up depth)
+ *   2  register/LDS kernel wherever its limits allow, regardless of lane efficiency
+ * Returns the previous mode, or -1 for an unknown mode (nothing changes). */
+int adaptra_set_kernel_mode(int mode);
+
+/* Measurement hook, process-wide: when both are non-NULL hipEvent_t handles, adaptra_eval
+ * and adaptra_best record `before` on the stream just ahead of their resolve kernels
+ * (the max-plus recurrence) and `after` right behind them, so that a caller can time
+ * exactly those launches.  Pass NULL, NULL to switch it off.  Always returns ADAPTRA_OK. */
+int adaptra_set_resolve_events(void *before, void *after);
+
+/* hipError_t (as int) of the last failed HIP call on this thread, 0 if none. */
+int adaptra_last_hip_error(void);
+
+/* Library version, major * 1000 + minor. */
+int adaptra_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADAPTRA_H */

@@ -1,0 +1,214 @@
+"""Thin ctypes binding of libadaptra.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels.  PyTorch supplies device
+memory (tensors) and the current stream; nothing here computes.  If the library is
+missing this module raises -- there is no CPU fallback.
+
+Names and arguments mirror include/adaptra.h.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libadaptra.so")
+
+OK, EINVAL, EWORKSPACE, EHIP, ERANGE, EOVERFLOW = 0, 1, 2, 3, 4, 5
+ERROR_NAMES = {0: "ADAPTRA_OK", 1: "ADAPTRA_EINVAL", 2: "ADAPTRA_EWORKSPACE", 3: "ADAPTRA_EHIP",
+               4: "ADAPTRA_ERANGE", 5: "ADAPTRA_EOVERFLOW"}
+FLAG_FEASIBLE, FLAG_DEADLOCK, FLAG_MEMCAP = 1, 2, 4
+INT32_MAX = 2 ** 31 - 1
+
+EXPORTS = ("adaptra_workspace_bytes", "adaptra_check_inputs", "adaptra_eval", "adaptra_best",
+           "adaptra_set_kernel_mode", "adaptra_set_resolve_events", "adaptra_last_hip_error",
+           "adaptra_version")
+
+
+class AdaptraError(RuntimeError):
+    def __init__(self, code: int, where: str, hip: int = 0):
+        self.code = code
+        self.hip_error = hip
+        extra = f" (hipError_t {hip})" if code == EHIP else ""
+        super().__init__(f"{where}: {ERROR_NAMES.get(code, code)}{extra}")
+
+
+class Params(ctypes.Structure):
+    _fields_ = [("S", ctypes.c_int32), ("M", ctypes.c_int32),
+                ("t_f", ctypes.c_void_p), ("t_b", ctypes.c_void_p), ("mem_cap", ctypes.c_void_p),
+                ("hist_bins", ctypes.c_int32), ("hist_shift", ctypes.c_int32)]
+
+
+class Candidates(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int64), ("w", ctypes.c_void_p), ("w_bound", ctypes.c_int32)]
+
+
+class Scenarios(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int64), ("c_fwd", ctypes.c_void_p), ("c_bwd", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load the HIP library built in-tree; fail loudly if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2504_19232_amd.build` "
+                "(there is no CPU fallback)")
+        lib = ctypes.CDLL(LIB_PATH)
+        P, C, Sc = ctypes.POINTER(Params), ctypes.POINTER(Candidates), ctypes.POINTER(Scenarios)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        lib.adaptra_workspace_bytes.restype = sz
+        lib.adaptra_workspace_bytes.argtypes = [P, ctypes.c_int64, ctypes.c_int64]
+        lib.adaptra_check_inputs.restype = ctypes.c_int
+        lib.adaptra_check_inputs.argtypes = [P, C, Sc, vp, sz, vp]
+        lib.adaptra_eval.restype = ctypes.c_int
+        lib.adaptra_eval.argtypes = [P, C, Sc, vp, vp, vp, vp, sz, vp]
+        lib.adaptra_best.restype = ctypes.c_int
+        lib.adaptra_best.argtypes = [P, C, Sc, vp, vp, vp, vp, vp, sz, vp]
+        lib.adaptra_set_kernel_mode.restype = ctypes.c_int
+        lib.adaptra_set_kernel_mode.argtypes = [ctypes.c_int]
+        lib.adaptra_set_resolve_events.restype = ctypes.c_int
+        lib.adaptra_set_resolve_events.argtypes = [vp, vp]
+        lib.adaptra_last_hip_error.restype = ctypes.c_int
+        lib.adaptra_version.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+def _check_i32(t, name, shape=None):
+    import torch
+    if t is None:
+        return
+    if not (t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
+        raise TypeError(f"{name} must be a contiguous int32 CUDA tensor")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+
+
+class Problem:
+    """Device-resident inputs of one batch, plus the marshalled structs.
+
+    t_f, t_b, mem_cap: int32 [S]; w: int32 [S, C]; c_fwd, c_bwd: int32 [S-1, K] -- all CUDA
+    tensors, kept alive by this object."""
+
+    def __init__(self, M: int, t_f, t_b, w, c_fwd, c_bwd, mem_cap=None, hist_bins: int = 0, hist_shift: int = 0,
+                 w_bound: int = -1):
+        S = int(t_f.shape[0])
+        C = int(w.shape[1])
+        K = int(c_fwd.shape[1])
+        _check_i32(t_f, "t_f", (S,)); _check_i32(t_b, "t_b", (S,)); _check_i32(mem_cap, "mem_cap", (S,))
+        _check_i32(w, "w", (S, C)); _check_i32(c_fwd, "c_fwd", (S - 1, K)); _check_i32(c_bwd, "c_bwd", (S - 1, K))
+        self.S, self.M, self.C, self.K = S, int(M), C, K
+        self.hist_bins, self.hist_shift = int(hist_bins), int(hist_shift)
+        self.tensors = (t_f, t_b, w, c_fwd, c_bwd, mem_cap)
+        self.device = w.device
+        self.params = Params(S, int(M), _ptr(t_f), _ptr(t_b), _ptr(mem_cap), int(hist_bins), int(hist_shift))
+        self.cands = Candidates(C, _ptr(w), int(w_bound))
+        self.scens = Scenarios(K, _ptr(c_fwd) if S > 1 else None, _ptr(c_bwd) if S > 1 else None)
+
+    @classmethod
+    def from_workload(cls, wl, device="cuda:0", w_bound: int = -1):
+        import torch
+        dev = torch.device(device)
+
+        def up(a):
+            return None if a is None else torch.from_numpy(a).to(dev)
+        return cls(wl.M, up(wl.t_f), up(wl.t_b), up(wl.w), up(wl.c_fwd), up(wl.c_bwd), up(wl.mem_cap),
+                   wl.hist_bins, wl.hist_shift, w_bound)
+
+
+def adaptra_workspace_bytes(S: int, M: int, n_cand: int, n_scen: int) -> int:
+    p = Params(S, M, None, None, None, 0, 0)
+    return int(load().adaptra_workspace_bytes(ctypes.byref(p), n_cand, n_scen))
+
+
+def alloc_workspace(prob: Problem):
+    import torch
+    n = adaptra_workspace_bytes(prob.S, prob.M, prob.C, prob.K)
+    if n == 0:
+        raise AdaptraError(EINVAL, "adaptra_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=prob.device)
+
+
+def _raise(rc: int, where: str):
+    if rc != OK:
+        raise AdaptraError(rc, where, load().adaptra_last_hip_error())
+
+
+def adaptra_check_inputs(prob: Problem, workspace=None, stream=None) -> int:
+    """Returns the library's code (OK, ERANGE, EOVERFLOW ...) without raising for data findings."""
+    ws = alloc_workspace(prob) if workspace is None else workspace
+    rc = load().adaptra_check_inputs(ctypes.byref(prob.params), ctypes.byref(prob.cands), ctypes.byref(prob.scens),
+                                     ws.data_ptr(), ws.numel(), _stream(stream))
+    if rc in (EINVAL, EWORKSPACE, EHIP):
+        _raise(rc, "adaptra_check_inputs")
+    return rc
+
+
+def adaptra_eval(prob: Problem, out_makespan=None, out_bubble=None, out_feasible=None, *,
+                 want_bubble: bool = True, workspace=None, stream=None):
+    """Enqueue the evaluation of every pair; returns (makespan [K,C], bubble [S,K,C] | None, feasible [K,C])."""
+    import torch
+    dev = prob.device
+    if out_makespan is None:
+        out_makespan = torch.empty((prob.K, prob.C), dtype=torch.int32, device=dev)
+    if out_feasible is None:
+        out_feasible = torch.empty((prob.K, prob.C), dtype=torch.uint8, device=dev)
+    if out_bubble is None and want_bubble:
+        out_bubble = torch.empty((prob.S, prob.K, prob.C), dtype=torch.int32, device=dev)
+    ws = alloc_workspace(prob) if workspace is None else workspace
+    rc = load().adaptra_eval(ctypes.byref(prob.params), ctypes.byref(prob.cands), ctypes.byref(prob.scens),
+                             out_makespan.data_ptr(), _ptr(out_bubble), out_feasible.data_ptr(),
+                             ws.data_ptr(), ws.numel(), _stream(stream))
+    _raise(rc, "adaptra_eval")
+    return out_makespan, out_bubble, out_feasible
+
+
+def adaptra_best(prob: Problem, out_best_idx=None, out_best_makespan=None, out_best_bubble=None, out_hist=None, *,
+                 want_bubble: bool = True, workspace=None, stream=None):
+    """Enqueue the per-scenario search; returns (best_idx [K], best_makespan [K], best_bubble [K,S] | None,
+    hist [S,bins] | None)."""
+    import torch
+    dev = prob.device
+    if out_best_idx is None:
+        out_best_idx = torch.empty(prob.K, dtype=torch.int32, device=dev)
+    if out_best_makespan is None:
+        out_best_makespan = torch.empty(prob.K, dtype=torch.int32, device=dev)
+    if out_best_bubble is None and want_bubble:
+        out_best_bubble = torch.empty((prob.K, prob.S), dtype=torch.int32, device=dev)
+    if out_hist is None and prob.hist_bins > 0:
+        out_hist = torch.empty((prob.S, prob.hist_bins), dtype=torch.int64, device=dev)
+    ws = alloc_workspace(prob) if workspace is None else workspace
+    rc = load().adaptra_best(ctypes.byref(prob.params), ctypes.byref(prob.cands), ctypes.byref(prob.scens),
+                             out_best_idx.data_ptr(), out_best_makespan.data_ptr(), _ptr(out_best_bubble),
+                             _ptr(out_hist), ws.data_ptr(), ws.numel(), _stream(stream))
+    _raise(rc, "adaptra_best")
+    return out_best_idx, out_best_makespan, out_best_bubble, out_hist
+
+
+def adaptra_set_kernel_mode(mode: int) -> int:
+    return int(load().adaptra_set_kernel_mode(int(mode)))
+
+
+def adaptra_set_resolve_events(before: Optional[int], after: Optional[int]) -> int:
+    """before / after: raw hipEvent_t handles (ints) or None."""
+    return int(load().adaptra_set_resolve_events(before, after))
+
+
+def adaptra_version() -> int:
+    return int(load().adaptra_version())

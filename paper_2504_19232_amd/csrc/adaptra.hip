@@ -1,0 +1,764 @@
+// adaptra.hip -- gfx950 kernels and the C ABI of the batched pipeline-schedule evaluator.
+//
+// Model and notation follow the Adaptra paper: S stages, M micro-batches, w[s] warm-up
+// forwards of stage s (the paper's x_s = w[s] + 1), link delays c_fwd / c_bwd, the
+// dependency rules of Section 3.1 and the stage order of Sections 4.1 / 4.3.  Everything
+// is int32 microseconds; there is no floating point on this path.
+//
+// Kernels
+//   k_prepass            per candidate: clamp w, Lemma 1 test (deadlock), memory-cap test
+//                        (Algorithm 1's x_max), flag byte, ring-depth class, packed w bytes
+//   k_resolve_scen_lanes the hot kernel: one wavefront = one candidate at a time x 64
+//                        scenarios (one per lane); stage frontiers in VGPRs, the forward
+//                        frontier of the in-flight micro-batches in an LDS ring
+//   k_resolve_general    any S / M / warm-up depth: one lane per pair (64 candidates of one
+//                        scenario per wavefront), state in global scratch, DPP argmin
+//   k_fill_eval          feasibility byte for every pair, sentinels for deadlocked pairs
+//   k_best_init / k_best_finalize   search keys and histogram set-up / decoding
+//   k_check_inputs       range scan for adaptra_check_inputs
+//
+// Order of evaluation used by both resolve kernels: with w non-increasing over stages
+// (Lemma 1) the rounds r = -w[0] .. M-1, each a forward sweep s = 0..S-1 over
+// F(s, w[s] + r) followed (r >= 0) by a backward sweep s = S-1..0 over B(s, r), visit every
+// op after all of its predecessors and every stage's ops in that stage's own order.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "adaptra.h"
+
+namespace {
+
+constexpr int kNeg = -(1 << 30);          // "no earlier op": below every shifted time
+constexpr int kChunk = 16;                // candidates one wavefront works through
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlock = 64 * kWavesPerBlock;
+constexpr int kClassDead = 255;           // deadlocked: never resolved
+constexpr int kClassDeep = 254;           // warm-up depth beyond the LDS ring: general kernel
+constexpr int kNumRingClasses = 8;        // ring of 8 * (class + 1) slots
+constexpr int kMaxLdsHistBytes = 16384;
+constexpr unsigned long long kNoKey = ~0ull;
+
+struct KArgs {
+    int S, M;
+    const int *t_f, *t_b, *mem_cap;
+    long long C, K;
+    const int *w, *cf, *cb;
+    unsigned char *cand_flag, *cand_class, *cand_wq;
+    int wq_stride;                         // bytes per candidate in cand_wq
+    int *out_makespan, *out_bubble;
+    unsigned char *out_feasible;
+    unsigned long long *keys, *hist;
+    int *best_idx, *best_makespan, *best_bubble;
+    int hist_bins, hist_shift, hist_in_lds;
+    int *scratch;
+    int cls_lo, cls_hi, ring_slots, general_all;
+    long long n_chunks;
+    int n_ktiles;
+    int *status;
+};
+
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ int imax(int a, int b) { return a > b ? a : b; }
+__device__ __forceinline__ int clampw(int w, int M) { return w < 0 ? 0 : (w > M - 1 ? M - 1 : w); }
+
+// ---------------------------------------------------------------------------------------
+// Wavefront-wide minimum of a 64-bit key: DPP butterflies inside each row of 16 lanes,
+// ds_swizzle across the two rows of a half, v_readlane across the halves.
+template <int kCtrl>
+__device__ __forceinline__ unsigned long long dpp_min_step(unsigned long long v) {
+    unsigned lo = (unsigned)v, hi = (unsigned)(v >> 32);
+    unsigned olo = (unsigned)__builtin_amdgcn_update_dpp((int)lo, (int)lo, kCtrl, 0xf, 0xf, false);
+    unsigned ohi = (unsigned)__builtin_amdgcn_update_dpp((int)hi, (int)hi, kCtrl, 0xf, 0xf, false);
+    unsigned long long o = ((unsigned long long)ohi << 32) | olo;
+    return o < v ? o : v;
+}
+
+__device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v) {
+    v = dpp_min_step<0xB1>(v);    // quad_perm [1,0,3,2]: lane ^ 1
+    v = dpp_min_step<0x4E>(v);    // quad_perm [2,3,0,1]: lane ^ 2
+    v = dpp_min_step<0x141>(v);   // row_half_mirror: joins the two quads of 8 lanes
+    v = dpp_min_step<0x140>(v);   // row_mirror: joins the two halves of a row
+    {
+        unsigned lo = (unsigned)v, hi = (unsigned)(v >> 32);
+        unsigned olo = (unsigned)__builtin_amdgcn_ds_swizzle((int)lo, 0x401F);   // lane ^ 16
+        unsigned ohi = (unsigned)__builtin_amdgcn_ds_swizzle((int)hi, 0x401F);
+        unsigned long long o = ((unsigned long long)ohi << 32) | olo;
+        v = o < v ? o : v;
+    }
+    unsigned long long a = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(v >> 32), 0) << 32) |
+                           (unsigned)__builtin_amdgcn_readlane((int)v, 0);
+    unsigned long long b = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(v >> 32), 32) << 32) |
+                           (unsigned)__builtin_amdgcn_readlane((int)v, 32);
+    return a < b ? a : b;
+}
+
+// ---------------------------------------------------------------------------------------
+// Per candidate, independent of the scenario: w' = clamp(w, 0, M-1); deadlock iff some
+// w'[s] < w'[s+1] (Lemma 1); memory cap exceeded iff some w'[s] + 1 > mem_cap[s]
+// (Algorithm 1, x_max).  Also packs w' into bytes for the hot kernel and bins the
+// candidate by the ring depth it needs, w'[0] + 1 slots.
+__global__ __launch_bounds__(kBlock) void k_prepass(KArgs a) {
+    long long c = (long long)blockIdx.x * kBlock + threadIdx.x;
+    if (c >= a.C) return;
+    const int S = a.S, M = a.M;
+    bool dead = false, mem = false;
+    int prev = clampw(a.w[c], M);
+    const int w0 = prev;
+    if (a.mem_cap && prev + 1 > a.mem_cap[0]) mem = true;
+    for (int s = 1; s < S; ++s) {
+        int ws = clampw(a.w[(long long)s * a.C + c], M);
+        if (prev < ws) dead = true;
+        if (a.mem_cap && ws + 1 > a.mem_cap[s]) mem = true;
+        prev = ws;
+    }
+    int flag = (dead ? ADAPTRA_FLAG_DEADLOCK : 0) | (mem ? ADAPTRA_FLAG_MEMCAP : 0);
+    if (flag == 0) flag = ADAPTRA_FLAG_FEASIBLE;
+    int cls;
+    if (dead) cls = kClassDead;
+    else if (w0 + 1 > 8 * kNumRingClasses) cls = kClassDeep;
+    else cls = (w0 + 8) / 8 - 1;            // ring of 8 * (cls + 1) >= w0 + 1 slots
+    a.cand_flag[c] = (unsigned char)flag;
+    a.cand_class[c] = (unsigned char)cls;
+    if (cls < kNumRingClasses) {
+        unsigned char *q = a.cand_wq + c * a.wq_stride;
+        for (int s = 0; s < S; ++s) q[s] = (unsigned char)clampw(a.w[(long long)s * a.C + c], M);
+    }
+}
+
+// Flag byte for every pair; INT32_MAX for the makespan and bubbles of deadlocked pairs.
+__global__ __launch_bounds__(kBlock) void k_fill_eval(KArgs a) {
+    const long long P = a.C * a.K;
+    const long long stride = (long long)gridDim.x * kBlock;
+    for (long long p = (long long)blockIdx.x * kBlock + threadIdx.x; p < P; p += stride) {
+        const long long c = p % a.C;
+        const int flag = a.cand_flag[c];
+        a.out_feasible[p] = (unsigned char)flag;
+        if (flag & ADAPTRA_FLAG_DEADLOCK) {
+            a.out_makespan[p] = INT32_MAX;
+            if (a.out_bubble)
+                for (int s = 0; s < a.S; ++s) a.out_bubble[(long long)s * P + p] = INT32_MAX;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_best_init(KArgs a) {
+    const long long n = a.K + (a.hist ? (long long)a.S * a.hist_bins : 0);
+    const long long stride = (long long)gridDim.x * kBlock;
+    for (long long i = (long long)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) {
+        if (i < a.K) a.keys[i] = kNoKey;
+        else a.hist[i - a.K] = 0ull;
+    }
+}
+
+// key = makespan << 32 | candidate: the minimum key is the smallest makespan, ties to the
+// lowest index.  Bubbles of the winner: makespan - M (t_f + t_b) per stage.
+__global__ __launch_bounds__(kBlock) void k_best_finalize(KArgs a) {
+    const long long k = (long long)blockIdx.x * kBlock + threadIdx.x;
+    if (k >= a.K) return;
+    const unsigned long long key = a.keys[k];
+    const bool none = key == kNoKey;
+    const int mk = none ? INT32_MAX : (int)(key >> 32);
+    a.best_idx[k] = none ? -1 : (int)(unsigned)key;
+    a.best_makespan[k] = mk;
+    if (a.best_bubble)
+        for (int s = 0; s < a.S; ++s)
+            a.best_bubble[k * a.S + s] = none ? INT32_MAX : mk - a.M * (a.t_f[s] + a.t_b[s]);
+}
+
+// ---------------------------------------------------------------------------------------
+// General kernel: one lane per pair, 64 consecutive candidates of one scenario per
+// wavefront.  Plain form of the Section 3.1 recurrence:
+//   start F(s,m) = max(last[s], fin F(s-1,m) + c_fwd[s-1]),  fin = start + t_f[s]
+//   start B(s,m) = max(last[s], fin B(s+1,m) + c_bwd[s]),    fin = start + t_b[s]
+// State per lane in global scratch, laid out [index][thread] so that lanes coalesce:
+//   last[S], w'[S], fwd[M] (finish time of micro-batch m's latest forward).
+template <bool BEST>
+__global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
+    const int S = a.S, M = a.M;
+    const long long NT = (long long)gridDim.x * kBlock;
+    const long long tid = (long long)blockIdx.x * kBlock + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    int *last = a.scratch + tid;
+    int *wl = a.scratch + (long long)S * NT + tid;
+    int *fwd = a.scratch + 2ll * S * NT + tid;
+    const long long ctiles = (a.C + 63) / 64;
+    const long long ntiles = a.K * ctiles;
+    const long long nwaves = NT >> 6;
+    for (long long tile = tid >> 6; tile < ntiles; tile += nwaves) {
+        const long long k = tile / ctiles;
+        const long long c = (tile % ctiles) * 64 + lane;
+        bool run = false;
+        if (c < a.C) {
+            const int flag = a.cand_flag[c];
+            const int cls = a.cand_class[c];
+            run = BEST ? (flag == ADAPTRA_FLAG_FEASIBLE) : !(flag & ADAPTRA_FLAG_DEADLOCK);
+            if (!a.general_all && cls <= a.cls_hi) run = false;   // the register/LDS kernel's share
+        }
+        unsigned long long key = kNoKey;
+        if (run) {
+            for (int s = 0; s < S; ++s) {
+                wl[s * NT] = clampw(a.w[(long long)s * a.C + c], M);
+                last[s * NT] = 0;
+            }
+            const int w0 = wl[0];
+            for (int r = -w0; r < M; ++r) {
+                for (int s = 0; s < S; ++s) {                    // forward sweep
+                    const int m = wl[s * NT] + r;
+                    if (m >= 0 && m < M) {
+                        const int arrive = s == 0 ? 0 : fwd[m * NT] + a.cf[(long long)(s - 1) * a.K + k];
+                        const int fin = imax(last[s * NT], arrive) + a.t_f[s];
+                        last[s * NT] = fin;
+                        fwd[m * NT] = fin;
+                    }
+                }
+                if (r >= 0) {                                    // backward sweep
+                    int carry = 0;
+                    for (int s = S - 1; s >= 0; --s) {
+                        const int arrive = s == S - 1 ? 0 : carry + a.cb[(long long)s * a.K + k];
+                        const int fin = imax(last[s * NT], arrive) + a.t_b[s];
+                        last[s * NT] = fin;
+                        carry = fin;
+                    }
+                }
+            }
+            int mk = 0;
+            for (int s = 0; s < S; ++s) mk = imax(mk, last[s * NT]);
+            if (BEST) {
+                key = ((unsigned long long)(unsigned)mk << 32) | (unsigned)c;
+                if (a.hist) {
+                    for (int s = 0; s < S; ++s) {
+                        int b = (mk - M * (a.t_f[s] + a.t_b[s])) >> a.hist_shift;
+                        b = b > a.hist_bins - 1 ? a.hist_bins - 1 : b;
+                        atomicAdd(&a.hist[s * a.hist_bins + b], 1ull);
+                    }
+                }
+            } else {
+                const long long P = a.C * a.K;
+                const long long p = k * a.C + c;
+                a.out_makespan[p] = mk;
+                if (a.out_bubble)
+                    for (int s = 0; s < S; ++s)
+                        a.out_bubble[(long long)s * P + p] = mk - M * (a.t_f[s] + a.t_b[s]);
+            }
+        }
+        if (BEST) {
+            key = wave_min_u64(key);
+            if (lane == 0 && key != kNoKey) atomicMin(&a.keys[k], key);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Hot kernel: lane = scenario, the candidate (hence the whole op order, every ring index
+// and every branch) is uniform across the wavefront and lives in SGPRs.
+//
+// Shifted times.  Let a[s] = sum_{j<=s} t_f[j] + sum_{l<s} c_fwd[l], the earliest possible
+// finish of F(s,0).  Each stage keeps one register
+//     L[s] = (finish of its last forward, or start of its last backward) - a[s].
+// In these coordinates the dependency rules of Section 3.1 become
+//     forward  after a forward :  L[s] = max(L[s] + t_f[s],           R[m])
+//     forward  after a backward:  L[s] = max(L[s] + t_f[s] + t_b[s],  R[m])
+//     backward after a forward :  L[s] = max(L[s],                    carry + q[s])
+//     backward after a backward:  L[s] = max(L[s] + t_b[s],           carry + q[s])
+// with R[m] the shifted finish of micro-batch m's forward on stage s-1 (read from, and
+// written back to, LDS slot m mod D), carry = L[s+1] after its backward, and
+//     q[s] = c_fwd[s] + c_bwd[s] + t_f[s+1] + t_b[s+1]      (one VGPR per link and lane).
+// Forward delays and forward durations are folded into a[s], backward durations into the
+// next op's addend, so the steady state costs two integer VALU ops per resolved op.
+// At the end  makespan = finish of B(0, M-1) = L[0] + t_f[0] + t_b[0].
+//
+// LDS ring: at round r the forwards in flight between stages are micro-batches
+// w[S-1] + r < m <= w[0] + r, one value each, so D >= w[0] + 1 slots of 64 lanes suffice;
+// slot-major layout [slot][lane] keeps every access conflict-free.
+template <int S, bool BEST>
+__global__ __launch_bounds__(kBlock) void k_resolve_scen_lanes(KArgs a) {
+    extern __shared__ int lds[];
+    const int lane = threadIdx.x & 63;
+    const int wv = uni(threadIdx.x >> 6);
+    const int M = a.M;
+    const int ring_bytes = a.ring_slots * 256;
+    char *const ring = (char *)lds + wv * ring_bytes + lane * 4;
+    unsigned *const hist_lds = (unsigned *)((char *)lds + kWavesPerBlock * ring_bytes);
+    const bool lds_hist = BEST && a.hist && a.hist_in_lds;
+    if (lds_hist) {
+        for (int i = threadIdx.x; i < S * a.hist_bins; i += kBlock) hist_lds[i] = 0;
+        __syncthreads();
+    }
+
+    const long long task = (long long)blockIdx.x * kWavesPerBlock + wv;
+    const int tile = (int)(task % a.n_ktiles);
+    const long long c0 = (task / a.n_ktiles) * kChunk;
+    if (c0 < a.C) {
+        const long long k = (long long)tile * 64 + lane;
+        const bool kvalid = k < a.K;
+        const long long kk = kvalid ? k : a.K - 1;
+        int tf[S], tb[S], tau[S];
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            tf[s] = uni(a.t_f[s]);
+            tb[s] = uni(a.t_b[s]);
+            tau[s] = tf[s] + tb[s];
+        }
+        int q[S > 1 ? S - 1 : 1];
+#pragma unroll
+        for (int s = 0; s + 1 < S; ++s) q[s] = a.cf[s * a.K + kk] + a.cb[s * a.K + kk] + tau[s + 1];
+
+        unsigned long long key = kNoKey;
+        const int c_end = (int)((a.C - c0 < kChunk) ? (a.C - c0) : kChunk);
+        for (int ci = 0; ci < c_end; ++ci) {
+            const long long c = c0 + ci;
+            const int cls = uni(a.cand_class[c]);
+            if (cls < a.cls_lo || cls > a.cls_hi) continue;
+            if (BEST && uni(a.cand_flag[c]) != ADAPTRA_FLAG_FEASIBLE) continue;
+            int wq[S];
+            {
+                const unsigned *p = (const unsigned *)(a.cand_wq + c * a.wq_stride);
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    const unsigned word = (unsigned)uni((int)p[s >> 2]);
+                    wq[s] = (int)((word >> (8 * (s & 3))) & 0xffu);
+                }
+            }
+            const int W = wq[0];
+            int L[S], soff[S];
+            L[0] = -tf[0];
+#pragma unroll
+            for (int s = 1; s < S; ++s) L[s] = kNeg;
+#pragma unroll
+            for (int s = 0; s < S; ++s) {         // slot of micro-batch wq[s] - W (<= 0), mod D
+                int m0 = wq[s] - W + a.ring_slots;
+                if (m0 >= a.ring_slots) m0 -= a.ring_slots;
+                soff[s] = m0 * 256;
+            }
+
+#define ADAPTRA_F_OP(s, e)                                              \
+    do {                                                                \
+        int *slot = (int *)(ring + soff[s]);                            \
+        if ((s) == 0) {                                                 \
+            L[0] += (e);                                                \
+            if (S > 1) *slot = L[0];                                    \
+        } else {                                                        \
+            const int x = *slot;                                        \
+            L[s] = imax(L[s] + (e), x);                                 \
+            if ((s) < S - 1) *slot = L[s];                              \
+        }                                                               \
+    } while (0)
+#define ADAPTRA_ADVANCE(s)                                              \
+    do {                                                                \
+        soff[s] += 256;                                                 \
+        if (soff[s] == ring_bytes) soff[s] = 0;                         \
+    } while (0)
+
+            // warm-up rounds r = -W .. 0: forwards only, each after a forward
+            for (int r = -W; r <= 0; ++r) {
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    if (wq[s] + r >= 0) ADAPTRA_F_OP(s, tf[s]);
+                    ADAPTRA_ADVANCE(s);
+                }
+            }
+            {   // B(s, 0): each after a forward
+                int carry = L[S - 1];
+#pragma unroll
+                for (int s = S - 2; s >= 0; --s) {
+                    L[s] = imax(L[s], carry + q[s]);
+                    carry = L[s];
+                }
+            }
+            // steady rounds r = 1 .. M-1-W: F after B, B after F on every stage
+            const int r_steady_end = M - 1 - W;
+            for (int r = 1; r <= r_steady_end; ++r) {
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    ADAPTRA_F_OP(s, tau[s]);
+                    ADAPTRA_ADVANCE(s);
+                }
+                int carry = L[S - 1];
+#pragma unroll
+                for (int s = S - 2; s >= 0; --s) {
+                    L[s] = imax(L[s], carry + q[s]);
+                    carry = L[s];
+                }
+            }
+            // cool-down rounds r = M-W .. M-1: stages run out of forwards one by one
+            for (int r = M - W; r <= M - 1; ++r) {
+                int carry = 0;
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    if (wq[s] + r <= M - 1) ADAPTRA_F_OP(s, tau[s]);
+                    ADAPTRA_ADVANCE(s);
+                }
+#pragma unroll
+                for (int s = S - 1; s >= 0; --s) {
+                    const bool had_f = wq[s] + r <= M - 1;
+                    const int prev = had_f ? L[s] : L[s] + tb[s];
+                    L[s] = (s == S - 1) ? prev : imax(prev, carry + q[s]);
+                    carry = L[s];
+                }
+            }
+#undef ADAPTRA_F_OP
+#undef ADAPTRA_ADVANCE
+
+            const int mk = L[0] + tf[0] + tb[0];
+            if (BEST) {
+                if (kvalid) {
+                    const unsigned long long cand = ((unsigned long long)(unsigned)mk << 32) | (unsigned)c;
+                    key = cand < key ? cand : key;
+                    if (a.hist) {
+#pragma unroll
+                        for (int s = 0; s < S; ++s) {
+                            int b = (mk - M * tau[s]) >> a.hist_shift;
+                            b = b > a.hist_bins - 1 ? a.hist_bins - 1 : b;
+                            if (lds_hist) atomicAdd(&hist_lds[s * a.hist_bins + b], 1u);
+                            else atomicAdd(&a.hist[s * a.hist_bins + b], 1ull);
+                        }
+                    }
+                }
+            } else if (kvalid) {
+                const long long P = a.C * a.K;
+                const long long p = k * a.C + c;
+                a.out_makespan[p] = mk;
+                if (a.out_bubble) {
+#pragma unroll
+                    for (int s = 0; s < S; ++s) a.out_bubble[(long long)s * P + p] = mk - M * tau[s];
+                }
+            }
+        }
+        if (BEST && kvalid && key != kNoKey) atomicMin(&a.keys[k], key);
+    }
+    if (lds_hist) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < S * a.hist_bins; i += kBlock) {
+            const unsigned n = hist_lds[i];
+            if (n) atomicAdd(&a.hist[i], (unsigned long long)n);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// status[0] = number of negative entries, status[1] = max time, status[2] = max delay
+__global__ __launch_bounds__(kBlock) void k_check_inputs(KArgs a) {
+    const long long nw = (long long)a.S * a.C;
+    const long long nc = (long long)(a.S - 1) * a.K;
+    const long long n = nw + 2 * nc + 2 * a.S;
+    const long long stride = (long long)gridDim.x * kBlock;
+    int neg = 0, maxt = 0, maxc = 0;
+    for (long long i = (long long)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) {
+        if (i < nw) {
+            neg += a.w[i] < 0;
+        } else if (i < nw + nc) {
+            const int v = a.cf[i - nw];
+            neg += v < 0;
+            maxc = imax(maxc, v);
+        } else if (i < nw + 2 * nc) {
+            const int v = a.cb[i - nw - nc];
+            neg += v < 0;
+            maxc = imax(maxc, v);
+        } else {
+            const long long j = i - nw - 2 * nc;
+            const int v = j < a.S ? a.t_f[j] : a.t_b[j - a.S];
+            neg += v < 0;
+            maxt = imax(maxt, v);
+        }
+    }
+    if (neg) atomicAdd(&a.status[0], neg);
+    if (maxt) atomicMax(&a.status[1], maxt);
+    if (maxc) atomicMax(&a.status[2], maxc);
+}
+
+__global__ void k_zero_status(KArgs a) {
+    if (threadIdx.x < 4) a.status[threadIdx.x] = 0;
+}
+
+// ---------------------------------------------------------------------------------------
+// Host side
+thread_local int g_last_hip_error = 0;
+int g_kernel_mode = 0;
+hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Workspace {
+    size_t off_flag, off_class, off_wq, off_keys, off_status, off_scratch, total;
+    int wq_stride;
+    long long general_threads;
+};
+
+// The general kernel keeps (2 S + M) ints per thread in scratch; bound the scratch to
+// about 256 MiB by limiting the number of resident threads.
+long long general_thread_count(int S, int M) {
+    const long long per_thread = (2ll * S + M) * 4;
+    long long nt = (256ll << 20) / per_thread;
+    if (nt > 65536) nt = 65536;
+    if (nt < 4096) nt = 4096;
+    return nt / kBlock * kBlock;
+}
+
+bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws) {
+    if (S < 1 || S > ADAPTRA_MAX_STAGES || M < 1 || M > ADAPTRA_MAX_MICROBATCHES) return false;
+    if (C < 1 || C > INT32_MAX || K < 1 || K > INT32_MAX) return false;
+    ws->wq_stride = (S + 3) & ~3;
+    ws->general_threads = general_thread_count(S, M);
+    size_t o = 0;
+    ws->off_flag = o;    o += align256((size_t)C);
+    ws->off_class = o;   o += align256((size_t)C);
+    ws->off_wq = o;      o += align256((size_t)C * ws->wq_stride);
+    ws->off_keys = o;    o += align256((size_t)K * 8);
+    ws->off_status = o;  o += 256;
+    ws->off_scratch = o; o += align256((size_t)ws->general_threads * (2 * S + M) * 4);
+    ws->total = o;
+    return true;
+}
+
+bool fast_kernel_supports(int S) { return S == 2 || S == 4 || S == 8 || S == 16 || S == 32; }
+
+// The hot kernel puts scenarios on lanes: use it when at least half of the lanes of the
+// last scenario tile carry work, or when asked to.
+bool use_fast(int S, long long K) {
+    if (g_kernel_mode == 1 || !fast_kernel_supports(S)) return false;
+    if (g_kernel_mode == 2) return true;
+    const long long tiles = (K + 63) / 64;
+    return K * 2 >= tiles * 64;
+}
+
+int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return ADAPTRA_EHIP;
+}
+
+#define ADAPTRA_LAUNCH_CHECK()                          \
+    do {                                                \
+        hipError_t e_ = hipGetLastError();              \
+        if (e_ != hipSuccess) return hip_fail(e_);      \
+    } while (0)
+
+int grid_for(long long n, long long cap = 1 << 20) {
+    long long g = (n + kBlock - 1) / kBlock;
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return (int)g;
+}
+
+int validate_common(const adaptra_params_t *p, const adaptra_candidates_t *cd,
+                    const adaptra_scenarios_t *sc, void *workspace, size_t workspace_bytes,
+                    Workspace *ws) {
+    if (!p || !cd || !sc) return ADAPTRA_EINVAL;
+    if (!plan_workspace(p->S, p->M, cd->n, sc->n, ws)) return ADAPTRA_EINVAL;
+    if (!p->t_f || !p->t_b || !cd->w) return ADAPTRA_EINVAL;
+    if (p->S > 1 && (!sc->c_fwd || !sc->c_bwd)) return ADAPTRA_EINVAL;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws->total) return ADAPTRA_EWORKSPACE;
+    return ADAPTRA_OK;
+}
+
+void fill_args(KArgs *a, const adaptra_params_t *p, const adaptra_candidates_t *cd,
+               const adaptra_scenarios_t *sc, void *workspace, const Workspace &ws) {
+    *a = KArgs{};
+    a->S = p->S; a->M = p->M;
+    a->t_f = p->t_f; a->t_b = p->t_b; a->mem_cap = p->mem_cap;
+    a->C = cd->n; a->K = sc->n;
+    a->w = cd->w; a->cf = sc->c_fwd; a->cb = sc->c_bwd;
+    char *base = (char *)workspace;
+    a->cand_flag = (unsigned char *)(base + ws.off_flag);
+    a->cand_class = (unsigned char *)(base + ws.off_class);
+    a->cand_wq = (unsigned char *)(base + ws.off_wq);
+    a->wq_stride = ws.wq_stride;
+    a->keys = (unsigned long long *)(base + ws.off_keys);
+    a->status = (int *)(base + ws.off_status);
+    a->scratch = (int *)(base + ws.off_scratch);
+    a->n_ktiles = (int)((sc->n + 63) / 64);
+    a->n_chunks = (cd->n + kChunk - 1) / kChunk;
+}
+
+template <int S, bool BEST>
+int launch_fast_one(KArgs a, int w_bound, hipStream_t st) {
+    const long long tasks = a.n_chunks * a.n_ktiles;
+    const long long blocks = (tasks + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks > INT32_MAX) return ADAPTRA_EINVAL;
+    // With a bound on w one launch covers every ring class up to the bound's; without,
+    // one launch per class, each with the smallest ring that fits its candidates.
+    int first = 0, last = kNumRingClasses - 1;
+    bool single = false;
+    if (w_bound >= 0) {
+        int wb = w_bound > a.M - 1 ? a.M - 1 : w_bound;
+        last = (wb + 8) / 8 - 1;
+        if (last > kNumRingClasses - 1) last = kNumRingClasses - 1;
+        single = true;
+    }
+    for (int cls = single ? last : first; cls <= last; ++cls) {
+        a.cls_lo = single ? 0 : cls;
+        a.cls_hi = cls;
+        a.ring_slots = 8 * (cls + 1);
+        size_t lds = (size_t)kWavesPerBlock * a.ring_slots * 256;
+        if (BEST && a.hist && a.hist_in_lds) lds += (size_t)S * a.hist_bins * 4;
+        if (lds > 48 * 1024) {      // above the default dynamic-LDS limit: raise it for this kernel
+            hipError_t e = hipFuncSetAttribute((const void *)k_resolve_scen_lanes<S, BEST>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        hipLaunchKernelGGL((k_resolve_scen_lanes<S, BEST>), dim3((unsigned)blocks), dim3(kBlock), lds, st, a);
+        ADAPTRA_LAUNCH_CHECK();
+    }
+    return ADAPTRA_OK;
+}
+
+template <bool BEST>
+int launch_fast(const KArgs &a, int w_bound, hipStream_t st) {
+    switch (a.S) {
+        case 2: return launch_fast_one<2, BEST>(a, w_bound, st);
+        case 4: return launch_fast_one<4, BEST>(a, w_bound, st);
+        case 8: return launch_fast_one<8, BEST>(a, w_bound, st);
+        case 16: return launch_fast_one<16, BEST>(a, w_bound, st);
+        case 32: return launch_fast_one<32, BEST>(a, w_bound, st);
+        default: return ADAPTRA_EINVAL;
+    }
+}
+
+template <bool BEST>
+int launch_general(KArgs a, const Workspace &ws, bool all, hipStream_t st) {
+    a.general_all = all ? 1 : 0;
+    const long long ntiles = a.K * ((a.C + 63) / 64);
+    long long threads = ntiles * 64;
+    if (threads > ws.general_threads) threads = ws.general_threads;
+    const int blocks = (int)((threads + kBlock - 1) / kBlock);
+    hipLaunchKernelGGL((k_resolve_general<BEST>), dim3(blocks), dim3(kBlock), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    return ADAPTRA_OK;
+}
+
+int record_event(hipEvent_t ev, hipStream_t st) {
+    if (!g_ev_before || !g_ev_after) return ADAPTRA_OK;
+    hipError_t e = hipEventRecord(ev, st);
+    return e == hipSuccess ? ADAPTRA_OK : hip_fail(e);
+}
+
+// The measurement events bracket the kernel that carries the load: the register/LDS
+// kernel when it is in use, else the general kernel.
+template <bool BEST>
+int launch_resolve(KArgs a, const Workspace &ws, int w_bound, hipStream_t st) {
+    int rc;
+    if (use_fast(a.S, a.K)) {
+        a.cls_hi = kNumRingClasses - 1;
+        if (w_bound >= 0) {
+            const int wb = w_bound > a.M - 1 ? a.M - 1 : w_bound;
+            const int hi = (wb + 8) / 8 - 1;
+            if (hi < a.cls_hi) a.cls_hi = hi;
+        }
+        const int general_from = a.cls_hi;               // classes above it go to the general kernel
+        if ((rc = record_event(g_ev_before, st))) return rc;
+        if ((rc = launch_fast<BEST>(a, w_bound, st))) return rc;
+        if ((rc = record_event(g_ev_after, st))) return rc;
+        a.cls_hi = general_from;
+        return launch_general<BEST>(a, ws, false, st);   // too deep for the ring, or beyond w_bound
+    }
+    if ((rc = record_event(g_ev_before, st))) return rc;
+    if ((rc = launch_general<BEST>(a, ws, true, st))) return rc;
+    return record_event(g_ev_after, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t adaptra_workspace_bytes(const adaptra_params_t *params, int64_t n_cand, int64_t n_scen) {
+    Workspace ws;
+    if (!params || !plan_workspace(params->S, params->M, n_cand, n_scen, &ws)) return 0;
+    return ws.total;
+}
+
+int adaptra_check_inputs(const adaptra_params_t *params, const adaptra_candidates_t *cands,
+                         const adaptra_scenarios_t *scens,
+                         void *workspace, size_t workspace_bytes, void *stream) {
+    Workspace ws;
+    int rc = validate_common(params, cands, scens, workspace, workspace_bytes, &ws);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    KArgs a;
+    fill_args(&a, params, cands, scens, workspace, ws);
+    hipLaunchKernelGGL(k_zero_status, dim3(1), dim3(64), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    const long long n = (long long)a.S * a.C + 2ll * (a.S - 1) * a.K + 2 * a.S;
+    hipLaunchKernelGGL(k_check_inputs, dim3(grid_for(n, 4096)), dim3(kBlock), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    int status[4] = {0, 0, 0, 0};
+    hipError_t e = hipMemcpyAsync(status, a.status, sizeof(status), hipMemcpyDeviceToHost, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return hip_fail(e);
+    if (status[0] != 0) return ADAPTRA_ERANGE;
+    const long long bound = 2ll * a.M * a.S * ((long long)status[1] + (long long)status[2]);
+    if (bound >= (1ll << 31)) return ADAPTRA_EOVERFLOW;
+    return ADAPTRA_OK;
+}
+
+int adaptra_eval(const adaptra_params_t *params, const adaptra_candidates_t *cands,
+                 const adaptra_scenarios_t *scens,
+                 int32_t *out_makespan, int32_t *out_bubble, uint8_t *out_feasible,
+                 void *workspace, size_t workspace_bytes, void *stream) {
+    Workspace ws;
+    int rc = validate_common(params, cands, scens, workspace, workspace_bytes, &ws);
+    if (rc) return rc;
+    if (!out_makespan || !out_feasible) return ADAPTRA_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    KArgs a;
+    fill_args(&a, params, cands, scens, workspace, ws);
+    a.out_makespan = out_makespan;
+    a.out_bubble = out_bubble;
+    a.out_feasible = out_feasible;
+    hipLaunchKernelGGL(k_prepass, dim3(grid_for(a.C, INT32_MAX)), dim3(kBlock), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_fill_eval, dim3(grid_for(a.C * a.K, 1 << 16)), dim3(kBlock), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    return launch_resolve<false>(a, ws, cands->w_bound, st);
+}
+
+int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *cands,
+                 const adaptra_scenarios_t *scens,
+                 int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
+                 uint64_t *out_hist,
+                 void *workspace, size_t workspace_bytes, void *stream) {
+    Workspace ws;
+    int rc = validate_common(params, cands, scens, workspace, workspace_bytes, &ws);
+    if (rc) return rc;
+    if (!out_best_idx || !out_best_makespan) return ADAPTRA_EINVAL;
+    if (params->hist_bins < 0 || params->hist_bins > 65536) return ADAPTRA_EINVAL;
+    if (params->hist_bins > 0 && (!out_hist || params->hist_shift < 0 || params->hist_shift > 30))
+        return ADAPTRA_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    KArgs a;
+    fill_args(&a, params, cands, scens, workspace, ws);
+    a.best_idx = out_best_idx;
+    a.best_makespan = out_best_makespan;
+    a.best_bubble = out_best_bubble;
+    a.hist = params->hist_bins > 0 ? (unsigned long long *)out_hist : nullptr;
+    a.hist_bins = params->hist_bins;
+    a.hist_shift = params->hist_shift;
+    a.hist_in_lds = (size_t)a.S * a.hist_bins * 4 <= (size_t)kMaxLdsHistBytes;
+    hipLaunchKernelGGL(k_prepass, dim3(grid_for(a.C, INT32_MAX)), dim3(kBlock), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_best_init, dim3(grid_for(a.K + (long long)a.S * a.hist_bins, 4096)), dim3(kBlock), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    rc = launch_resolve<true>(a, ws, cands->w_bound, st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_best_finalize, dim3(grid_for(a.K, INT32_MAX)), dim3(kBlock), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    return ADAPTRA_OK;
+}
+
+int adaptra_set_kernel_mode(int mode) {
+    if (mode < 0 || mode > 2) return -1;
+    const int prev = g_kernel_mode;
+    g_kernel_mode = mode;
+    return prev;
+}
+
+int adaptra_set_resolve_events(void *before, void *after) {
+    g_ev_before = (hipEvent_t)before;
+    g_ev_after = (hipEvent_t)after;
+    return ADAPTRA_OK;
+}
+
+int adaptra_last_hip_error(void) { return g_last_hip_error; }
+
+int adaptra_version(void) { return 1; }
+
+}  // extern "C"

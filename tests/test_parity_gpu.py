@@ -1,0 +1,283 @@
+"""GPU parity: the HIP library, called through its C ABI (ctypes), against the CPU oracle
+on the same seeded inputs.  All values are integers, so the bar is bit-exact."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2504_19232_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+INT32_MAX = 2 ** 31 - 1
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2504_19232_amd import binding
+    binding.load()
+    yield binding
+    binding.adaptra_set_kernel_mode(0)
+
+
+def gpu_eval(binding, wl, mode=0, want_bubble=True):
+    import torch
+    binding.adaptra_set_kernel_mode(mode)
+    prob = binding.Problem.from_workload(wl)
+    mk, bub, fl = binding.adaptra_eval(prob, want_bubble=want_bubble)
+    torch.cuda.synchronize()
+    binding.adaptra_set_kernel_mode(0)
+    return mk.cpu().numpy(), None if bub is None else bub.cpu().numpy(), fl.cpu().numpy()
+
+
+def gpu_best(binding, wl, mode=0):
+    import torch
+    binding.adaptra_set_kernel_mode(mode)
+    prob = binding.Problem.from_workload(wl)
+    idx, mk, bub, hist = binding.adaptra_best(prob)
+    torch.cuda.synchronize()
+    binding.adaptra_set_kernel_mode(0)
+    return (idx.cpu().numpy(), mk.cpu().numpy(), bub.cpu().numpy(),
+            None if hist is None else hist.cpu().numpy().astype(np.uint64))
+
+
+def check_full(binding, oracle, wl, modes=(0, 1, 2)):
+    ref = oracle.eval_workload(wl)
+    rbest = oracle.best_from_eval(ref["makespan"], ref["flag"], ref["bubble"])
+    rhist = (oracle.hist_from_eval(ref["bubble"], ref["flag"], wl.hist_bins, wl.hist_shift)
+             if wl.hist_bins else None)
+    for mode in modes:
+        say(f"  {wl.name}: eval mode {mode}")
+        mk, bub, fl = gpu_eval(binding, wl, mode)
+        assert np.array_equal(fl, ref["flag"]), f"flag mismatch mode {mode}"
+        assert np.array_equal(mk, ref["makespan"]), f"makespan mismatch mode {mode}"
+        assert np.array_equal(bub, ref["bubble"]), f"bubble mismatch mode {mode}"
+        say(f"  {wl.name}: best mode {mode}")
+        idx, bmk, bbub, hist = gpu_best(binding, wl, mode)
+        assert np.array_equal(idx, rbest["best_idx"]), f"best_idx mismatch mode {mode}"
+        assert np.array_equal(bmk, rbest["best_makespan"])
+        assert np.array_equal(bbub, rbest["best_bubble"])
+        if rhist is not None:
+            assert np.array_equal(hist, rhist), f"histogram mismatch mode {mode}"
+
+
+@pytest.mark.parametrize("index", [0, 1])
+def test_config_full_parity(lib, oracle, index):
+    wl = workloads.config(index)
+    say(f"config {index}: {wl.name}, {wl.n_pairs} pairs")
+    check_full(lib, oracle, wl)
+
+
+RAGGED = [
+    # seed, S, M, C, K, kwargs
+    (1, 1, 1, 5, 3, {}),
+    (2, 1, 7, 70, 65, dict(hist_bins=8, hist_shift=6)),
+    (3, 2, 3, 33, 64, {}),
+    (4, 3, 5, 100, 7, {}),                      # S without a register kernel
+    (5, 4, 8, 257, 129, dict(hist_bins=16, hist_shift=8)),
+    (6, 4, 1, 64, 64, {}),                      # a single micro-batch
+    (7, 5, 12, 130, 40, dict(cap=False)),
+    (8, 8, 32, 1000, 64, dict(d_max=7, hist_bins=64, hist_shift=10)),
+    (9, 8, 100, 300, 100, dict(w_extra=60)),    # warm-up deeper than the LDS ring
+    (10, 8, 9, 200, 64, dict(w_extra=20)),      # w above M-1 everywhere: clamped
+    (11, 16, 64, 500, 70, dict(d_max=4)),
+    (12, 16, 20, 77, 128, dict(w_extra=3, hist_bins=300, hist_shift=7)),   # histogram too wide for LDS
+    (13, 32, 40, 150, 64, dict(d_max=4)),
+    (14, 32, 128, 64, 65, dict(d_max=4, c_hi=50000)),
+    (15, 64, 70, 40, 30, dict(d_max=2)),
+    (16, 2, 300, 50, 64, dict(w_extra=1)),
+    (17, 8, 64, 17, 1, dict()),                 # a single scenario
+    (18, 8, 200, 64, 64, dict(w_extra=40)),     # ring classes 5-6
+]
+
+
+@pytest.mark.parametrize("seed,S,M,C,K,kw", RAGGED, ids=[f"S{r[1]}_M{r[2]}_C{r[3]}_K{r[4]}" for r in RAGGED])
+def test_ragged_shapes_full_parity(lib, oracle, seed, S, M, C, K, kw):
+    wl = workloads.random_workload(seed, S, M, C, K, **kw)
+    say(f"ragged {wl.name}")
+    check_full(lib, oracle, wl)
+
+
+def test_no_feasible_candidate(lib, oracle):
+    wl = workloads.random_workload(40, 4, 6, 90, 70)
+    wl.mem_cap[:] = 0                                   # nobody fits
+    check_full(lib, oracle, wl)
+    idx, mk, bub, _ = gpu_best(lib, wl)
+    assert np.all(idx == -1) and np.all(mk == INT32_MAX) and np.all(bub == INT32_MAX)
+
+
+def test_zero_times_and_zero_delays(lib, oracle):
+    wl = workloads.random_workload(41, 8, 16, 128, 64, cap=False)
+    wl.t_f[::2] = 0
+    wl.t_b[1::3] = 0
+    wl.c_fwd[:] = 0
+    wl.c_bwd[::2] = 0
+    check_full(lib, oracle, wl)
+
+
+def _sampled_parity(lib, oracle, index, n_sample, full_scenarios):
+    """Full-size configuration, launch shape as benchmarked: every pair is evaluated on the
+    GPU; the oracle checks (a) a seeded sample of pairs, (b) whole scenarios including the
+    search over all candidates; (c) adaptra_best must equal a host argmin over the GPU's own
+    complete evaluation for every scenario."""
+    wl = workloads.config(index)
+    say(f"config {index}: {wl.name}: GPU eval of {wl.n_pairs} pairs")
+    mk, _, fl = gpu_eval(lib, wl, want_bubble=False)
+    tau = (wl.t_f + wl.t_b).astype(np.int64)
+    # (a) sampled pairs, with bubbles from a second, bubble-enabled pass over a sub-problem
+    pc, ps = workloads.sample_pairs(900 + index, wl.n_cand, wl.n_scen, n_sample)
+    say(f"  oracle on {n_sample} sampled pairs")
+    ref = oracle.eval_workload(wl, pair_cand=pc, pair_scen=ps)
+    assert np.array_equal(fl[ps, pc], ref["flag"])
+    assert np.array_equal(mk[ps, pc], ref["makespan"])
+    live = (ref["flag"] & 2) == 0
+    assert np.array_equal((mk[ps, pc].astype(np.int64)[None, :] - wl.M * tau[:, None])[:, live],
+                          ref["bubble"][:, live].astype(np.int64))
+    # (c) search == argmin over the GPU's evaluation
+    say("  GPU best vs host argmin over the GPU evaluation")
+    idx, bmk, bbub, hist = gpu_best(lib, wl)
+    masked = np.where(fl == 1, mk.astype(np.int64), np.int64(2) ** 40)
+    want_idx = masked.argmin(axis=1).astype(np.int32)
+    any_ok = (fl == 1).any(axis=1)
+    want_idx[~any_ok] = -1
+    want_mk = np.where(any_ok, masked.min(axis=1), INT32_MAX).astype(np.int32)
+    assert np.array_equal(idx, want_idx)
+    assert np.array_equal(bmk, want_mk)
+    want_bub = np.where(any_ok[:, None], want_mk.astype(np.int64)[:, None] - wl.M * tau[None, :], INT32_MAX)
+    assert np.array_equal(bbub.astype(np.int64), want_bub)
+    if wl.hist_bins:
+        want = np.zeros((wl.S, wl.hist_bins), dtype=np.uint64)
+        ok = fl == 1
+        for s in range(wl.S):
+            b = np.minimum(wl.hist_bins - 1, (mk[ok].astype(np.int64) - wl.M * tau[s]) >> wl.hist_shift)
+            want[s] = np.bincount(b, minlength=wl.hist_bins).astype(np.uint64)
+        assert np.array_equal(hist, want)
+    # (b) whole scenarios through the oracle, search included
+    for k in full_scenarios:
+        say(f"  oracle on all {wl.n_cand} candidates of scenario {k}")
+        cand = np.arange(wl.n_cand, dtype=np.int64)
+        ref = oracle.eval_workload(wl, pair_cand=cand, pair_scen=np.full(wl.n_cand, k, dtype=np.int64),
+                                   want_bubble=False)
+        assert np.array_equal(fl[k], ref["flag"])
+        assert np.array_equal(mk[k], ref["makespan"])
+        rb = oracle.best_from_eval(ref["makespan"][None, :], ref["flag"][None, :])
+        assert idx[k] == rb["best_idx"][0] and bmk[k] == rb["best_makespan"][0]
+
+
+def test_config2_sampled_parity(lib, oracle):
+    _sampled_parity(lib, oracle, 2, 1 << 15, (0, 131))
+
+
+def test_config3_sampled_parity(lib, oracle):
+    _sampled_parity(lib, oracle, 3, 1 << 13, (0, 517))
+
+
+def test_config4_sampled_parity(lib, oracle):
+    _sampled_parity(lib, oracle, 4, 1 << 14, (37,))
+
+
+def test_bubble_output_at_full_size_config3_subset(lib, oracle):
+    """Bubble array written by the benchmarked launch shape (S = 32): a slice of configuration 3
+    (all scenarios, 2048 candidates) with the bubble output on, sampled against the oracle."""
+    wl = workloads.config(3)
+    wl.w = np.ascontiguousarray(wl.w[:, 4096:4096 + 2048])
+    mk, bub, fl = gpu_eval(lib, wl, want_bubble=True)
+    pc, ps = workloads.sample_pairs(77, wl.n_cand, wl.n_scen, 1 << 11)
+    ref = oracle.eval_workload(wl, pair_cand=pc, pair_scen=ps)
+    assert np.array_equal(fl[ps, pc], ref["flag"])
+    assert np.array_equal(mk[ps, pc], ref["makespan"])
+    assert np.array_equal(bub[:, ps, pc], ref["bubble"])
+    tau = (wl.t_f + wl.t_b).astype(np.int64)
+    live = (fl & 2) == 0
+    full = mk.astype(np.int64)[None] - wl.M * tau[:, None, None]
+    assert np.array_equal(bub.astype(np.int64)[:, live], full[:, live])
+    assert np.all(bub[:, ~live] == INT32_MAX)
+
+
+def test_errors_and_check_inputs(lib):
+    import torch
+    b = lib
+    wl = workloads.random_workload(50, 4, 8, 64, 64)
+    prob = b.Problem.from_workload(wl)
+    ws = b.alloc_workspace(prob)
+    assert b.adaptra_check_inputs(prob, ws) == b.ERANGE      # random_workload plants negative w
+    wl.w = np.abs(wl.w)
+    prob = b.Problem.from_workload(wl)
+    assert b.adaptra_check_inputs(prob, ws) == b.OK
+    wl2 = workloads.random_workload(51, 4, 8, 64, 64)
+    wl2.w = np.abs(wl2.w)
+    wl2.c_fwd[1, 3] = -1
+    assert b.adaptra_check_inputs(b.Problem.from_workload(wl2), ws) == b.ERANGE
+    wl3 = workloads.random_workload(52, 4, 8, 64, 64)
+    wl3.w = np.abs(wl3.w)
+    wl3.c_bwd[2, 5] = 2 ** 31 // (2 * 4 * 8)                 # 2 M S (t + c) reaches 2^31
+    assert b.adaptra_check_inputs(b.Problem.from_workload(wl3), ws) == b.EOVERFLOW
+    # too small / misaligned workspace, bad sizes
+    with pytest.raises(b.AdaptraError) as e:
+        b.adaptra_eval(prob, workspace=ws[:1024])
+    assert e.value.code == b.EWORKSPACE
+    with pytest.raises(b.AdaptraError) as e:
+        b.adaptra_eval(prob, workspace=ws[1:])
+    assert e.value.code == b.EWORKSPACE
+    bad = b.Problem.from_workload(wl)
+    bad.params.M = 0
+    with pytest.raises(b.AdaptraError) as e:
+        b.adaptra_eval(bad, workspace=ws)
+    assert e.value.code == b.EINVAL
+    bad = b.Problem.from_workload(wl)
+    bad.params.hist_bins = 4                                  # histogram requested, no buffer
+    bad.hist_bins = 0
+    with pytest.raises(b.AdaptraError) as e:
+        b.adaptra_best(bad, workspace=ws)
+    assert e.value.code == b.EINVAL
+    torch.cuda.synchronize()
+
+
+def test_runs_on_a_side_stream_and_is_repeatable(lib, oracle):
+    import torch
+    b = lib
+    wl = workloads.random_workload(60, 8, 24, 512, 64, hist_bins=32, hist_shift=8)
+    ref = oracle.eval_workload(wl)
+    rbest = oracle.best_from_eval(ref["makespan"], ref["flag"], ref["bubble"])
+    prob = b.Problem.from_workload(wl)
+    ws = b.alloc_workspace(prob)
+    st = torch.cuda.Stream()
+    outs = []
+    with torch.cuda.stream(st):
+        for _ in range(3):
+            mk, bub, fl = b.adaptra_eval(prob, workspace=ws)
+            idx, bmk, bbub, hist = b.adaptra_best(prob, workspace=ws)
+            outs.append((mk, idx, hist))
+    st.synchronize()
+    for mk, idx, hist in outs:
+        assert np.array_equal(mk.cpu().numpy(), ref["makespan"])
+        assert np.array_equal(idx.cpu().numpy(), rbest["best_idx"])
+    assert torch.equal(outs[0][2], outs[2][2])               # histogram overwritten, not accumulated
+
+
+@pytest.mark.parametrize("bound", [-1, 3, 10, 17, 63, 1000])
+def test_w_bound_promise_kept_or_broken(lib, oracle, bound):
+    """The w_bound hint only sizes the on-chip ring; results must not depend on it, even when
+    candidates exceed it (those take the general kernel)."""
+    import torch
+    b = lib
+    wl = workloads.random_workload(70, 8, 40, 400, 64, d_max=6, w_extra=4, hist_bins=16, hist_shift=9)
+    ref = oracle.eval_workload(wl)
+    rbest = oracle.best_from_eval(ref["makespan"], ref["flag"], ref["bubble"])
+    rhist = oracle.hist_from_eval(ref["bubble"], ref["flag"], wl.hist_bins, wl.hist_shift)
+    prob = b.Problem.from_workload(wl, w_bound=bound)
+    mk, bub, fl = b.adaptra_eval(prob)
+    idx, bmk, bbub, hist = b.adaptra_best(prob)
+    torch.cuda.synchronize()
+    assert np.array_equal(fl.cpu().numpy(), ref["flag"])
+    assert np.array_equal(mk.cpu().numpy(), ref["makespan"])
+    assert np.array_equal(bub.cpu().numpy(), ref["bubble"])
+    assert np.array_equal(idx.cpu().numpy(), rbest["best_idx"])
+    assert np.array_equal(hist.cpu().numpy().astype(np.uint64), rhist)
