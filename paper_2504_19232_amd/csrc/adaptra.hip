@@ -13,7 +13,8 @@
 //                        frontier of the in-flight micro-batches in an LDS ring
 //   k_resolve_general    any S / M / warm-up depth: one lane per pair (64 candidates of one
 //                        scenario per wavefront), state in global scratch, DPP argmin
-//   k_fill_eval          feasibility byte for every pair, sentinels for deadlocked pairs
+//   k_eval_epilogue      after the resolve kernels: flag byte and bubbles of every pair,
+//                        sentinels for deadlocked pairs (one coalesced streaming pass)
 //   k_best_init / k_best_finalize   search keys and histogram set-up / decoding
 //   k_check_inputs       range scan for adaptra_check_inputs
 //
@@ -36,6 +37,7 @@ constexpr int kClassDead = 255;           // deadlocked: never resolved
 constexpr int kClassDeep = 254;           // warm-up depth beyond the LDS ring: general kernel
 constexpr int kNumRingClasses = 8;        // ring of 8 * (class + 1) slots
 constexpr int kMaxLdsHistBytes = 16384;
+constexpr int kPrefetchStages = 8;        // ring reads run this many stages ahead of their use
 constexpr unsigned long long kNoKey = ~0ull;
 
 struct KArgs {
@@ -59,6 +61,71 @@ struct KArgs {
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ int imax(int a, int b) { return a > b ? a : b; }
+// Ring offset of a stage, one slot (256 B) further, wrapping to slot 0.  The offset is kept
+// biased by -ring_bytes (mod 2^32) so that the wrap shows up as the carry of the add: two
+// SALU ops instead of add, compare, select.  The bias is folded into the lane's base address.
+__device__ __forceinline__ unsigned ring_next(unsigned t, unsigned bias) {
+    asm("s_add_u32 %0, %0, 0x100\n\ts_cmov_b32 %0, %1" : "+s"(t) : "s"(bias) : "scc");
+    return t;
+}
+
+// bit `kBit` of the uniform 64-bit mask set ? b : a.  One SALU op spreads the bit over vcc
+// (a signed one-bit field extract), one VALU op selects; a branch would cost more issue
+// slots than it saves, hoisted lane masks two SGPRs per stage.
+template <int kBit>
+__device__ __forceinline__ int select_by_bit(unsigned long long mask, int a, int b) {
+    int o;
+    asm("s_bfe_i64 vcc, %1, %2\n\tv_cndmask_b32 %0, %3, %4, vcc"
+        : "=v"(o) : "s"(mask), "n"(kBit | (1 << 16)), "v"(a), "v"(b) : "scc", "vcc");
+    return o;
+}
+
+typedef __attribute__((address_space(3))) int lds_int;
+
+// Compile-time stage loops: the stage index must be a constant (register arrays, asm
+// immediates), so they are unrolled by template recursion rather than by a pragma.
+template <int kI>
+struct StageIndex {
+    static constexpr int value = kI;
+};
+template <int kBegin, int kEnd, class F>
+__device__ __forceinline__ void stages_up(F &&f) {
+    if constexpr (kBegin < kEnd) {
+        f(StageIndex<kBegin>{});
+        stages_up<kBegin + 1, kEnd>(f);
+    }
+}
+template <int kBegin, int kEnd, class F>          // kBegin down to kEnd, inclusive
+__device__ __forceinline__ void stages_down(F &&f) {
+    if constexpr (kBegin >= kEnd) {
+        f(StageIndex<kBegin>{});
+        stages_down<kBegin - 1, kEnd>(f);
+    }
+}
+// stages kBegin, kBegin+1, ... while the stage index is below `limit` (uniform): the first
+// stage at or past the limit ends the sweep with a single branch.
+template <int kBegin, int kEnd, class F>
+__device__ __forceinline__ void stages_below(int limit, F &&f) {
+    if constexpr (kBegin < kEnd) {
+        if (kBegin < limit) {
+            f(StageIndex<kBegin>{});
+            stages_below<kBegin + 1, kEnd>(limit, f);
+        }
+    }
+}
+#define ADAPTRA_STAGE_LAMBDA(si) [&](auto si) __attribute__((always_inline))
+
+// Kernel arguments of the hot kernel, read where they are used.  The struct is the
+// kernel's only parameter, so it sits at the start of the kernarg segment; going through
+// an opaque copy of that pointer makes every use a fresh scalar load (a scalar-cache hit)
+// instead of two dozen values kept in SGPRs across the round loops, where the stage
+// constants and ring offsets need the room.
+typedef const __attribute__((address_space(4))) KArgs *KArgsPtr;
+__device__ __forceinline__ KArgsPtr kargs() {
+    KArgsPtr p = (KArgsPtr)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(p));
+    return p;
+}
 __device__ __forceinline__ int clampw(int w, int M) { return w < 0 ? 0 : (w > M - 1 ? M - 1 : w); }
 
 // ---------------------------------------------------------------------------------------
@@ -125,18 +192,24 @@ __global__ __launch_bounds__(kBlock) void k_prepass(KArgs a) {
     }
 }
 
-// Flag byte for every pair; INT32_MAX for the makespan and bubbles of deadlocked pairs.
-__global__ __launch_bounds__(kBlock) void k_fill_eval(KArgs a) {
+// Runs after the resolve kernels, which leave the makespan of every pair that is not
+// deadlocked in out_makespan.  One streaming pass over all pairs, coalesced along the
+// candidate axis: flag byte; INT32_MAX for deadlocked pairs; bubble[s] = makespan -
+// M (t_f[s] + t_b[s]) (idle time of stage s inside [0, makespan]) for the others.
+__global__ __launch_bounds__(kBlock) void k_eval_epilogue(KArgs a) {
     const long long P = a.C * a.K;
     const long long stride = (long long)gridDim.x * kBlock;
     for (long long p = (long long)blockIdx.x * kBlock + threadIdx.x; p < P; p += stride) {
         const long long c = p % a.C;
         const int flag = a.cand_flag[c];
+        const bool dead = flag & ADAPTRA_FLAG_DEADLOCK;
         a.out_feasible[p] = (unsigned char)flag;
-        if (flag & ADAPTRA_FLAG_DEADLOCK) {
-            a.out_makespan[p] = INT32_MAX;
-            if (a.out_bubble)
-                for (int s = 0; s < a.S; ++s) a.out_bubble[(long long)s * P + p] = INT32_MAX;
+        int mk = INT32_MAX;
+        if (dead) a.out_makespan[p] = INT32_MAX;
+        else mk = a.out_makespan[p];
+        if (a.out_bubble) {
+            for (int s = 0; s < a.S; ++s)
+                a.out_bubble[(long long)s * P + p] = dead ? INT32_MAX : mk - a.M * (a.t_f[s] + a.t_b[s]);
         }
     }
 }
@@ -233,12 +306,8 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
                     }
                 }
             } else {
-                const long long P = a.C * a.K;
                 const long long p = k * a.C + c;
-                a.out_makespan[p] = mk;
-                if (a.out_bubble)
-                    for (int s = 0; s < S; ++s)
-                        a.out_bubble[(long long)s * P + p] = mk - M * (a.t_f[s] + a.t_b[s]);
+                a.out_makespan[p] = mk;          // bubbles follow in k_eval_epilogue
             }
         }
         if (BEST) {
@@ -269,168 +338,204 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
 //
 // LDS ring: at round r the forwards in flight between stages are micro-batches
 // w[S-1] + r < m <= w[0] + r, one value each, so D >= w[0] + 1 slots of 64 lanes suffice;
-// slot-major layout [slot][lane] keeps every access conflict-free.
+// slot-major layout [slot][lane] keeps every access conflict-free.  The reads are software
+// pipelined: each is issued several stages (or, for the first stages, a whole backward
+// sweep) ahead of its use, so the LDS latency does not stall every stage.
 template <int S, bool BEST>
-__global__ __launch_bounds__(kBlock) void k_resolve_scen_lanes(KArgs a) {
+__global__ __launch_bounds__(kBlock, S >= 32 ? 4 : 6) void k_resolve_scen_lanes(KArgs) {
+    // The arguments are read through kargs() where they are needed (see there), never
+    // through the by-value parameter.
     extern __shared__ int lds[];
+    constexpr int kPD = S - 1 < kPrefetchStages ? S - 1 : kPrefetchStages;
     const int lane = threadIdx.x & 63;
     const int wv = uni(threadIdx.x >> 6);
-    const int M = a.M;
-    const int ring_bytes = a.ring_slots * 256;
-    char *const ring = (char *)lds + wv * ring_bytes + lane * 4;
+    const unsigned ring_bytes = (unsigned)kargs()->ring_slots * 256u;
+    const unsigned bias = 0u - ring_bytes;                 // ring offsets live in [bias, 2^32)
+    // LDS byte address of this lane's column of the wave's ring, plus ring_bytes (un-bias)
+    const unsigned ring = (unsigned)(size_t)(lds_int *)lds + (unsigned)wv * ring_bytes + (unsigned)lane * 4u + ring_bytes;
     unsigned *const hist_lds = (unsigned *)((char *)lds + kWavesPerBlock * ring_bytes);
-    const bool lds_hist = BEST && a.hist && a.hist_in_lds;
+    const bool lds_hist = BEST && kargs()->hist && kargs()->hist_in_lds;
     if (lds_hist) {
-        for (int i = threadIdx.x; i < S * a.hist_bins; i += kBlock) hist_lds[i] = 0;
+        const int n = S * kargs()->hist_bins;
+        for (int i = threadIdx.x; i < n; i += kBlock) hist_lds[i] = 0;
         __syncthreads();
     }
 
     const long long task = (long long)blockIdx.x * kWavesPerBlock + wv;
-    const int tile = (int)(task % a.n_ktiles);
-    const long long c0 = (task / a.n_ktiles) * kChunk;
-    if (c0 < a.C) {
+    const int tile = (int)(task % kargs()->n_ktiles);
+    const long long c0 = (task / kargs()->n_ktiles) * kChunk;
+    if (c0 < kargs()->C) {
+        const long long K = kargs()->K;
         const long long k = (long long)tile * 64 + lane;
-        const bool kvalid = k < a.K;
-        const long long kk = kvalid ? k : a.K - 1;
-        int tf[S], tb[S], tau[S];
+        const bool kvalid = k < K;
+        const long long kk = kvalid ? k : K - 1;
+        // t_f + t_b of every stage: SGPRs.  t_f and t_b themselves, needed only while the
+        // pipeline fills and drains, share one VGPR each (lane s holds stage s) and are
+        // fetched with v_readlane where used.
+        int tau[S];
+        {
+            const int *t_f = kargs()->t_f, *t_b = kargs()->t_b;
 #pragma unroll
-        for (int s = 0; s < S; ++s) {
-            tf[s] = uni(a.t_f[s]);
-            tb[s] = uni(a.t_b[s]);
-            tau[s] = tf[s] + tb[s];
+            for (int s = 0; s < S; ++s) tau[s] = uni(t_f[s]) + uni(t_b[s]);
         }
+        const int tf_lanes = kargs()->t_f[lane < S ? lane : 0];
+        const int tb_lanes = kargs()->t_b[lane < S ? lane : 0];
         int q[S > 1 ? S - 1 : 1];
+        {
+            const int *cf = kargs()->cf, *cb = kargs()->cb;
 #pragma unroll
-        for (int s = 0; s + 1 < S; ++s) q[s] = a.cf[s * a.K + kk] + a.cb[s * a.K + kk] + tau[s + 1];
+            for (int s = 0; s + 1 < S; ++s) q[s] = cf[s * K + kk] + cb[s * K + kk] + tau[s + 1];
+        }
 
         unsigned long long key = kNoKey;
-        const int c_end = (int)((a.C - c0 < kChunk) ? (a.C - c0) : kChunk);
+        const long long c_left = kargs()->C - c0;
+        const int c_end = (int)(c_left < kChunk ? c_left : kChunk);
         for (int ci = 0; ci < c_end; ++ci) {
             const long long c = c0 + ci;
-            const int cls = uni(a.cand_class[c]);
-            if (cls < a.cls_lo || cls > a.cls_hi) continue;
-            if (BEST && uni(a.cand_flag[c]) != ADAPTRA_FLAG_FEASIBLE) continue;
-            int wq[S];
             {
-                const unsigned *p = (const unsigned *)(a.cand_wq + c * a.wq_stride);
-#pragma unroll
-                for (int s = 0; s < S; ++s) {
-                    const unsigned word = (unsigned)uni((int)p[s >> 2]);
-                    wq[s] = (int)((word >> (8 * (s & 3))) & 0xffu);
-                }
+                const int cls = uni(kargs()->cand_class[c]);
+                if (cls < kargs()->cls_lo || cls > kargs()->cls_hi) continue;
+                if (BEST && uni(kargs()->cand_flag[c]) != ADAPTRA_FLAG_FEASIBLE) continue;
             }
-            const int W = wq[0];
-            int L[S], soff[S];
-            L[0] = -tf[0];
+            // w of the candidate: lane s holds w[s] (fetched with v_readlane where a stage's
+            // own value is needed).  zmask, bit s: stages s-1 and s share w (slack 0).
+            const int wq_lanes = kargs()->cand_wq[c * kargs()->wq_stride + (lane < S ? lane : 0)];
+            const int W = __builtin_amdgcn_readlane(wq_lanes, 0);
+            const int M = kargs()->M;
+            const int wq_prev = __shfl_up(wq_lanes, 1);   // all lanes take part: not under the &&
+            const unsigned long long zmask = __ballot(lane >= 1 && lane < S && wq_prev == wq_lanes);
+            int L[S], x[S];
+            unsigned soff[S];     // biased ring offset of the stage's next forward micro-batch
 #pragma unroll
-            for (int s = 1; s < S; ++s) L[s] = kNeg;
-#pragma unroll
-            for (int s = 0; s < S; ++s) {         // slot of micro-batch wq[s] - W (<= 0), mod D
-                int m0 = wq[s] - W + a.ring_slots;
-                if (m0 >= a.ring_slots) m0 -= a.ring_slots;
-                soff[s] = m0 * 256;
+            for (int s = 0; s < S; ++s) {
+                L[s] = kNeg;
+                x[s] = 0;
+                soff[s] = bias;   // micro-batch 0 sits in slot 0
             }
+            L[0] = -__builtin_amdgcn_readlane(tf_lanes, 0);
 
-#define ADAPTRA_F_OP(s, e)                                              \
-    do {                                                                \
-        int *slot = (int *)(ring + soff[s]);                            \
-        if ((s) == 0) {                                                 \
-            L[0] += (e);                                                \
-            if (S > 1) *slot = L[0];                                    \
-        } else {                                                        \
-            const int x = *slot;                                        \
-            L[s] = imax(L[s] + (e), x);                                 \
-            if ((s) < S - 1) *slot = L[s];                              \
-        }                                                               \
+// One forward step of stage s.  x[s] is the value micro-batch m got on stage s-1, read from
+// ring slot m mod D some stages earlier; if the two stages have equal w that value is only
+// being produced in this very round and comes from L[s-1] instead.  The result goes to slot
+// m and the stage's offset moves on to slot m+1.
+#define ADAPTRA_F_OP(s, e)                                                      \
+    do {                                                                        \
+        if constexpr ((s) == 0) {                                               \
+            L[0] += (e);                                                        \
+        } else {                                                                \
+            const int t = L[s] + (e);                                           \
+            L[s] = imax(t, select_by_bit<(s)>(zmask, x[s], L[(s) > 0 ? (s) - 1 : 0])); \
+        }                                                                       \
+        if constexpr ((s) < S - 1) *(lds_int *)(ring + soff[s]) = L[s];         \
+        soff[s] = ring_next(soff[s], bias);                                     \
     } while (0)
-#define ADAPTRA_ADVANCE(s)                                              \
-    do {                                                                \
-        soff[s] += 256;                                                 \
-        if (soff[s] == ring_bytes) soff[s] = 0;                         \
+// Reads run kPD stages ahead of their use: stage s issues the read of stage s+kPD ...
+#define ADAPTRA_READ_AHEAD(s)                                                   \
+    do {                                                                        \
+        if constexpr ((s) + kPD <= S - 1)                                       \
+            x[(s) + kPD <= S - 1 ? (s) + kPD : 0] =                             \
+                *(lds_int *)(ring + soff[(s) + kPD <= S - 1 ? (s) + kPD : 0]);  \
+    } while (0)
+// ... and the reads of stages 1..kPD for the next round are issued at the end of the
+// forward sweep, so that they complete under the backward sweep.
+#define ADAPTRA_READ_NEXT_ROUND()                                               \
+    stages_up<1, kPD + 1>(ADAPTRA_STAGE_LAMBDA(sj) {                            \
+        constexpr int j = decltype(sj)::value;                                  \
+        x[j] = *(lds_int *)(ring + soff[j]);                                    \
+    })
+#define ADAPTRA_B_SWEEP()                                                       \
+    do {                                                                        \
+        int carry = L[S - 1];                                                   \
+        stages_down<S - 2, 0>(ADAPTRA_STAGE_LAMBDA(si) {                        \
+            constexpr int s = decltype(si)::value;                              \
+            L[s] = imax(L[s], carry + q[s]);                                    \
+            carry = L[s];                                                       \
+        });                                                                     \
     } while (0)
 
-            // warm-up rounds r = -W .. 0: forwards only, each after a forward
-            for (int r = -W; r <= 0; ++r) {
-#pragma unroll
-                for (int s = 0; s < S; ++s) {
-                    if (wq[s] + r >= 0) ADAPTRA_F_OP(s, tf[s]);
-                    ADAPTRA_ADVANCE(s);
+            // warm-up rounds r = -W .. 0: forwards only, each after a forward.  Stage s has
+            // started once w[s] + r >= 0; w is non-increasing, so the running stages are
+            // 0 .. nv-1 and the sweep stops at the first one that has not started.
+            {
+                int nv = 0;
+                for (int r = -W; r <= 0; ++r) {
+                    while (nv < S && __builtin_amdgcn_readlane(wq_lanes, nv) + r >= 0) ++nv;
+                    stages_below<0, S>(nv, ADAPTRA_STAGE_LAMBDA(si) {
+                        constexpr int s = decltype(si)::value;
+                        ADAPTRA_F_OP(s, __builtin_amdgcn_readlane(tf_lanes, s));
+                        ADAPTRA_READ_AHEAD(s);
+                    });
+                    ADAPTRA_READ_NEXT_ROUND();
                 }
             }
-            {   // B(s, 0): each after a forward
-                int carry = L[S - 1];
-#pragma unroll
-                for (int s = S - 2; s >= 0; --s) {
-                    L[s] = imax(L[s], carry + q[s]);
-                    carry = L[s];
-                }
-            }
+            ADAPTRA_B_SWEEP();                    // B(s, 0): each after a forward
             // steady rounds r = 1 .. M-1-W: F after B, B after F on every stage
-            const int r_steady_end = M - 1 - W;
-            for (int r = 1; r <= r_steady_end; ++r) {
-#pragma unroll
-                for (int s = 0; s < S; ++s) {
+            for (int r = M - 1 - W; r > 0; --r) {
+                stages_up<0, S>(ADAPTRA_STAGE_LAMBDA(si) {
+                    constexpr int s = decltype(si)::value;
                     ADAPTRA_F_OP(s, tau[s]);
-                    ADAPTRA_ADVANCE(s);
-                }
-                int carry = L[S - 1];
-#pragma unroll
-                for (int s = S - 2; s >= 0; --s) {
-                    L[s] = imax(L[s], carry + q[s]);
-                    carry = L[s];
-                }
+                    ADAPTRA_READ_AHEAD(s);
+                });
+                ADAPTRA_READ_NEXT_ROUND();
+                ADAPTRA_B_SWEEP();
             }
-            // cool-down rounds r = M-W .. M-1: stages run out of forwards one by one
-            for (int r = M - W; r <= M - 1; ++r) {
-                int carry = 0;
-#pragma unroll
-                for (int s = 0; s < S; ++s) {
-                    if (wq[s] + r <= M - 1) ADAPTRA_F_OP(s, tau[s]);
-                    ADAPTRA_ADVANCE(s);
-                }
-#pragma unroll
-                for (int s = S - 1; s >= 0; --s) {
-                    const bool had_f = wq[s] + r <= M - 1;
-                    const int prev = had_f ? L[s] : L[s] + tb[s];
-                    L[s] = (s == S - 1) ? prev : imax(prev, carry + q[s]);
-                    carry = L[s];
+            // cool-down rounds r = M-W .. M-1: stage s is out of forwards once
+            // w[s] + r > M-1, which holds for the stages 0 .. done-1.
+            {
+                int done = 0;
+                for (int r = M - W; r <= M - 1; ++r) {
+                    while (done < S && __builtin_amdgcn_readlane(wq_lanes, done) + r > M - 1) ++done;
+                    stages_up<0, S>(ADAPTRA_STAGE_LAMBDA(si) {
+                        constexpr int s = decltype(si)::value;
+                        if (s >= done) ADAPTRA_F_OP(s, tau[s]);
+                        ADAPTRA_READ_AHEAD(s);
+                    });
+                    ADAPTRA_READ_NEXT_ROUND();
+                    int carry = 0;
+                    stages_down<S - 1, 0>(ADAPTRA_STAGE_LAMBDA(si) {
+                        constexpr int s = decltype(si)::value;
+                        int prev = L[s];
+                        if (s < done) prev += __builtin_amdgcn_readlane(tb_lanes, s);   // B after B
+                        L[s] = (s == S - 1) ? prev : imax(prev, carry + q[s < S - 1 ? s : 0]);
+                        carry = L[s];
+                    });
                 }
             }
 #undef ADAPTRA_F_OP
-#undef ADAPTRA_ADVANCE
+#undef ADAPTRA_READ_AHEAD
+#undef ADAPTRA_READ_NEXT_ROUND
+#undef ADAPTRA_B_SWEEP
 
-            const int mk = L[0] + tf[0] + tb[0];
+            const int mk = L[0] + tau[0];
             if (BEST) {
                 if (kvalid) {
                     const unsigned long long cand = ((unsigned long long)(unsigned)mk << 32) | (unsigned)c;
                     key = cand < key ? cand : key;
-                    if (a.hist) {
+                    if (kargs()->hist) {
+                        const int bins = kargs()->hist_bins, shift = kargs()->hist_shift;
+                        unsigned long long *const hist = kargs()->hist;
 #pragma unroll
                         for (int s = 0; s < S; ++s) {
-                            int b = (mk - M * tau[s]) >> a.hist_shift;
-                            b = b > a.hist_bins - 1 ? a.hist_bins - 1 : b;
-                            if (lds_hist) atomicAdd(&hist_lds[s * a.hist_bins + b], 1u);
-                            else atomicAdd(&a.hist[s * a.hist_bins + b], 1ull);
+                            int b = (mk - M * tau[s]) >> shift;
+                            b = b > bins - 1 ? bins - 1 : b;
+                            if (lds_hist) atomicAdd(&hist_lds[s * bins + b], 1u);
+                            else atomicAdd(&hist[s * bins + b], 1ull);
                         }
                     }
                 }
             } else if (kvalid) {
-                const long long P = a.C * a.K;
-                const long long p = k * a.C + c;
-                a.out_makespan[p] = mk;
-                if (a.out_bubble) {
-#pragma unroll
-                    for (int s = 0; s < S; ++s) a.out_bubble[(long long)s * P + p] = mk - M * tau[s];
-                }
+                kargs()->out_makespan[k * kargs()->C + c] = mk;   // bubbles follow in k_eval_epilogue
             }
         }
-        if (BEST && kvalid && key != kNoKey) atomicMin(&a.keys[k], key);
+        if (BEST && kvalid && key != kNoKey) atomicMin(&kargs()->keys[k], key);
     }
     if (lds_hist) {
         __syncthreads();
-        for (int i = threadIdx.x; i < S * a.hist_bins; i += kBlock) {
-            const unsigned n = hist_lds[i];
-            if (n) atomicAdd(&a.hist[i], (unsigned long long)n);
+        const int n = S * kargs()->hist_bins;
+        unsigned long long *const hist = kargs()->hist;
+        for (int i = threadIdx.x; i < n; i += kBlock) {
+            const unsigned cnt = hist_lds[i];
+            if (cnt) atomicAdd(&hist[i], (unsigned long long)cnt);
         }
     }
 }
@@ -706,9 +811,11 @@ int adaptra_eval(const adaptra_params_t *params, const adaptra_candidates_t *can
     a.out_feasible = out_feasible;
     hipLaunchKernelGGL(k_prepass, dim3(grid_for(a.C, INT32_MAX)), dim3(kBlock), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_fill_eval, dim3(grid_for(a.C * a.K, 1 << 16)), dim3(kBlock), 0, st, a);
+    rc = launch_resolve<false>(a, ws, cands->w_bound, st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_eval_epilogue, dim3(grid_for(a.C * a.K, 1 << 16)), dim3(kBlock), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
-    return launch_resolve<false>(a, ws, cands->w_bound, st);
+    return ADAPTRA_OK;
 }
 
 int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *cands,
