@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--no-bubble", action="store_true", help="skip adaptra_eval's [S][K][C] bubble output")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-mode", type=int, default=0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device-to-device copy before the timed region (a kernel of "
+                         "known traffic, to scale the FETCH_SIZE / WRITE_SIZE counters in a profile)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); nothing here is distributed.",
@@ -117,6 +120,13 @@ def main():
     def step():
         binding.adaptra_eval(prob, mk, bub, fl, want_bubble=bub is not None, workspace=ws)
         binding.adaptra_best(prob, bidx, bmk, bbub, hist, workspace=ws)
+
+    if args.copy_calibration:
+        src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

@@ -56,7 +56,8 @@ struct KArgs {
     int cls_lo, cls_hi, ring_slots, general_all;
     long long n_chunks;
     int n_ktiles;
-    int *status;
+    int *status;                           // [0..3] input check, [16..24] candidates per ring class
+    int *mk_t;                             // eval: makespan, candidate-major [C][K]
 };
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -165,8 +166,11 @@ __device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v)
 // (Algorithm 1, x_max).  Also packs w' into bytes for the hot kernel and bins the
 // candidate by the ring depth it needs, w'[0] + 1 slots.
 __global__ __launch_bounds__(kBlock) void k_prepass(KArgs a) {
+    __shared__ int class_count[kNumRingClasses + 1];
+    if (threadIdx.x <= kNumRingClasses) class_count[threadIdx.x] = 0;
+    __syncthreads();
     long long c = (long long)blockIdx.x * kBlock + threadIdx.x;
-    if (c >= a.C) return;
+    if (c < a.C) {
     const int S = a.S, M = a.M;
     bool dead = false, mem = false;
     int prev = clampw(a.w[c], M);
@@ -190,27 +194,45 @@ __global__ __launch_bounds__(kBlock) void k_prepass(KArgs a) {
         unsigned char *q = a.cand_wq + c * a.wq_stride;
         for (int s = 0; s < S; ++s) q[s] = (unsigned char)clampw(a.w[(long long)s * a.C + c], M);
     }
+    if (!dead) atomicAdd(&class_count[cls == kClassDeep ? kNumRingClasses : cls], 1);
+    }
+    __syncthreads();       // how many candidates need which ring depth: lets the kernels that
+    if (threadIdx.x <= kNumRingClasses && class_count[threadIdx.x])   // have no share exit at once
+        atomicAdd(&a.status[16 + threadIdx.x], class_count[threadIdx.x]);
 }
 
 // Runs after the resolve kernels, which leave the makespan of every pair that is not
-// deadlocked in out_makespan.  One streaming pass over all pairs, coalesced along the
-// candidate axis: flag byte; INT32_MAX for deadlocked pairs; bubble[s] = makespan -
-// M (t_f[s] + t_b[s]) (idle time of stage s inside [0, makespan]) for the others.
+// deadlocked in the candidate-major scratch mk_t[C][K].  Each block transposes one tile of
+// 64 candidates x 64 scenarios through LDS and writes, coalesced along the candidate axis:
+// makespan, flag byte, and bubble[s] = makespan - M (t_f[s] + t_b[s]) (idle time of stage s
+// inside [0, makespan]); INT32_MAX for deadlocked pairs.
 __global__ __launch_bounds__(kBlock) void k_eval_epilogue(KArgs a) {
+    __shared__ int tile[64][65];
+    __shared__ int tau[ADAPTRA_MAX_STAGES];
+    const long long ctiles = (a.C + 63) / 64;
+    const long long c0 = ((long long)blockIdx.x % ctiles) * 64;
+    const long long k0 = ((long long)blockIdx.x / ctiles) * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    if (threadIdx.x < a.S) tau[threadIdx.x] = a.t_f[threadIdx.x] + a.t_b[threadIdx.x];
+    for (int i = ty; i < 64; i += kWavesPerBlock) {          // row = candidate, lanes = scenarios
+        const long long c = c0 + i, k = k0 + tx;
+        if (c < a.C && k < a.K && !(a.cand_flag[c] & ADAPTRA_FLAG_DEADLOCK)) tile[i][tx] = a.mk_t[c * a.K + k];
+    }
+    __syncthreads();
     const long long P = a.C * a.K;
-    const long long stride = (long long)gridDim.x * kBlock;
-    for (long long p = (long long)blockIdx.x * kBlock + threadIdx.x; p < P; p += stride) {
-        const long long c = p % a.C;
-        const int flag = a.cand_flag[c];
-        const bool dead = flag & ADAPTRA_FLAG_DEADLOCK;
+    const long long c = c0 + tx;
+    if (c >= a.C) return;
+    const int flag = a.cand_flag[c];
+    const bool dead = flag & ADAPTRA_FLAG_DEADLOCK;
+    for (int i = ty; i < 64; i += kWavesPerBlock) {          // row = scenario, lanes = candidates
+        const long long k = k0 + i;
+        if (k >= a.K) break;
+        const long long p = k * a.C + c;
+        const int mk = dead ? INT32_MAX : tile[tx][i];
+        a.out_makespan[p] = mk;
         a.out_feasible[p] = (unsigned char)flag;
-        int mk = INT32_MAX;
-        if (dead) a.out_makespan[p] = INT32_MAX;
-        else mk = a.out_makespan[p];
-        if (a.out_bubble) {
-            for (int s = 0; s < a.S; ++s)
-                a.out_bubble[(long long)s * P + p] = dead ? INT32_MAX : mk - a.M * (a.t_f[s] + a.t_b[s]);
-        }
+        if (a.out_bubble)
+            for (int s = 0; s < a.S; ++s) a.out_bubble[(long long)s * P + p] = dead ? INT32_MAX : mk - a.M * tau[s];
     }
 }
 
@@ -254,6 +276,11 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
     int *last = a.scratch + tid;
     int *wl = a.scratch + (long long)S * NT + tid;
     int *fwd = a.scratch + 2ll * S * NT + tid;
+    if (!a.general_all) {      // only the candidates the register/LDS kernel left over: often none
+        int mine = 0;
+        for (int cls = a.cls_hi + 1; cls <= kNumRingClasses; ++cls) mine += a.status[16 + cls];
+        if (mine == 0) return;
+    }
     const long long ctiles = (a.C + 63) / 64;
     const long long ntiles = a.K * ctiles;
     const long long nwaves = NT >> 6;
@@ -306,8 +333,7 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
                     }
                 }
             } else {
-                const long long p = k * a.C + c;
-                a.out_makespan[p] = mk;          // bubbles follow in k_eval_epilogue
+                a.mk_t[c * a.K + k] = mk;        // transposed and completed by k_eval_epilogue
             }
         }
         if (BEST) {
@@ -524,7 +550,9 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? 4 : 6) void k_resolve_scen_lanes(
                     }
                 }
             } else if (kvalid) {
-                kargs()->out_makespan[k * kargs()->C + c] = mk;   // bubbles follow in k_eval_epilogue
+                // candidate-major scratch: the 64 lanes write 256 contiguous bytes;
+                // k_eval_epilogue transposes into out_makespan and adds bubbles and flags
+                kargs()->mk_t[c * K + k] = mk;
             }
         }
         if (BEST && kvalid && key != kNoKey) atomicMin(&kargs()->keys[k], key);
@@ -572,7 +600,7 @@ __global__ __launch_bounds__(kBlock) void k_check_inputs(KArgs a) {
 }
 
 __global__ void k_zero_status(KArgs a) {
-    if (threadIdx.x < 4) a.status[threadIdx.x] = 0;
+    if (threadIdx.x < 32) a.status[threadIdx.x] = 0;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -584,7 +612,7 @@ hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Workspace {
-    size_t off_flag, off_class, off_wq, off_keys, off_status, off_scratch, total;
+    size_t off_flag, off_class, off_wq, off_keys, off_status, off_scratch, off_mkt, total;
     int wq_stride;
     long long general_threads;
 };
@@ -611,6 +639,7 @@ bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws) {
     ws->off_keys = o;    o += align256((size_t)K * 8);
     ws->off_status = o;  o += 256;
     ws->off_scratch = o; o += align256((size_t)ws->general_threads * (2 * S + M) * 4);
+    ws->off_mkt = o;     o += align256((size_t)C * (size_t)K * 4);
     ws->total = o;
     return true;
 }
@@ -670,6 +699,7 @@ void fill_args(KArgs *a, const adaptra_params_t *p, const adaptra_candidates_t *
     a->keys = (unsigned long long *)(base + ws.off_keys);
     a->status = (int *)(base + ws.off_status);
     a->scratch = (int *)(base + ws.off_scratch);
+    a->mk_t = (int *)(base + ws.off_mkt);
     a->n_ktiles = (int)((sc->n + 63) / 64);
     a->n_chunks = (cd->n + kChunk - 1) / kChunk;
 }
@@ -809,11 +839,15 @@ int adaptra_eval(const adaptra_params_t *params, const adaptra_candidates_t *can
     a.out_makespan = out_makespan;
     a.out_bubble = out_bubble;
     a.out_feasible = out_feasible;
+    hipLaunchKernelGGL(k_zero_status, dim3(1), dim3(64), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_prepass, dim3(grid_for(a.C, INT32_MAX)), dim3(kBlock), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
     rc = launch_resolve<false>(a, ws, cands->w_bound, st);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_eval_epilogue, dim3(grid_for(a.C * a.K, 1 << 16)), dim3(kBlock), 0, st, a);
+    const long long tiles = ((a.C + 63) / 64) * ((a.K + 63) / 64);
+    if (tiles > INT32_MAX) return ADAPTRA_EINVAL;
+    hipLaunchKernelGGL(k_eval_epilogue, dim3((unsigned)tiles), dim3(kBlock), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
     return ADAPTRA_OK;
 }
@@ -840,6 +874,8 @@ int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *can
     a.hist_bins = params->hist_bins;
     a.hist_shift = params->hist_shift;
     a.hist_in_lds = (size_t)a.S * a.hist_bins * 4 <= (size_t)kMaxLdsHistBytes;
+    hipLaunchKernelGGL(k_zero_status, dim3(1), dim3(64), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_prepass, dim3(grid_for(a.C, INT32_MAX)), dim3(kBlock), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_best_init, dim3(grid_for(a.K + (long long)a.S * a.hist_bins, 4096)), dim3(kBlock), 0, st, a);
