@@ -37,7 +37,13 @@ constexpr int kClassDead = 255;           // deadlocked: never resolved
 constexpr int kClassDeep = 254;           // warm-up depth beyond the LDS ring: general kernel
 constexpr int kNumRingClasses = 8;        // ring of 8 * (class + 1) slots
 constexpr int kMaxLdsHistBytes = 16384;
-constexpr int kPrefetchStages = 8;        // ring reads run this many stages ahead of their use
+#ifndef ADAPTRA_PD
+#define ADAPTRA_PD 4
+#endif
+#ifndef ADAPTRA_WAVES32
+#define ADAPTRA_WAVES32 4
+#endif
+constexpr int kPrefetchStages = ADAPTRA_PD;        // ring reads run this many stages ahead of their use
 constexpr unsigned long long kNoKey = ~0ull;
 
 struct KArgs {
@@ -70,14 +76,19 @@ __device__ __forceinline__ unsigned ring_next(unsigned t, unsigned bias) {
     return t;
 }
 
-// bit `kBit` of the uniform 64-bit mask set ? b : a.  One SALU op spreads the bit over vcc
-// (a signed one-bit field extract), one VALU op selects; a branch would cost more issue
-// slots than it saves, hoisted lane masks two SGPRs per stage.
+// The two uniform chores of a forward step, in one asm block so that the scheduler keeps
+// them next to the step's VALU work (separate asm statements get s_nop spacers):
+//   - returns bit `kBit` of the 64-bit mask set ? b : a.  One SALU op spreads the bit over
+//     vcc (a signed one-bit field extract), one VALU op selects; a branch around a move
+//     measured slower, hoisted lane masks would need two SGPRs per stage.
+//   - advances the stage's ring offset `t` by one slot (see ring_next).
 template <int kBit>
-__device__ __forceinline__ int select_by_bit(unsigned long long mask, int a, int b) {
+__device__ __forceinline__ int select_by_bit_and_advance(unsigned long long mask, int a, int b,
+                                                         unsigned &t, unsigned bias) {
     int o;
-    asm("s_bfe_i64 vcc, %1, %2\n\tv_cndmask_b32 %0, %3, %4, vcc"
-        : "=v"(o) : "s"(mask), "n"(kBit | (1 << 16)), "v"(a), "v"(b) : "scc", "vcc");
+    asm("s_bfe_i64 vcc, %2, %3\n\tv_cndmask_b32 %0, %4, %5, vcc\n\t"
+        "s_add_u32 %1, %1, 0x100\n\ts_cmov_b32 %1, %6"
+        : "=v"(o), "+s"(t) : "s"(mask), "n"(kBit | (1 << 16)), "v"(a), "v"(b), "s"(bias) : "scc", "vcc");
     return o;
 }
 
@@ -368,7 +379,7 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
 // pipelined: each is issued several stages (or, for the first stages, a whole backward
 // sweep) ahead of its use, so the LDS latency does not stall every stage.
 template <int S, bool BEST>
-__global__ __launch_bounds__(kBlock, S >= 32 ? 4 : 6) void k_resolve_scen_lanes(KArgs) {
+__global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resolve_scen_lanes(KArgs) {
     // The arguments are read through kargs() where they are needed (see there), never
     // through the by-value parameter.
     extern __shared__ int lds[];
@@ -446,14 +457,16 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? 4 : 6) void k_resolve_scen_lanes(
 // m and the stage's offset moves on to slot m+1.
 #define ADAPTRA_F_OP(s, e)                                                      \
     do {                                                                        \
+        const unsigned slot = ring + soff[s];                                   \
         if constexpr ((s) == 0) {                                               \
             L[0] += (e);                                                        \
+            soff[0] = ring_next(soff[0], bias);                                 \
         } else {                                                                \
             const int t = L[s] + (e);                                           \
-            L[s] = imax(t, select_by_bit<(s)>(zmask, x[s], L[(s) > 0 ? (s) - 1 : 0])); \
+            L[s] = imax(t, select_by_bit_and_advance<(s)>(zmask, x[s], L[(s) > 0 ? (s) - 1 : 0], \
+                                                          soff[s], bias));      \
         }                                                                       \
-        if constexpr ((s) < S - 1) *(lds_int *)(ring + soff[s]) = L[s];         \
-        soff[s] = ring_next(soff[s], bias);                                     \
+        if constexpr ((s) < S - 1) *(lds_int *)slot = L[s];                     \
     } while (0)
 // Reads run kPD stages ahead of their use: stage s issues the read of stage s+kPD ...
 #define ADAPTRA_READ_AHEAD(s)                                                   \
