@@ -54,6 +54,20 @@ class HipEvents:
         self.hip.hipEventDestroy(ev)
 
 
+def traffic_from_profile(S: int, config: int):
+    """HBM bytes per launch of the resolve kernel, as measured with rocprofv3 (FETCH_SIZE and
+    WRITE_SIZE, scaled by a copy of known size) and recorded in the committed summary; None
+    if there is no summary for this workload.  It cannot be measured from inside this process."""
+    path = os.path.join(ROOT, "profiles", f"resolve_scen_lanes_S{S}_config{config}.txt")
+    try:
+        for line in open(path):
+            if line.strip().startswith("traffic_bytes_per_launch["):
+                return int(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(wl, target_seconds: float = 15.0) -> dict:
     """The oracle as it stands, on the host cores, on a seeded sample of this workload's pairs."""
     from oracle import oracle
@@ -161,6 +175,17 @@ def main():
     t_eval = timed(lambda: binding.adaptra_eval(prob, mk, bub, fl, want_bubble=bub is not None, workspace=ws))
     t_best = timed(lambda: binding.adaptra_best(prob, bidx, bmk, bbub, hist, workspace=ws))
 
+    # sustained int32 VALU rate of this GPU (independent v_add_u32 / v_max_i32 chains, no memory)
+    scr = torch.zeros(64, dtype=torch.int32, device=dev)
+    binding.adaptra_valu_probe(8192, 100, scr)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    probe_ops = binding.adaptra_valu_probe(8192, 1000, scr)
+    e1.record()
+    torch.cuda.synchronize()
+    measured_peak = probe_ops / (e0.elapsed_time(e1) * 1e-3)
+
     flags = fl[0].cpu().numpy()                    # the flag depends on the candidate only
     n_live = int(((flags & 2) == 0).sum())
     n_feasible = int((flags == 1).sum())
@@ -190,7 +215,8 @@ def main():
         "best": {"ms": t_best * 1e3, "evaluations_per_s": C * K / t_best, "resolved_ops_per_s": ops_best / t_best},
         "roofline": {"bound": "alu", "kernel": f"k_resolve_scen_lanes<{S}, eval>",
                      "achieved": achieved / 1e12, "peak": INT32_VALU_PEAK / 1e12, "unit": "Tint32op/s",
-                     "frac": achieved / INT32_VALU_PEAK, "traffic": None,
+                     "frac": achieved / INT32_VALU_PEAK, "traffic": traffic_from_profile(S, args.config),
+                     "peak_measured": measured_peak / 1e12, "frac_of_measured": achieved / measured_peak,
                      "kernel_ms": kernel_avg_ms, "resolved_ops_per_launch": ops_eval,
                      "algorithmic_ops_per_resolved_op": 3},
     }

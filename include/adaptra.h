@@ -155,6 +155,13 @@ int adaptra_set_kernel_mode(int mode);
  * exactly those launches.  Pass NULL, NULL to switch it off.  Always returns ADAPTRA_OK. */
 int adaptra_set_resolve_events(void *before, void *after);
 
+/* Measurement aid for callers that report a roofline (bench.py): enqueue a kernel of
+ * `blocks` x 256 threads in which every lane performs iters x 512 independent int32
+ * VALU operations (v_add_u32 / v_max_i32 pairs, the two ops of the recurrence), with no
+ * memory traffic.  `scratch` is a DEVICE int32 (never written in practice).  *lane_ops
+ * (HOST, may be NULL) receives the number of lane operations enqueued.  Asynchronous. */
+int adaptra_valu_probe(int32_t blocks, int32_t iters, int32_t *scratch, void *stream, int64_t *lane_ops);
+
 /* hipError_t (as int) of the last failed HIP call on this thread, 0 if none. */
 int adaptra_last_hip_error(void);
 

@@ -22,7 +22,7 @@ FLAG_FEASIBLE, FLAG_DEADLOCK, FLAG_MEMCAP = 1, 2, 4
 INT32_MAX = 2 ** 31 - 1
 
 EXPORTS = ("adaptra_workspace_bytes", "adaptra_check_inputs", "adaptra_eval", "adaptra_best",
-           "adaptra_set_kernel_mode", "adaptra_set_resolve_events", "adaptra_last_hip_error",
+           "adaptra_set_kernel_mode", "adaptra_set_resolve_events", "adaptra_valu_probe", "adaptra_last_hip_error",
            "adaptra_version")
 
 
@@ -74,6 +74,8 @@ def load() -> ctypes.CDLL:
         lib.adaptra_set_kernel_mode.argtypes = [ctypes.c_int]
         lib.adaptra_set_resolve_events.restype = ctypes.c_int
         lib.adaptra_set_resolve_events.argtypes = [vp, vp]
+        lib.adaptra_valu_probe.restype = ctypes.c_int
+        lib.adaptra_valu_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp, ctypes.POINTER(ctypes.c_int64)]
         lib.adaptra_last_hip_error.restype = ctypes.c_int
         lib.adaptra_version.restype = ctypes.c_int
         _lib = lib
@@ -208,6 +210,14 @@ def adaptra_set_kernel_mode(mode: int) -> int:
 def adaptra_set_resolve_events(before: Optional[int], after: Optional[int]) -> int:
     """before / after: raw hipEvent_t handles (ints) or None."""
     return int(load().adaptra_set_resolve_events(before, after))
+
+
+def adaptra_valu_probe(blocks: int, iters: int, scratch, stream=None) -> int:
+    """Enqueue the integer-VALU rate probe; returns the number of lane operations enqueued."""
+    n = ctypes.c_int64(0)
+    rc = load().adaptra_valu_probe(int(blocks), int(iters), scratch.data_ptr(), _stream(stream), ctypes.byref(n))
+    _raise(rc, "adaptra_valu_probe")
+    return int(n.value)
 
 
 def adaptra_version() -> int:

@@ -617,6 +617,27 @@ __global__ void k_zero_status(KArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Measurement aid: sustained rate of the two integer VALU ops the recurrence is made of.
+// Every lane runs 8 independent chains of  v = max(v + c, d)  (one v_add_u32, one
+// v_max_i32 each), 8 x 2 x 32 ops per loop trip, so neither latency nor memory limits it.
+__global__ __launch_bounds__(kBlock) void k_valu_probe(int iters, int c, int d, int *out) {
+    int v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = threadIdx.x + j;
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int u = 0; u < 32; ++u) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = imax(v[j] + c, d + j);
+        }
+    }
+    int r = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) r ^= v[j];
+    if (r == 0x7fffffff) out[0] = r;          // practically never: keeps the chains alive
+}
+
+// ---------------------------------------------------------------------------------------
 // Host side
 thread_local int g_last_hip_error = 0;
 int g_kernel_mode = 0;
@@ -910,6 +931,14 @@ int adaptra_set_kernel_mode(int mode) {
 int adaptra_set_resolve_events(void *before, void *after) {
     g_ev_before = (hipEvent_t)before;
     g_ev_after = (hipEvent_t)after;
+    return ADAPTRA_OK;
+}
+
+int adaptra_valu_probe(int32_t blocks, int32_t iters, int32_t *scratch, void *stream, int64_t *lane_ops) {
+    if (blocks < 1 || iters < 1 || !scratch) return ADAPTRA_EINVAL;
+    hipLaunchKernelGGL(k_valu_probe, dim3(blocks), dim3(kBlock), 0, (hipStream_t)stream, iters, 1, -5, scratch);
+    ADAPTRA_LAUNCH_CHECK();
+    if (lane_ops) *lane_ops = (int64_t)blocks * kBlock * (int64_t)iters * 32 * 8 * 2;
     return ADAPTRA_OK;
 }
 
