@@ -68,25 +68,31 @@ def traffic_from_profile(S: int, config: int):
     return None
 
 
-def cpu_baseline(wl, target_seconds: float = 15.0) -> dict:
-    """The oracle as it stands, on the host cores, on a seeded sample of this workload's pairs."""
+def cpu_baseline(wl, target_seconds: float = 16.0) -> dict:
+    """The oracle as it stands, on the host cores, on a seeded sample of this workload's pairs:
+    all threads for about `target_seconds`, then one thread on a sixteenth of that sample."""
     from oracle import oracle
     from paper_2504_19232_amd import workloads
     threads = oracle.default_threads()
-    n = 512
     pc, ps = workloads.sample_pairs(4242, wl.n_cand, wl.n_scen, 1 << 22)
+    n0 = 1 << 14
     t0 = time.perf_counter()
-    oracle.eval_workload(wl, pair_cand=pc[:n], pair_scen=ps[:n], threads=threads)
+    oracle.eval_workload(wl, pair_cand=pc[:n0], pair_scen=ps[:n0], threads=threads)
     probe = time.perf_counter() - t0
-    n = int(min(len(pc), max(n, n * target_seconds / max(probe, 1e-3))))
+    n = int(min(len(pc), max(n0, n0 * target_seconds / max(probe, 1e-3))))
     t0 = time.perf_counter()
     r = oracle.eval_workload(wl, pair_cand=pc[:n], pair_scen=ps[:n], threads=threads)
     dt = time.perf_counter() - t0
     live = int(((r["flag"] & 2) == 0).sum())
+    n1 = max(256, n // (16 * max(threads, 1)))
+    t0 = time.perf_counter()
+    oracle.eval_workload(wl, pair_cand=pc[:n1], pair_scen=ps[:n1], threads=1)
+    dt1 = time.perf_counter() - t0
     return {"value": n / dt, "unit": "evaluations/s", "cores": threads, "kind": "oracle",
             "sample": f"{n} seeded random pairs of the workload ({live} not deadlocked), "
                       f"event-driven simulation incl. bubbles, {dt:.1f} s",
-            "resolved_ops_per_s": live * 2.0 * wl.S * wl.M / dt}
+            "resolved_ops_per_s": live * 2.0 * wl.S * wl.M / dt,
+            "one_core": {"value": n1 / dt1, "sample_pairs": n1, "seconds": dt1}}
 
 
 def main():

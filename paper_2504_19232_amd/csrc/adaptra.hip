@@ -30,8 +30,14 @@
 namespace {
 
 constexpr int kNeg = -(1 << 30);          // "no earlier op": below every shifted time
-constexpr int kChunk = 16;                // candidates one wavefront works through
-constexpr int kWavesPerBlock = 4;
+#ifndef ADAPTRA_CHUNK
+#define ADAPTRA_CHUNK 16
+#endif
+constexpr int kChunk = ADAPTRA_CHUNK;      // candidates one wavefront works through
+#ifndef ADAPTRA_WPB
+#define ADAPTRA_WPB 4
+#endif
+constexpr int kWavesPerBlock = ADAPTRA_WPB;
 constexpr int kBlock = 64 * kWavesPerBlock;
 constexpr int kClassDead = 255;           // deadlocked: never resolved
 constexpr int kClassDeep = 254;           // warm-up depth beyond the LDS ring: general kernel
@@ -406,22 +412,18 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resol
         const long long k = (long long)tile * 64 + lane;
         const bool kvalid = k < K;
         const long long kk = kvalid ? k : K - 1;
-        // t_f + t_b of every stage: SGPRs.  t_f and t_b themselves, needed only while the
-        // pipeline fills and drains, share one VGPR each (lane s holds stage s) and are
-        // fetched with v_readlane where used.
-        int tau[S];
-        {
-            const int *t_f = kargs()->t_f, *t_b = kargs()->t_b;
-#pragma unroll
-            for (int s = 0; s < S; ++s) tau[s] = uni(t_f[s]) + uni(t_b[s]);
-        }
+        // t_f and t_b of the stages share one VGPR each (lane s holds stage s); the addend a
+        // stage currently needs is kept in an SGPR (add_f below) and switched with v_readlane
+        // when the stage changes phase.
         const int tf_lanes = kargs()->t_f[lane < S ? lane : 0];
         const int tb_lanes = kargs()->t_b[lane < S ? lane : 0];
+        const int tau0 = uni(kargs()->t_f[0]) + uni(kargs()->t_b[0]);
         int q[S > 1 ? S - 1 : 1];
         {
-            const int *cf = kargs()->cf, *cb = kargs()->cb;
+            const int *cf = kargs()->cf, *cb = kargs()->cb, *t_f = kargs()->t_f, *t_b = kargs()->t_b;
 #pragma unroll
-            for (int s = 0; s + 1 < S; ++s) q[s] = cf[s * K + kk] + cb[s * K + kk] + tau[s + 1];
+            for (int s = 0; s + 1 < S; ++s)
+                q[s] = cf[s * K + kk] + cb[s * K + kk] + uni(t_f[s + 1]) + uni(t_b[s + 1]);
         }
 
         unsigned long long key = kNoKey;
@@ -443,11 +445,14 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resol
             const unsigned long long zmask = __ballot(lane >= 1 && lane < S && wq_prev == wq_lanes);
             int L[S], x[S];
             unsigned soff[S];     // biased ring offset of the stage's next forward micro-batch
+            int add_f[S];         // what the stage's next op adds to L[s]: t_f while the pipeline
+                                  // fills, t_f + t_b in steady state, t_b once out of forwards
 #pragma unroll
             for (int s = 0; s < S; ++s) {
                 L[s] = kNeg;
                 x[s] = 0;
                 soff[s] = bias;   // micro-batch 0 sits in slot 0
+                add_f[s] = __builtin_amdgcn_readlane(tf_lanes, s);
             }
             L[0] = -__builtin_amdgcn_readlane(tf_lanes, 0);
 
@@ -501,18 +506,20 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resol
                     while (nv < S && __builtin_amdgcn_readlane(wq_lanes, nv) + r >= 0) ++nv;
                     stages_below<0, S>(nv, ADAPTRA_STAGE_LAMBDA(si) {
                         constexpr int s = decltype(si)::value;
-                        ADAPTRA_F_OP(s, __builtin_amdgcn_readlane(tf_lanes, s));
+                        ADAPTRA_F_OP(s, add_f[s]);
                         ADAPTRA_READ_AHEAD(s);
                     });
                     ADAPTRA_READ_NEXT_ROUND();
                 }
             }
             ADAPTRA_B_SWEEP();                    // B(s, 0): each after a forward
+#pragma unroll
+            for (int s = 0; s < S; ++s) add_f[s] += __builtin_amdgcn_readlane(tb_lanes, s);
             // steady rounds r = 1 .. M-1-W: F after B, B after F on every stage
             for (int r = M - 1 - W; r > 0; --r) {
                 stages_up<0, S>(ADAPTRA_STAGE_LAMBDA(si) {
                     constexpr int s = decltype(si)::value;
-                    ADAPTRA_F_OP(s, tau[s]);
+                    ADAPTRA_F_OP(s, add_f[s]);
                     ADAPTRA_READ_AHEAD(s);
                 });
                 ADAPTRA_READ_NEXT_ROUND();
@@ -523,10 +530,11 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resol
             {
                 int done = 0;
                 for (int r = M - W; r <= M - 1; ++r) {
+                    const int done_before = done;
                     while (done < S && __builtin_amdgcn_readlane(wq_lanes, done) + r > M - 1) ++done;
                     stages_up<0, S>(ADAPTRA_STAGE_LAMBDA(si) {
                         constexpr int s = decltype(si)::value;
-                        if (s >= done) ADAPTRA_F_OP(s, tau[s]);
+                        if (s >= done) ADAPTRA_F_OP(s, add_f[s]);
                         ADAPTRA_READ_AHEAD(s);
                     });
                     ADAPTRA_READ_NEXT_ROUND();
@@ -534,7 +542,10 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resol
                     stages_down<S - 1, 0>(ADAPTRA_STAGE_LAMBDA(si) {
                         constexpr int s = decltype(si)::value;
                         int prev = L[s];
-                        if (s < done) prev += __builtin_amdgcn_readlane(tb_lanes, s);   // B after B
+                        if (s < done) {                                   // B after B
+                            if (s >= done_before) add_f[s] -= __builtin_amdgcn_readlane(tf_lanes, s);
+                            prev += add_f[s];
+                        }
                         L[s] = (s == S - 1) ? prev : imax(prev, carry + q[s < S - 1 ? s : 0]);
                         carry = L[s];
                     });
@@ -545,7 +556,7 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resol
 #undef ADAPTRA_READ_NEXT_ROUND
 #undef ADAPTRA_B_SWEEP
 
-            const int mk = L[0] + tau[0];
+            const int mk = L[0] + tau0;
             if (BEST) {
                 if (kvalid) {
                     const unsigned long long cand = ((unsigned long long)(unsigned)mk << 32) | (unsigned)c;
@@ -555,7 +566,8 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resol
                         unsigned long long *const hist = kargs()->hist;
 #pragma unroll
                         for (int s = 0; s < S; ++s) {
-                            int b = (mk - M * tau[s]) >> shift;
+                            const int tau_s = __builtin_amdgcn_readlane(tf_lanes, s) + __builtin_amdgcn_readlane(tb_lanes, s);
+                            int b = (mk - M * tau_s) >> shift;
                             b = b > bins - 1 ? bins - 1 : b;
                             if (lds_hist) atomicAdd(&hist_lds[s * bins + b], 1u);
                             else atomicAdd(&hist[s * bins + b], 1ull);
