@@ -141,6 +141,26 @@ int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *can
                  uint64_t *out_hist,
                  void *workspace, size_t workspace_bytes, void *stream);
 
+/* The paper's analytic planning (Section 4.2), one result per scenario, as a cheap seed and
+ * as the reference point for the exhaustive search of adaptra_best.  Every output is
+ * optional (NULL to skip) and uses w = x - 1.
+ *   x_max             Algorithm 1: activations a device can hold, floor(M / M^F), >= 1
+ *   w_current         DEVICE int32 [S]: the schedule in use, for the Eq. (1) test (required
+ *                     iff out_not_absorbed is given); typically out_w_init of an earlier call
+ *   out_w_init        DEVICE int32 [S]: Algorithm 1 (initial planning): x_0 = x_max, slack
+ *                     spread as evenly as possible, x_{S-1} = 1
+ *   out_w_adapted     DEVICE int32 [S][n_scen]: Algorithm 2 (dynamic adaptation):
+ *                     Delta_i = min(M - 2S, max(ceil((t_f[i] + t_b[i] + c_fwd[i] + c_bwd[i]) /
+ *                     (t_f[i+1] + t_b[i+1])), 2)), floored at 0, x_i = min(x_{i+1} + Delta_i, M).
+ *                     The layout is that of adaptra_candidates_t.w with n = n_scen.
+ *   out_not_absorbed  DEVICE uint8 [S-1][n_scen]: 1 where Eq. (1) fails for w_current, i.e. the
+ *                     link's delay would cascade: t_f[i] + t_b[i] + c_fwd[i] + c_bwd[i] >
+ *                     (w_current[i] - w_current[i+1]) (t_f[i+1] + t_b[i+1])
+ * params->mem_cap and the histogram fields are ignored.  Asynchronous on `stream`. */
+int adaptra_seed(const adaptra_params_t *params, const adaptra_scenarios_t *scens, int32_t x_max,
+                 const int32_t *w_current, int32_t *out_w_init, int32_t *out_w_adapted,
+                 uint8_t *out_not_absorbed, void *stream);
+
 /* Kernel selection, process-wide; for tests and measurements.
  *   0  automatic (default): register/LDS kernel where S and the scenario count suit
  *      it, the general kernel otherwise

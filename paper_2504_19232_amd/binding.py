@@ -21,7 +21,7 @@ ERROR_NAMES = {0: "ADAPTRA_OK", 1: "ADAPTRA_EINVAL", 2: "ADAPTRA_EWORKSPACE", 3:
 FLAG_FEASIBLE, FLAG_DEADLOCK, FLAG_MEMCAP = 1, 2, 4
 INT32_MAX = 2 ** 31 - 1
 
-EXPORTS = ("adaptra_workspace_bytes", "adaptra_check_inputs", "adaptra_eval", "adaptra_best",
+EXPORTS = ("adaptra_workspace_bytes", "adaptra_check_inputs", "adaptra_eval", "adaptra_best", "adaptra_seed",
            "adaptra_set_kernel_mode", "adaptra_set_resolve_events", "adaptra_valu_probe", "adaptra_last_hip_error",
            "adaptra_version")
 
@@ -70,6 +70,8 @@ def load() -> ctypes.CDLL:
         lib.adaptra_eval.argtypes = [P, C, Sc, vp, vp, vp, vp, sz, vp]
         lib.adaptra_best.restype = ctypes.c_int
         lib.adaptra_best.argtypes = [P, C, Sc, vp, vp, vp, vp, vp, sz, vp]
+        lib.adaptra_seed.restype = ctypes.c_int
+        lib.adaptra_seed.argtypes = [P, Sc, ctypes.c_int32, vp, vp, vp, vp, vp]
         lib.adaptra_set_kernel_mode.restype = ctypes.c_int
         lib.adaptra_set_kernel_mode.argtypes = [ctypes.c_int]
         lib.adaptra_set_resolve_events.restype = ctypes.c_int
@@ -201,6 +203,22 @@ def adaptra_best(prob: Problem, out_best_idx=None, out_best_makespan=None, out_b
                              _ptr(out_hist), ws.data_ptr(), ws.numel(), _stream(stream))
     _raise(rc, "adaptra_best")
     return out_best_idx, out_best_makespan, out_best_bubble, out_hist
+
+
+def adaptra_seed(prob: Problem, x_max: int = 1, w_current=None, *, want_init: bool = True,
+                 want_adapted: bool = True, want_not_absorbed: bool = False, stream=None):
+    """Enqueue the analytic planning; returns (w_init [S] | None, w_adapted [S,K] | None,
+    not_absorbed [S-1,K] | None)."""
+    import torch
+    dev = prob.device
+    w_init = torch.empty(prob.S, dtype=torch.int32, device=dev) if want_init else None
+    w_ad = torch.empty((prob.S, prob.K), dtype=torch.int32, device=dev) if want_adapted else None
+    na = torch.empty((max(prob.S - 1, 0), prob.K), dtype=torch.uint8, device=dev) if want_not_absorbed else None
+    _check_i32(w_current, "w_current", (prob.S,))
+    rc = load().adaptra_seed(ctypes.byref(prob.params), ctypes.byref(prob.scens), int(x_max), _ptr(w_current),
+                             _ptr(w_init), _ptr(w_ad), _ptr(na), _stream(stream))
+    _raise(rc, "adaptra_seed")
+    return w_init, w_ad, na
 
 
 def adaptra_set_kernel_mode(mode: int) -> int:

@@ -17,6 +17,7 @@
 //                        sentinels for deadlocked pairs (one coalesced streaming pass)
 //   k_best_init / k_best_finalize   search keys and histogram set-up / decoding
 //   k_check_inputs       range scan for adaptra_check_inputs
+//   k_seed               the paper's analytic planning (Algorithm 1, Algorithm 2, Eq. (1))
 //
 // Order of evaluation used by both resolve kernels: with w non-increasing over stages
 // (Lemma 1) the rounds r = -w[0] .. M-1, each a forward sweep s = 0..S-1 over
@@ -629,6 +630,67 @@ __global__ void k_zero_status(KArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
+// The paper's analytic planning, one thread per scenario (Section 4.2).
+//   Algorithm 1 (initial planning, scenario independent; thread 0 only): x_0 = x_max, the
+//     slack x_max - 1 spread over the S - 1 links as evenly as possible, x_{S-1} = 1.
+//   Algorithm 2 (dynamic adaptation): x_{S-1} = 1, and from the last link backwards
+//     Delta_i = min(M - 2S, max(ceil((t_f[i] + t_b[i] + c_fwd[i] + c_bwd[i]) / (t_f[i+1] + t_b[i+1])), 2)),
+//     floored at 0 (Lemma 1), x_i = min(x_{i+1} + Delta_i, M); a zero denominator lets the clip decide.
+//   Eq. (1) for the schedule w_cur: link i absorbs its delay iff
+//     t_f[i] + t_b[i] + c_fwd[i] + c_bwd[i] <= (w_cur[i] - w_cur[i+1]) (t_f[i+1] + t_b[i+1]).
+// Outputs are w = x - 1.
+struct SeedArgs {
+    int S, M, x_max;
+    long long K;
+    const int *t_f, *t_b, *cf, *cb, *w_cur;
+    int *w_init, *w_adapted;
+    unsigned char *not_absorbed;
+};
+
+__global__ __launch_bounds__(kBlock) void k_seed(SeedArgs a) {
+    const long long k = (long long)blockIdx.x * kBlock + threadIdx.x;
+    const int S = a.S;
+    if (k == 0 && a.w_init) {
+        int x = a.x_max;
+        a.w_init[0] = x - 1;
+        if (S > 1) {
+            const int avg = (a.x_max - 1) / (S - 1), r = (a.x_max - 1) % (S - 1);
+            for (int i = 1; i < S; ++i) {
+                x -= (i <= r) ? avg + 1 : avg;
+                a.w_init[i] = x - 1;
+            }
+        }
+    }
+    if (k >= a.K) return;
+    if (a.w_adapted) {
+        int x = 1;
+        a.w_adapted[(long long)(S - 1) * a.K + k] = 0;
+        const int clip = a.M - 2 * S;
+        for (int i = S - 2; i >= 0; --i) {
+            const long long num = (long long)a.t_f[i] + a.t_b[i] + a.cf[(long long)i * a.K + k] + a.cb[(long long)i * a.K + k];
+            const long long den = (long long)a.t_f[i + 1] + a.t_b[i + 1];
+            long long d = clip;
+            if (den != 0) {
+                long long ratio = (num + den - 1) / den;
+                if (ratio < 2) ratio = 2;
+                if (ratio < d) d = ratio;
+            }
+            if (d < 0) d = 0;
+            const long long nx = x + d;
+            x = nx > a.M ? a.M : (int)nx;
+            a.w_adapted[(long long)i * a.K + k] = x - 1;
+        }
+    }
+    if (a.not_absorbed) {
+        for (int i = 0; i + 1 < S; ++i) {
+            const long long lhs = (long long)a.t_f[i] + a.t_b[i] + a.cf[(long long)i * a.K + k] + a.cb[(long long)i * a.K + k];
+            const long long rhs = ((long long)a.w_cur[i] - a.w_cur[i + 1]) * ((long long)a.t_f[i + 1] + a.t_b[i + 1]);
+            a.not_absorbed[(long long)i * a.K + k] = lhs <= rhs ? 0 : 1;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // Measurement aid: sustained rate of the two integer VALU ops the recurrence is made of.
 // Every lane runs 8 independent chains of  v = max(v + c, d)  (one v_add_u32, one
 // v_max_i32 each), 8 x 2 x 32 ops per loop trip, so neither latency nor memory limits it.
@@ -929,6 +991,26 @@ int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *can
     rc = launch_resolve<true>(a, ws, cands->w_bound, st);
     if (rc) return rc;
     hipLaunchKernelGGL(k_best_finalize, dim3(grid_for(a.K, INT32_MAX)), dim3(kBlock), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    return ADAPTRA_OK;
+}
+
+int adaptra_seed(const adaptra_params_t *params, const adaptra_scenarios_t *scens, int32_t x_max,
+                 const int32_t *w_current, int32_t *out_w_init, int32_t *out_w_adapted,
+                 uint8_t *out_not_absorbed, void *stream) {
+    if (!params || !scens) return ADAPTRA_EINVAL;
+    const int S = params->S, M = params->M;
+    if (S < 1 || S > ADAPTRA_MAX_STAGES || M < 1 || M > ADAPTRA_MAX_MICROBATCHES) return ADAPTRA_EINVAL;
+    if (scens->n < 1 || scens->n > INT32_MAX || !params->t_f || !params->t_b) return ADAPTRA_EINVAL;
+    if (S > 1 && (!scens->c_fwd || !scens->c_bwd)) return ADAPTRA_EINVAL;
+    if (out_w_init && x_max < 1) return ADAPTRA_EINVAL;
+    if (out_not_absorbed && !w_current) return ADAPTRA_EINVAL;
+    if (!out_w_init && !out_w_adapted && !out_not_absorbed) return ADAPTRA_EINVAL;
+    SeedArgs a;
+    a.S = S; a.M = M; a.x_max = x_max; a.K = scens->n;
+    a.t_f = params->t_f; a.t_b = params->t_b; a.cf = scens->c_fwd; a.cb = scens->c_bwd;
+    a.w_cur = w_current; a.w_init = out_w_init; a.w_adapted = out_w_adapted; a.not_absorbed = out_not_absorbed;
+    hipLaunchKernelGGL(k_seed, dim3(grid_for(a.K, INT32_MAX)), dim3(kBlock), 0, (hipStream_t)stream, a);
     ADAPTRA_LAUNCH_CHECK();
     return ADAPTRA_OK;
 }

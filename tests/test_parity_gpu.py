@@ -287,3 +287,71 @@ def test_w_bound_promise_kept_or_broken(lib, oracle, bound):
     assert np.array_equal(bub.cpu().numpy(), ref["bubble"])
     assert np.array_equal(idx.cpu().numpy(), rbest["best_idx"])
     assert np.array_equal(hist.cpu().numpy().astype(np.uint64), rhist)
+
+
+@pytest.mark.parametrize("index", [0, 1, 2, 3, 4])
+def test_analytic_seed_parity(lib, index):
+    """Algorithm 1, Algorithm 2 and the Eq. (1) test on the GPU against the step-by-step oracle,
+    on the scenario sets of the five configurations."""
+    import torch
+    from oracle import seed
+    b = lib
+    wl = workloads.config(index)
+    prob = b.Problem.from_workload(wl)
+    x_max = wl.S + 3
+    w_init, w_ad, _ = b.adaptra_seed(prob, x_max)
+    _, _, na = b.adaptra_seed(prob, 1, w_init, want_init=False, want_adapted=False, want_not_absorbed=True)
+    torch.cuda.synchronize()
+    w_init, w_ad, na = w_init.cpu().numpy(), w_ad.cpu().numpy(), na.cpu().numpy()
+    ref_init = seed.to_w(seed.get_init_warmup_fwds(wl.S, x_max))
+    assert list(w_init) == ref_init
+    ks = range(wl.n_scen) if wl.n_scen <= 64 else range(0, wl.n_scen, 7)
+    for k in ks:
+        ref = seed.to_w(seed.get_adapted_warmup_fwds(wl.S, wl.M, wl.t_f, wl.t_b, wl.c_fwd[:, k], wl.c_bwd[:, k]))
+        assert list(w_ad[:, k]) == ref, k
+        ok = seed.absorbed(wl.S, wl.t_f, wl.t_b, ref_init, wl.c_fwd[:, k], wl.c_bwd[:, k])
+        assert list(na[:, k]) == [0 if v else 1 for v in ok], k
+
+
+def test_analytic_seed_edge_cases(lib):
+    import torch
+    from oracle import seed
+    b = lib
+    for (sd, S, M, K) in [(1, 1, 5, 3), (2, 2, 3, 70), (3, 6, 9, 10), (4, 64, 200, 5), (5, 5, 4000, 300)]:
+        wl = workloads.random_workload(sd, S, M, 8, K, c_hi=60000)
+        if S > 2:
+            wl.t_f[2] = 0
+            wl.t_b[2] = 0                      # a zero denominator on link 1
+        prob = b.Problem.from_workload(wl)
+        for x_max in (1, 2, S, 3 * S + 1):
+            w_init, w_ad, _ = b.adaptra_seed(prob, x_max)
+            torch.cuda.synchronize()
+            assert list(w_init.cpu().numpy()) == seed.to_w(seed.get_init_warmup_fwds(S, x_max))
+        w_ad = w_ad.cpu().numpy()
+        for k in range(K):
+            ref = seed.to_w(seed.get_adapted_warmup_fwds(S, M, wl.t_f, wl.t_b, wl.c_fwd[:, k], wl.c_bwd[:, k]))
+            assert list(w_ad[:, k]) == ref
+    with pytest.raises(b.AdaptraError):
+        b.adaptra_seed(prob, 0)                  # x_max must be >= 1 for Algorithm 1
+
+
+def test_algorithm2_pick_against_the_exhaustive_search(lib, oracle):
+    """Algorithm 2's vectors are valid candidates: evaluating them (diagonal of the
+    scenario x scenario grid) can never beat adaptra_best over a candidate set that contains them."""
+    import torch
+    b = lib
+    wl = workloads.config(1)
+    wl.mem_cap = None
+    prob = b.Problem.from_workload(wl)
+    _, w_ad, _ = b.adaptra_seed(prob, 1, want_init=False)
+    torch.cuda.synchronize()
+    w_all = np.concatenate([wl.w, w_ad.cpu().numpy()], axis=1)
+    wl2 = workloads.Workload("cfg1+alg2", wl.S, wl.M, wl.t_f, wl.t_b, None, np.ascontiguousarray(w_all), wl.c_fwd, wl.c_bwd)
+    mk, _, fl = gpu_eval(lib, wl2, want_bubble=False)
+    idx, bmk, _, _ = gpu_best(lib, wl2)
+    C0 = wl.n_cand
+    diag = mk[np.arange(wl.n_scen), C0 + np.arange(wl.n_scen)]
+    assert np.all(fl[:, C0:] == 1)              # Algorithm 2 never violates Lemma 1
+    assert np.all(bmk <= diag)
+    ref = oracle.eval_workload(wl2, pair_cand=C0 + np.arange(wl.n_scen), pair_scen=np.arange(wl.n_scen), want_bubble=False)
+    assert np.array_equal(diag, ref["makespan"])
