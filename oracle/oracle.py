@@ -20,6 +20,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "adaptra_oracle.c")
+_SRC_ZB = os.path.join(_HERE, "zb_oracle.c")
 _LIB = os.path.join(_HERE, "libadaptra_oracle.so")
 _lib = None
 
@@ -29,10 +30,11 @@ FLAG_OK, FLAG_DEADLOCK, FLAG_MEMCAP = 1, 2, 4
 
 def build(force: bool = False) -> str:
     """Compile the simulator (gcc, -O2).  Building the checker is not using it."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_ZB))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         tmp = _LIB + f".tmp{os.getpid()}"
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC",
-                               "-pthread", _SRC, "-o", tmp])
+                               "-pthread", _SRC, _SRC_ZB, "-o", tmp])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -54,6 +56,12 @@ def _load():
         lib.adaptra_oracle_timeline.argtypes = [
             ctypes.c_int, ctypes.c_int, p32, p32, p32, p32, p32,
             p64, p64, p64, p64, p64, p32, p64]
+        lib.adaptra_oracle_zb.restype = ctypes.c_int64
+        lib.adaptra_oracle_zb.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, p32, p32, p32, p32, p32, p32, p32,
+                                          p32, p64, p64, p64]
+        lib.adaptra_oracle_zb_batch.restype = ctypes.c_int64
+        lib.adaptra_oracle_zb_batch.argtypes = [ctypes.c_int, ctypes.c_int, p32, p32, p32, ctypes.c_int64, p32,
+                                                ctypes.c_int64, p32, p32, p32, p32]
         _lib = lib
     return _lib
 
@@ -170,3 +178,49 @@ def timeline(S: int, M: int, t_f, t_b, w, cf, cb) -> dict:
         raise ValueError(f"oracle rejected the inputs (code {rc})")
     a.update(idle=idle, peak=peak, makespan=int(mk.value), completed=bool(rc))
     return a
+
+
+# ---------------------------------------------------------------------------------------
+# ZeroBubble-style schedules with F / B / W ops (zb_oracle.c)
+OP_NAMES = "FBW"
+
+
+def zb_simulate(S: int, N: int, t_f, t_b, t_w, cf, cb, *, x=None, order=None) -> dict:
+    """One pair.  With x (warm-up quotas, [S]) the schedule is generated by the two-phase
+    selection policy under the given delays; with order ([S, 3N], ops as type * N + m) that
+    fixed order is executed under the delays.  Returns makespan (None on deadlock), the
+    order run, start / fin [S, 3, N] and idle [S]."""
+    lib = _load()
+    t_f, t_b, t_w = _c32(t_f), _c32(t_b), _c32(t_w)
+    cf = _c32(cf if S > 1 else np.zeros(0))
+    cb = _c32(cb if S > 1 else np.zeros(0))
+    mode = 0 if order is None else 1
+    xs = _c32(x) if x is not None else None
+    od = _c32(order) if order is not None else None
+    out_order = np.empty((S, 3 * N), dtype=np.int32)
+    start = np.empty((S, 3, N), dtype=np.int64)
+    fin = np.empty((S, 3, N), dtype=np.int64)
+    idle = np.empty(S, dtype=np.int64)
+    mk = lib.adaptra_oracle_zb(S, N, mode, _p(t_f, ctypes.c_int32), _p(t_b, ctypes.c_int32), _p(t_w, ctypes.c_int32),
+                               _p(xs, ctypes.c_int32), _p(od, ctypes.c_int32), _p(cf, ctypes.c_int32),
+                               _p(cb, ctypes.c_int32), _p(out_order, ctypes.c_int32), _p(start, ctypes.c_int64),
+                               _p(fin, ctypes.c_int64), _p(idle, ctypes.c_int64))
+    if mk == -2:
+        raise ValueError("zb oracle rejected the inputs")
+    return {"makespan": None if mk < 0 else int(mk), "order": out_order, "start": start, "fin": fin, "idle": idle}
+
+
+def zb_batch(S: int, N: int, t_f, t_b, t_w, x, c_fwd, c_bwd, want_idle: bool = True) -> dict:
+    """Policy-generated schedules for every (candidate, scenario) pair: x [S, C], c [S-1, K];
+    makespan [K, C] (INT32_MAX on deadlock), idle [S, K, C]."""
+    lib = _load()
+    t_f, t_b, t_w, x, c_fwd, c_bwd = _c32(t_f), _c32(t_b), _c32(t_w), _c32(x), _c32(c_fwd), _c32(c_bwd)
+    C, K = int(x.shape[1]), int(c_fwd.shape[1])
+    mk = np.empty((K, C), dtype=np.int32)
+    idle = np.empty((S, K, C), dtype=np.int32) if want_idle else None
+    rc = lib.adaptra_oracle_zb_batch(S, N, _p(t_f, ctypes.c_int32), _p(t_b, ctypes.c_int32), _p(t_w, ctypes.c_int32),
+                                     C, _p(x, ctypes.c_int32), K, _p(c_fwd, ctypes.c_int32), _p(c_bwd, ctypes.c_int32),
+                                     _p(mk, ctypes.c_int32), _p(idle, ctypes.c_int32))
+    if rc != 0:
+        raise ValueError("zb oracle rejected the inputs")
+    return {"makespan": mk, "idle": idle}
