@@ -161,6 +161,30 @@ int adaptra_seed(const adaptra_params_t *params, const adaptra_scenarios_t *scen
                  const int32_t *w_current, int32_t *out_w_init, int32_t *out_w_adapted,
                  uint8_t *out_not_absorbed, void *stream);
 
+/* ZeroBubble-style schedules: three ops per stage and micro-batch -- forward F, backward-input
+ * B, backward-weight W (t_w: DEVICE int32 [S], >= 0) -- generated by the paper's two-phase
+ * operator selection policy (Section 4.3, Algorithm 3; simulation of Algorithm 4 in exact event
+ * time): an idle stage runs forwards only until its warm-up quota x_s = w_s + 1 is used up,
+ * then the available op of highest priority B > F > W, lowest micro-batch first within a type;
+ * F(s,m) becomes available when F(s-1,m) has finished plus c_fwd[s-1], B(s,m) when B(s+1,m)
+ * has finished plus c_bwd[s] (B(S-1,m) when F(S-1,m) has finished), W(s,m) when B(s,m) has
+ * finished.  Precondition beyond adaptra_eval's: t_f, t_b >= 1 (no two dependent ops in one
+ * instant), and 3 M S (max time + max delay) < 2^31.  mem_cap and the histogram fields of
+ * params are ignored; w is clamped into [0, M-1].
+ *   plan_scenario = -1  every pair generates its schedule under its own scenario's delays
+ *                       (the pipeline as Adaptra would re-plan it);
+ *   plan_scenario = k   the schedule of each candidate is generated once, under scenario k, and
+ *                       then executed as a fixed plan under every scenario (Section 3.2: a
+ *                       framework runs a fixed execution plan), e.g. k = the no-straggler case.
+ *   out_makespan  DEVICE int32 [n_scen][n_cand]
+ *   out_bubble    DEVICE int32 [S][n_scen][n_cand] = makespan - M (t_f + t_b + t_w), or NULL
+ * The workspace size comes from adaptra_zb_workspace_bytes.  Asynchronous on `stream`. */
+size_t adaptra_zb_workspace_bytes(const adaptra_params_t *params, int64_t n_cand, int64_t n_scen);
+int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const adaptra_candidates_t *cands,
+                    const adaptra_scenarios_t *scens, int64_t plan_scenario,
+                    int32_t *out_makespan, int32_t *out_bubble,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
 /* Kernel selection, process-wide; for tests and measurements.
  *   0  automatic (default): register/LDS kernel where S and the scenario count suit
  *      it, the general kernel otherwise

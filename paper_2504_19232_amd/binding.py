@@ -22,6 +22,7 @@ FLAG_FEASIBLE, FLAG_DEADLOCK, FLAG_MEMCAP = 1, 2, 4
 INT32_MAX = 2 ** 31 - 1
 
 EXPORTS = ("adaptra_workspace_bytes", "adaptra_check_inputs", "adaptra_eval", "adaptra_best", "adaptra_seed",
+           "adaptra_zb_workspace_bytes", "adaptra_zb_eval",
            "adaptra_set_kernel_mode", "adaptra_set_resolve_events", "adaptra_valu_probe", "adaptra_last_hip_error",
            "adaptra_version")
 
@@ -72,6 +73,10 @@ def load() -> ctypes.CDLL:
         lib.adaptra_best.argtypes = [P, C, Sc, vp, vp, vp, vp, vp, sz, vp]
         lib.adaptra_seed.restype = ctypes.c_int
         lib.adaptra_seed.argtypes = [P, Sc, ctypes.c_int32, vp, vp, vp, vp, vp]
+        lib.adaptra_zb_workspace_bytes.restype = sz
+        lib.adaptra_zb_workspace_bytes.argtypes = [P, ctypes.c_int64, ctypes.c_int64]
+        lib.adaptra_zb_eval.restype = ctypes.c_int
+        lib.adaptra_zb_eval.argtypes = [P, vp, C, Sc, ctypes.c_int64, vp, vp, vp, sz, vp]
         lib.adaptra_set_kernel_mode.restype = ctypes.c_int
         lib.adaptra_set_kernel_mode.argtypes = [ctypes.c_int]
         lib.adaptra_set_resolve_events.restype = ctypes.c_int
@@ -219,6 +224,26 @@ def adaptra_seed(prob: Problem, x_max: int = 1, w_current=None, *, want_init: bo
                              _ptr(w_init), _ptr(w_ad), _ptr(na), _stream(stream))
     _raise(rc, "adaptra_seed")
     return w_init, w_ad, na
+
+
+def adaptra_zb_eval(prob: Problem, t_w, plan_scenario: int = -1, *, want_bubble: bool = True,
+                    workspace=None, stream=None):
+    """Enqueue the ZeroBubble (F / B / W) evaluation; returns (makespan [K,C], bubble [S,K,C] | None)."""
+    import torch
+    dev = prob.device
+    _check_i32(t_w, "t_w", (prob.S,))
+    mk = torch.empty((prob.K, prob.C), dtype=torch.int32, device=dev)
+    bub = torch.empty((prob.S, prob.K, prob.C), dtype=torch.int32, device=dev) if want_bubble else None
+    if workspace is None:
+        n = int(load().adaptra_zb_workspace_bytes(ctypes.byref(prob.params), prob.C, prob.K))
+        if n == 0:
+            raise AdaptraError(EINVAL, "adaptra_zb_workspace_bytes")
+        workspace = torch.empty(n, dtype=torch.uint8, device=dev)
+    rc = load().adaptra_zb_eval(ctypes.byref(prob.params), t_w.data_ptr(), ctypes.byref(prob.cands),
+                                ctypes.byref(prob.scens), int(plan_scenario), mk.data_ptr(), _ptr(bub),
+                                workspace.data_ptr(), workspace.numel(), _stream(stream))
+    _raise(rc, "adaptra_zb_eval")
+    return mk, bub
 
 
 def adaptra_set_kernel_mode(mode: int) -> int:

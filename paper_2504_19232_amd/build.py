@@ -6,7 +6,7 @@ import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
-SRC = os.path.join(_HERE, "csrc", "adaptra.hip")
+SOURCES = [os.path.join(_HERE, "csrc", "adaptra.hip"), os.path.join(_HERE, "csrc", "adaptra_zb.hip")]
 INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(_HERE, "libadaptra.so")
 
@@ -20,7 +20,7 @@ HIPCC_FLAGS = [
 def build_library(verbose: bool = False, extra_flags=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + f".tmp{os.getpid()}"
-    cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, SRC, "-o", tmp]
+    cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, *SOURCES, "-o", tmp]
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)

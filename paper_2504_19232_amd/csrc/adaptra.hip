@@ -27,6 +27,7 @@
 #include <stdint.h>
 
 #include "adaptra.h"
+#include "adaptra_internal.h"
 
 namespace {
 
@@ -763,10 +764,7 @@ bool use_fast(int S, long long K) {
     return K * 2 >= tiles * 64;
 }
 
-int hip_fail(hipError_t e) {
-    g_last_hip_error = (int)e;
-    return ADAPTRA_EHIP;
-}
+int hip_fail(hipError_t e) { return adaptra_detail::hip_fail(e); }
 
 #define ADAPTRA_LAUNCH_CHECK()                          \
     do {                                                \
@@ -899,6 +897,11 @@ int launch_resolve(KArgs a, const Workspace &ws, int w_bound, hipStream_t st) {
 }
 
 }  // namespace
+
+int adaptra_detail::hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return ADAPTRA_EHIP;
+}
 
 extern "C" {
 

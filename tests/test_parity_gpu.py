@@ -355,3 +355,63 @@ def test_algorithm2_pick_against_the_exhaustive_search(lib, oracle):
     assert np.all(bmk <= diag)
     ref = oracle.eval_workload(wl2, pair_cand=C0 + np.arange(wl.n_scen), pair_scen=np.arange(wl.n_scen), want_bubble=False)
     assert np.array_equal(diag, ref["makespan"])
+
+
+def _zb_problem(b, S, N, t_f, t_b, t_w, w, cf, cb):
+    import torch
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+    prob = b.Problem(N, up(t_f), up(t_b), up(w), up(cf), up(cb))
+    return prob, up(t_w)
+
+
+def test_zb_paper_example_on_gpu(lib):
+    """The paper's printed ZeroBubble example through the GPU path: 390 ms without delay; the
+    plan generated without delay takes 400 / 440 ms under 10 / 20 ms on link 0 <-> 1; re-planned
+    under the delay it loses only the delay itself."""
+    import torch
+    b = lib
+    S, N, t = 4, 12, 10000
+    w = np.array([[6], [4], [2], [0]])                       # x = 7 5 3 1
+    delays = [0, 10000, 20000]
+    cf = np.zeros((S - 1, 3), dtype=np.int32)
+    cf[0] = delays
+    prob, t_w = _zb_problem(b, S, N, [t] * S, [t] * S, [t] * S, w, cf, cf)
+    mk_own, _ = b.adaptra_zb_eval(prob, t_w, -1)
+    mk_plan, bub = b.adaptra_zb_eval(prob, t_w, 0)
+    torch.cuda.synchronize()
+    assert list(mk_plan.cpu().numpy()[:, 0]) == [390000, 400000, 440000]
+    assert list(mk_own.cpu().numpy()[:, 0]) == [390000, 400000, 410000]
+    assert np.array_equal(bub.cpu().numpy()[:, :, 0], np.array([[30000, 40000, 80000]] * S))
+
+
+ZB_CASES = [(1, 1, 1, 3, 2), (2, 2, 3, 9, 5), (3, 4, 8, 40, 21), (4, 8, 16, 70, 33), (5, 5, 7, 300, 4),
+            (6, 16, 12, 20, 10), (7, 3, 40, 10, 64)]
+
+
+@pytest.mark.parametrize("seed_,S,N,C,K", ZB_CASES, ids=[f"S{c[1]}_N{c[2]}_C{c[3]}_K{c[4]}" for c in ZB_CASES])
+def test_zb_parity(lib, oracle, seed_, S, N, C, K):
+    import torch
+    b = lib
+    rng = np.random.default_rng(seed_)
+    t_f, t_b, t_w = rng.integers(1, 60, S), rng.integers(1, 90, S), rng.integers(0, 50, S)
+    w = np.sort(rng.integers(-1, N + 3, (S, C)), axis=0)[::-1]
+    w[:, ::5] = rng.integers(0, N, (S, len(range(0, C, 5))))           # some not monotone
+    cf = rng.integers(0, 400, (max(S - 1, 0), K))
+    cb = rng.integers(0, 400, (max(S - 1, 0), K))
+    prob, t_w_d = _zb_problem(b, S, N, t_f, t_b, t_w, w, cf, cb)
+    x = np.clip(w, 0, N - 1) + 1
+    ref = oracle.zb_batch(S, N, t_f, t_b, t_w, x, cf, cb)
+    mk, bub = b.adaptra_zb_eval(prob, t_w_d, -1)
+    torch.cuda.synchronize()
+    assert np.array_equal(mk.cpu().numpy(), ref["makespan"])
+    assert np.array_equal(bub.cpu().numpy(), ref["idle"])
+    # fixed plans generated under scenario 1 (or 0), replayed under every scenario
+    kp = 1 if K > 1 else 0
+    mkp, _ = b.adaptra_zb_eval(prob, t_w_d, kp, want_bubble=False)
+    torch.cuda.synchronize()
+    mkp = mkp.cpu().numpy()
+    for c in range(0, C, max(1, C // 12)):
+        gen = oracle.zb_simulate(S, N, t_f, t_b, t_w, cf[:, kp], cb[:, kp], x=x[:, c])
+        for k in range(0, K, max(1, K // 6)):
+            rep = oracle.zb_simulate(S, N, t_f, t_b, t_w, cf[:, k], cb[:, k], order=gen["order"])
+            assert mkp[k, c] == rep["makespan"], (c, k)
