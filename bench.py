@@ -103,6 +103,7 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload index 0..4 (default 3: S=32, M=128, 2^26 pairs)")
     ap.add_argument("--no-bubble", action="store_true", help="skip adaptra_eval's [S][K][C] bubble output")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-zb", action="store_true", help="skip the ZeroBubble (F/B/W) side measurement")
     ap.add_argument("--kernel-mode", type=int, default=0)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy before the timed region (a kernel of "
@@ -209,6 +210,25 @@ def main():
                      "frac_of_hbm_peak": seed_bytes / t_seed / 8e12, "includes": "output allocation by the binding"}
         del cfs, cbs, sprob
 
+    # ZeroBubble (F / B / W) policy evaluation, first version: timed on configuration 1's
+    # candidates and scenarios (S=8, N=32, 2^20 pairs, 3 S N = 768 ops per pair), t_w = t_b / 2
+    zb_info = None
+    if not args.no_zb:
+        wz = workloads.config(1)
+        zprob = binding.Problem.from_workload(wz)
+        t_w = torch.from_numpy((wz.t_b // 2).astype(np.int32)).to(dev)
+        zws = torch.empty(binding.load().adaptra_zb_workspace_bytes(ctypes.byref(zprob.params), zprob.C, zprob.K),
+                          dtype=torch.uint8, device=dev)
+        binding.adaptra_zb_eval(zprob, t_w, -1, workspace=zws)
+        t_zb = timed(lambda: binding.adaptra_zb_eval(zprob, t_w, -1, workspace=zws), n=2)
+        t_zbp = timed(lambda: binding.adaptra_zb_eval(zprob, t_w, 0, workspace=zws), n=2)
+        zops = zprob.C * zprob.K * 3 * wz.S * wz.M
+        zb_info = {"workload": f"{wz.name} + W ops: {zprob.C} candidates x {zprob.K} scenarios",
+                   "policy_ms": t_zb * 1e3, "policy_evaluations_per_s": zprob.C * zprob.K / t_zb,
+                   "policy_resolved_ops_per_s": zops / t_zb,
+                   "fixed_plan_ms": t_zbp * 1e3, "fixed_plan_evaluations_per_s": zprob.C * zprob.K / t_zbp}
+        del zws, zprob
+
     flags = fl[0].cpu().numpy()                    # the flag depends on the candidate only
     n_live = int(((flags & 2) == 0).sum())
     n_feasible = int((flags == 1).sum())
@@ -245,6 +265,8 @@ def main():
     }
     if seed_info:
         out["seed"] = seed_info
+    if zb_info:
+        out["zb"] = zb_info
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
