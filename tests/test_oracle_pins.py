@@ -370,3 +370,31 @@ def test_rejects_negative_times(oracle):
         oracle.timeline(2, 2, [1, -1], [1, 1], [1, 0], [0], [0])
     with pytest.raises(ValueError):
         oracle.timeline(2, 2, [1, 1], [1, 1], [1, 0], [-5], [0])
+
+
+def test_fb_simulator_agrees_with_the_paper_pinned_fbw_simulator(oracle):
+    """Cross-pin: the F/B/W fixed-plan executor (which reproduces the 390 / 400 / 440 ms the paper
+    prints, see test_oracle_zb_pins.py) run on a 1F1B-family plan with zero-length W ops must
+    give the F/B simulator's makespan and stage idle times."""
+    rng = np.random.default_rng(77)
+    for _ in range(40):
+        S, M = int(rng.integers(1, 7)), int(rng.integers(1, 12))
+        t_f, t_b, w, cf, cb = rand_instance(rng, S, M, valid=True, c_hi=300)
+        wc = np.minimum(w, M - 1)
+        plan = np.zeros((S, 3 * M), dtype=np.int32)
+        for s in range(S):
+            ops = [None] * (2 * M)
+            for m in range(M):
+                ops[_pos_f(wc[s], m)] = 0 * M + m
+                ops[_pos_b(wc[s], M, m)] = 1 * M + m
+            seq = []
+            for op in ops:
+                seq.append(op)
+                if op >= M:
+                    seq.append(2 * M + (op - M))          # W(m) right behind B(m), zero length
+            plan[s] = seq
+        zb = oracle.zb_simulate(S, M, t_f, t_b, np.zeros(S, dtype=np.int32), cf, cb, order=plan)
+        tl = oracle.timeline(S, M, t_f, t_b, w, cf, cb)
+        assert zb["makespan"] == tl["makespan"]
+        assert np.array_equal(zb["idle"], tl["idle"])
+        assert np.array_equal(zb["fin"][:, 0, :], tl["fin_f"]) and np.array_equal(zb["fin"][:, 1, :], tl["fin_b"])
