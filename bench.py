@@ -104,6 +104,8 @@ def main():
     ap.add_argument("--no-bubble", action="store_true", help="skip adaptra_eval's [S][K][C] bubble output")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-zb", action="store_true", help="skip the ZeroBubble (F/B/W) side measurement")
+    ap.add_argument("--no-sens", action="store_true",
+                    help="skip the per-scenario stage time and link sensitivity side measurements")
     ap.add_argument("--kernel-mode", type=int, default=0)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy before the timed region (a kernel of "
@@ -229,6 +231,29 @@ def main():
                    "fixed_plan_ms": t_zbp * 1e3, "fixed_plan_evaluations_per_s": zprob.C * zprob.K / t_zbp}
         del zws, zprob
 
+    # computation stragglers (per-scenario stage times) on the same workload, and the link
+    # sensitivities of 64 of its candidates (S copies of every scenario per candidate)
+    vt_info = sens_info = None
+    if not args.no_sens and S > 1:
+        tfs, tbs = workloads.straggler_stage_times(99, wl)
+        vprob = binding.Problem.from_workload(wl, dev, w_bound, t_f_scen=tfs, t_b_scen=tbs)
+        binding.adaptra_eval(vprob, mk, bub, fl, want_bubble=bub is not None, workspace=ws)
+        t_vt = timed(lambda: binding.adaptra_eval(vprob, mk, bub, fl, want_bubble=bub is not None, workspace=ws))
+        vt_info = {"eval_ms": t_vt * 1e3, "evaluations_per_s": C * K / t_vt, "vs_fixed_stage_times": t_eval / t_vt}
+        del vprob
+        pick = np.flatnonzero((fl[0].cpu().numpy() & 2) == 0)
+        pick = pick[:: max(1, len(pick) // 64)][:64]
+        sub = workloads.Workload(**{**wl.__dict__, "w": np.ascontiguousarray(wl.w[:, pick])})
+        sprob2 = binding.Problem.from_workload(sub, dev, w_bound)
+        sws = torch.empty(binding.load().adaptra_sensitivity_workspace_bytes(ctypes.byref(sprob2.params), sprob2.C, sprob2.K),
+                          dtype=torch.uint8, device=dev)
+        binding.adaptra_sensitivity(sprob2, 1, workspace=sws)
+        t_sens = timed(lambda: binding.adaptra_sensitivity(sprob2, 1, workspace=sws))
+        sens_info = {"candidates": int(sprob2.C), "scenarios": int(K), "links": S - 1, "ms": t_sens * 1e3,
+                     "evaluations_per_s": sprob2.C * K * S / t_sens,
+                     "includes": "output allocation by the binding"}
+        del sws, sprob2
+
     flags = fl[0].cpu().numpy()                    # the flag depends on the candidate only
     n_live = int(((flags & 2) == 0).sum())
     n_feasible = int((flags == 1).sum())
@@ -267,6 +292,9 @@ def main():
         out["seed"] = seed_info
     if zb_info:
         out["zb"] = zb_info
+    if vt_info:
+        out["stage_time_scenarios"] = vt_info
+        out["sensitivity"] = sens_info
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))

@@ -99,6 +99,9 @@ typedef struct adaptra_scenarios {
     int64_t n;               /* 1..2^31-1 */
     const int32_t *c_fwd;    /* DEVICE [S-1][n], >= 0 */
     const int32_t *c_bwd;    /* DEVICE [S-1][n], >= 0 */
+    const int32_t *t_f;      /* optional DEVICE [S][n]: per-scenario forward times (computation   */
+    const int32_t *t_b;      /* stragglers, Section 2.2); both or neither.  NULL = params->t_f /  */
+                             /* t_b in every scenario.  Ignored by adaptra_zb_eval.               */
 } adaptra_scenarios_t;
 
 /* Bytes of device scratch adaptra_eval / adaptra_best / adaptra_check_inputs need for
@@ -160,6 +163,29 @@ int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *can
 int adaptra_seed(const adaptra_params_t *params, const adaptra_scenarios_t *scens, int32_t x_max,
                  const int32_t *w_current, int32_t *out_w_init, int32_t *out_w_adapted,
                  uint8_t *out_not_absorbed, void *stream);
+
+/* Which link's delay is on the critical path (Section 3.1, Theorem 1: a delay a schedule has
+ * no slack for adds to the makespan once per micro-batch that waits on it; one it absorbs
+ * adds at most its one-off lead-in): for every candidate c, scenario k and link l the finite
+ * difference
+ *     out_sens[c][l][k] = makespan(w_c ; c_fwd[l][k] + delta) - makespan(w_c ; scenario k),
+ * obtained by evaluating the S - 1 perturbed copies of each scenario next to it with the
+ * kernels of adaptra_eval.  0 = the link is off the critical path for that pair; values above
+ * delta = the delay is paid more than once (cascading bubbles).  In this model a makespan
+ * depends on a link's delays only through c_fwd[l] + c_bwd[l], so the same figure holds for
+ * the backward direction.
+ *   delta          >= 1, microseconds added to one link at a time
+ *   out_makespan   DEVICE int32 [n_cand][n_scen] base makespans, or NULL   (candidate-major,
+ *   out_feasible   DEVICE uint8 [n_cand][n_scen] flag bytes, or NULL        unlike adaptra_eval)
+ *   out_sens       DEVICE int32 [n_cand][S-1][n_scen]; INT32_MAX for a deadlocked candidate
+ * Preconditions: adaptra_eval's, with delta of headroom on the delays; n_scen * S and
+ * n_cand * n_scen at most 2^31 - 1.  The workspace size comes from
+ * adaptra_sensitivity_workspace_bytes.  Asynchronous on `stream`. */
+size_t adaptra_sensitivity_workspace_bytes(const adaptra_params_t *params, int64_t n_cand, int64_t n_scen);
+int adaptra_sensitivity(const adaptra_params_t *params, const adaptra_candidates_t *cands,
+                        const adaptra_scenarios_t *scens, int32_t delta,
+                        int32_t *out_makespan, uint8_t *out_feasible, int32_t *out_sens,
+                        void *workspace, size_t workspace_bytes, void *stream);
 
 /* ZeroBubble-style schedules: three ops per stage and micro-batch -- forward F, backward-input
  * B, backward-weight W (t_w: DEVICE int32 [S], >= 0) -- generated by the paper's two-phase

@@ -127,6 +127,49 @@ def eval_workload(wl, **kw) -> dict:
     return eval_pairs(wl.S, wl.M, wl.t_f, wl.t_b, wl.mem_cap, wl.w, wl.c_fwd, wl.c_bwd, **kw)
 
 
+def eval_scenario_times(S: int, M: int, t_f_scen, t_b_scen, mem_cap, w, c_fwd, c_bwd, **kw) -> dict:
+    """Computation stragglers (Section 2.2): scenario k has its own stage times
+    t_f_scen[:, k], t_b_scen[:, k] ([S, K]).  One plain simulation per scenario; outputs
+    shaped as eval_pairs' full sweep ([K, C], bubble [S, K, C])."""
+    t_f_scen, t_b_scen = _c32(t_f_scen), _c32(t_b_scen)
+    c_fwd, c_bwd = _c32(c_fwd), _c32(c_bwd)
+    K = t_f_scen.shape[1]
+    rows = [eval_pairs(S, M, t_f_scen[:, k], t_b_scen[:, k], mem_cap, w,
+                       c_fwd[:, k:k + 1], c_bwd[:, k:k + 1], **kw) for k in range(K)]
+    out = {"makespan": np.concatenate([r["makespan"] for r in rows], axis=0),
+           "flag": np.concatenate([r["flag"] for r in rows], axis=0)}
+    for name in ("bubble", "peak"):
+        out[name] = None if rows[0][name] is None else np.concatenate([r[name] for r in rows], axis=1)
+    return out
+
+
+def sensitivity(S: int, M: int, t_f, t_b, mem_cap, w, c_fwd, c_bwd, delta: int = 1, *,
+                direction: str = "fwd", t_f_scen=None, t_b_scen=None) -> dict:
+    """Which link's delay is on the critical path (Section 3.1, Theorem 1), by plain
+    perturb-and-simulate: sens[c, l, k] = makespan with the delay of link l (forward
+    direction, or backward with direction="bwd") raised by delta, minus the makespan of
+    the scenario as given.  INT32_MAX where the candidate is deadlocked.
+    Returns makespan / flag [C, K] and sens [C, S-1, K]."""
+    def run(cf, cb):
+        if t_f_scen is None:
+            r = eval_pairs(S, M, t_f, t_b, mem_cap, w, cf, cb, want_bubble=False)
+        else:
+            r = eval_scenario_times(S, M, t_f_scen, t_b_scen, mem_cap, w, cf, cb, want_bubble=False)
+        return r["makespan"].T.astype(np.int64), r["flag"].T
+    c_fwd, c_bwd = _c32(c_fwd), _c32(c_bwd)
+    base, flag = run(c_fwd, c_bwd)
+    C, K = base.shape
+    sens = np.empty((C, max(S - 1, 0), K), dtype=np.int64)
+    for l in range(S - 1):
+        cf, cb = c_fwd.copy(), c_bwd.copy()
+        (cf if direction == "fwd" else cb)[l] += delta
+        up, _ = run(cf, cb)
+        sens[:, l, :] = up - base
+    dead = (flag & FLAG_DEADLOCK) != 0
+    sens[np.broadcast_to(dead[:, None, :], sens.shape)] = INT32_MAX
+    return {"makespan": base.astype(np.int32), "flag": flag, "sens": sens.astype(np.int32)}
+
+
 def best_from_eval(makespan: np.ndarray, flag: np.ndarray, bubble: Optional[np.ndarray] = None) -> dict:
     """Per-scenario search, written out: among candidates whose flag is 1 take the
     smallest makespan, ties to the lowest candidate index; -1 / INT32_MAX (and

@@ -22,6 +22,7 @@ FLAG_FEASIBLE, FLAG_DEADLOCK, FLAG_MEMCAP = 1, 2, 4
 INT32_MAX = 2 ** 31 - 1
 
 EXPORTS = ("adaptra_workspace_bytes", "adaptra_check_inputs", "adaptra_eval", "adaptra_best", "adaptra_seed",
+           "adaptra_sensitivity_workspace_bytes", "adaptra_sensitivity",
            "adaptra_zb_workspace_bytes", "adaptra_zb_eval",
            "adaptra_set_kernel_mode", "adaptra_set_resolve_events", "adaptra_valu_probe", "adaptra_last_hip_error",
            "adaptra_version")
@@ -46,7 +47,8 @@ class Candidates(ctypes.Structure):
 
 
 class Scenarios(ctypes.Structure):
-    _fields_ = [("n", ctypes.c_int64), ("c_fwd", ctypes.c_void_p), ("c_bwd", ctypes.c_void_p)]
+    _fields_ = [("n", ctypes.c_int64), ("c_fwd", ctypes.c_void_p), ("c_bwd", ctypes.c_void_p),
+                ("t_f", ctypes.c_void_p), ("t_b", ctypes.c_void_p)]
 
 
 _lib = None
@@ -73,6 +75,10 @@ def load() -> ctypes.CDLL:
         lib.adaptra_best.argtypes = [P, C, Sc, vp, vp, vp, vp, vp, sz, vp]
         lib.adaptra_seed.restype = ctypes.c_int
         lib.adaptra_seed.argtypes = [P, Sc, ctypes.c_int32, vp, vp, vp, vp, vp]
+        lib.adaptra_sensitivity_workspace_bytes.restype = sz
+        lib.adaptra_sensitivity_workspace_bytes.argtypes = [P, ctypes.c_int64, ctypes.c_int64]
+        lib.adaptra_sensitivity.restype = ctypes.c_int
+        lib.adaptra_sensitivity.argtypes = [P, C, Sc, ctypes.c_int32, vp, vp, vp, vp, sz, vp]
         lib.adaptra_zb_workspace_bytes.restype = sz
         lib.adaptra_zb_workspace_bytes.argtypes = [P, ctypes.c_int64, ctypes.c_int64]
         lib.adaptra_zb_eval.restype = ctypes.c_int
@@ -116,7 +122,7 @@ class Problem:
     tensors, kept alive by this object."""
 
     def __init__(self, M: int, t_f, t_b, w, c_fwd, c_bwd, mem_cap=None, hist_bins: int = 0, hist_shift: int = 0,
-                 w_bound: int = -1):
+                 w_bound: int = -1, t_f_scen=None, t_b_scen=None):
         S = int(t_f.shape[0])
         C = int(w.shape[1])
         K = int(c_fwd.shape[1])
@@ -124,21 +130,23 @@ class Problem:
         _check_i32(w, "w", (S, C)); _check_i32(c_fwd, "c_fwd", (S - 1, K)); _check_i32(c_bwd, "c_bwd", (S - 1, K))
         self.S, self.M, self.C, self.K = S, int(M), C, K
         self.hist_bins, self.hist_shift = int(hist_bins), int(hist_shift)
-        self.tensors = (t_f, t_b, w, c_fwd, c_bwd, mem_cap)
+        _check_i32(t_f_scen, "t_f_scen", (S, K)); _check_i32(t_b_scen, "t_b_scen", (S, K))
+        self.tensors = (t_f, t_b, w, c_fwd, c_bwd, mem_cap, t_f_scen, t_b_scen)
         self.device = w.device
         self.params = Params(S, int(M), _ptr(t_f), _ptr(t_b), _ptr(mem_cap), int(hist_bins), int(hist_shift))
         self.cands = Candidates(C, _ptr(w), int(w_bound))
-        self.scens = Scenarios(K, _ptr(c_fwd) if S > 1 else None, _ptr(c_bwd) if S > 1 else None)
+        self.scens = Scenarios(K, _ptr(c_fwd) if S > 1 else None, _ptr(c_bwd) if S > 1 else None,
+                               _ptr(t_f_scen), _ptr(t_b_scen))
 
     @classmethod
-    def from_workload(cls, wl, device="cuda:0", w_bound: int = -1):
+    def from_workload(cls, wl, device="cuda:0", w_bound: int = -1, t_f_scen=None, t_b_scen=None):
         import torch
         dev = torch.device(device)
 
         def up(a):
             return None if a is None else torch.from_numpy(a).to(dev)
         return cls(wl.M, up(wl.t_f), up(wl.t_b), up(wl.w), up(wl.c_fwd), up(wl.c_bwd), up(wl.mem_cap),
-                   wl.hist_bins, wl.hist_shift, w_bound)
+                   wl.hist_bins, wl.hist_shift, w_bound, up(t_f_scen), up(t_b_scen))
 
 
 def adaptra_workspace_bytes(S: int, M: int, n_cand: int, n_scen: int) -> int:
@@ -224,6 +232,26 @@ def adaptra_seed(prob: Problem, x_max: int = 1, w_current=None, *, want_init: bo
                              _ptr(w_init), _ptr(w_ad), _ptr(na), _stream(stream))
     _raise(rc, "adaptra_seed")
     return w_init, w_ad, na
+
+
+def adaptra_sensitivity(prob: Problem, delta: int = 1, *, want_makespan: bool = True, workspace=None, stream=None):
+    """Enqueue the per-link finite differences; returns (makespan [C,K] | None, flag [C,K] | None,
+    sens [C,S-1,K]) -- candidate-major, unlike adaptra_eval."""
+    import torch
+    dev = prob.device
+    mk = torch.empty((prob.C, prob.K), dtype=torch.int32, device=dev) if want_makespan else None
+    fl = torch.empty((prob.C, prob.K), dtype=torch.uint8, device=dev) if want_makespan else None
+    sens = torch.empty((prob.C, prob.S - 1, prob.K), dtype=torch.int32, device=dev)
+    if workspace is None:
+        n = int(load().adaptra_sensitivity_workspace_bytes(ctypes.byref(prob.params), prob.C, prob.K))
+        if n == 0:
+            raise AdaptraError(EINVAL, "adaptra_sensitivity_workspace_bytes")
+        workspace = torch.empty(n, dtype=torch.uint8, device=dev)
+    rc = load().adaptra_sensitivity(ctypes.byref(prob.params), ctypes.byref(prob.cands), ctypes.byref(prob.scens),
+                                    int(delta), _ptr(mk), _ptr(fl), _ptr(sens) if prob.S > 1 else None,
+                                    workspace.data_ptr(), workspace.numel(), _stream(stream))
+    _raise(rc, "adaptra_sensitivity")
+    return mk, fl, sens
 
 
 def adaptra_zb_eval(prob: Problem, t_w, plan_scenario: int = -1, *, want_bubble: bool = True,

@@ -15,6 +15,7 @@
 //                        scenario per wavefront), state in global scratch, DPP argmin
 //   k_eval_epilogue      after the resolve kernels: flag byte and bubbles of every pair,
 //                        sentinels for deadlocked pairs (one coalesced streaming pass)
+//   k_sens_epilogue      adaptra_sensitivity: differences against the base scenarios
 //   k_best_init / k_best_finalize   search keys and histogram set-up / decoding
 //   k_check_inputs       range scan for adaptra_check_inputs
 //   k_seed               the paper's analytic planning (Algorithm 1, Algorithm 2, Eq. (1))
@@ -58,7 +59,10 @@ struct KArgs {
     int S, M;
     const int *t_f, *t_b, *mem_cap;
     long long C, K;
+    long long Kin;                         // scenarios in the input arrays; K = Kin * (1 + links) when the
+    int sens_delta;                        // scenario axis also carries the link-perturbed copies
     const int *w, *cf, *cb;
+    const int *tfs, *tbs;                  // optional per-scenario stage times [S][K] (compute stragglers)
     unsigned char *cand_flag, *cand_class, *cand_wq;
     int wq_stride;                         // bytes per candidate in cand_wq
     int *out_makespan, *out_bubble;
@@ -232,7 +236,7 @@ __global__ __launch_bounds__(kBlock) void k_eval_epilogue(KArgs a) {
     const long long c0 = ((long long)blockIdx.x % ctiles) * 64;
     const long long k0 = ((long long)blockIdx.x / ctiles) * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    if (threadIdx.x < a.S) tau[threadIdx.x] = a.t_f[threadIdx.x] + a.t_b[threadIdx.x];
+    if (threadIdx.x < a.S) tau[threadIdx.x] = a.t_f[threadIdx.x] + a.t_b[threadIdx.x];   // unless per scenario
     for (int i = ty; i < 64; i += kWavesPerBlock) {          // row = candidate, lanes = scenarios
         const long long c = c0 + i, k = k0 + tx;
         if (c < a.C && k < a.K && !(a.cand_flag[c] & ADAPTRA_FLAG_DEADLOCK)) tile[i][tx] = a.mk_t[c * a.K + k];
@@ -251,8 +255,31 @@ __global__ __launch_bounds__(kBlock) void k_eval_epilogue(KArgs a) {
         a.out_makespan[p] = mk;
         a.out_feasible[p] = (unsigned char)flag;
         if (a.out_bubble)
-            for (int s = 0; s < a.S; ++s) a.out_bubble[(long long)s * P + p] = dead ? INT32_MAX : mk - a.M * tau[s];
+            for (int s = 0; s < a.S; ++s) {
+                const int tau_s = a.tfs ? a.tfs[(long long)s * a.K + k] + a.tbs[(long long)s * a.K + k] : tau[s];
+                a.out_bubble[(long long)s * P + p] = dead ? INT32_MAX : mk - a.M * tau_s;
+            }
     }
+}
+
+// Sensitivity epilogue.  The resolve kernels ran with the scenario axis holding Kin base
+// scenarios followed by, for every link l, a copy with c_fwd[l] raised by sens_delta:
+// mk_t[c][v * Kin + k], v = 0 base, v = 1 + l.  Writes, candidate-major (coalesced along k):
+//   out_makespan[c][k]   = base makespan                      (a.out_makespan, optional)
+//   out_feasible[c][k]   = flag byte of the candidate         (a.out_feasible, optional)
+//   out_sens[c][l][k]    = makespan(c_fwd[l] + delta) - base  (a.out_bubble)
+// INT32_MAX for a deadlocked candidate.
+__global__ __launch_bounds__(kBlock) void k_sens_epilogue(KArgs a) {
+    const long long n = a.C * a.Kin;
+    const long long i = (long long)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n) return;
+    const long long c = i / a.Kin, k = i % a.Kin;
+    const bool dead = a.cand_flag[c] & ADAPTRA_FLAG_DEADLOCK;
+    const int base = dead ? INT32_MAX : a.mk_t[c * a.K + k];
+    if (a.out_makespan) a.out_makespan[i] = base;
+    if (a.out_feasible) a.out_feasible[i] = a.cand_flag[c];
+    for (int l = 0; l + 1 < a.S; ++l)
+        a.out_bubble[(c * (a.S - 1) + l) * a.Kin + k] = dead ? INT32_MAX : a.mk_t[c * a.K + (1 + l) * a.Kin + k] - base;
 }
 
 __global__ __launch_bounds__(kBlock) void k_best_init(KArgs a) {
@@ -276,7 +303,9 @@ __global__ __launch_bounds__(kBlock) void k_best_finalize(KArgs a) {
     a.best_makespan[k] = mk;
     if (a.best_bubble)
         for (int s = 0; s < a.S; ++s)
-            a.best_bubble[k * a.S + s] = none ? INT32_MAX : mk - a.M * (a.t_f[s] + a.t_b[s]);
+            a.best_bubble[k * a.S + s] =
+                none ? INT32_MAX
+                     : mk - a.M * (a.tfs ? a.tfs[(long long)s * a.K + k] + a.tbs[(long long)s * a.K + k] : a.t_f[s] + a.t_b[s]);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -306,6 +335,8 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
     for (long long tile = tid >> 6; tile < ntiles; tile += nwaves) {
         const long long k = tile / ctiles;
         const long long c = (tile % ctiles) * 64 + lane;
+        const long long kin = k % a.Kin;             // scenario in the input arrays
+        const int link_up = (int)(k / a.Kin) - 1;    // link whose forward delay this copy raises, or -1
         bool run = false;
         if (c < a.C) {
             const int flag = a.cand_flag[c];
@@ -324,8 +355,8 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
                 for (int s = 0; s < S; ++s) {                    // forward sweep
                     const int m = wl[s * NT] + r;
                     if (m >= 0 && m < M) {
-                        const int arrive = s == 0 ? 0 : fwd[m * NT] + a.cf[(long long)(s - 1) * a.K + k];
-                        const int fin = imax(last[s * NT], arrive) + a.t_f[s];
+                        const int arrive = s == 0 ? 0 : fwd[m * NT] + a.cf[(long long)(s - 1) * a.Kin + kin] + (s - 1 == link_up ? a.sens_delta : 0);
+                        const int fin = imax(last[s * NT], arrive) + (a.tfs ? a.tfs[(long long)s * a.Kin + kin] : a.t_f[s]);
                         last[s * NT] = fin;
                         fwd[m * NT] = fin;
                     }
@@ -333,8 +364,8 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
                 if (r >= 0) {                                    // backward sweep
                     int carry = 0;
                     for (int s = S - 1; s >= 0; --s) {
-                        const int arrive = s == S - 1 ? 0 : carry + a.cb[(long long)s * a.K + k];
-                        const int fin = imax(last[s * NT], arrive) + a.t_b[s];
+                        const int arrive = s == S - 1 ? 0 : carry + a.cb[(long long)s * a.Kin + kin];
+                        const int fin = imax(last[s * NT], arrive) + (a.tbs ? a.tbs[(long long)s * a.Kin + kin] : a.t_b[s]);
                         last[s * NT] = fin;
                         carry = fin;
                     }
@@ -346,7 +377,8 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
                 key = ((unsigned long long)(unsigned)mk << 32) | (unsigned)c;
                 if (a.hist) {
                     for (int s = 0; s < S; ++s) {
-                        int b = (mk - M * (a.t_f[s] + a.t_b[s])) >> a.hist_shift;
+                        const int tau_s = a.tfs ? a.tfs[(long long)s * a.Kin + kin] + a.tbs[(long long)s * a.Kin + kin] : a.t_f[s] + a.t_b[s];
+                        int b = (mk - M * tau_s) >> a.hist_shift;
                         b = b > a.hist_bins - 1 ? a.hist_bins - 1 : b;
                         atomicAdd(&a.hist[s * a.hist_bins + b], 1ull);
                     }
@@ -386,8 +418,8 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
 // slot-major layout [slot][lane] keeps every access conflict-free.  The reads are software
 // pipelined: each is issued several stages (or, for the first stages, a whole backward
 // sweep) ahead of its use, so the LDS latency does not stall every stage.
-template <int S, bool BEST>
-__global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resolve_scen_lanes(KArgs) {
+template <int S, bool BEST, bool VT>
+__global__ __launch_bounds__(kBlock, S >= 32 ? (VT ? 3 : ADAPTRA_WAVES32) : 6) void k_resolve_scen_lanes(KArgs) {
     // The arguments are read through kargs() where they are needed (see there), never
     // through the by-value parameter.
     extern __shared__ int lds[];
@@ -414,18 +446,29 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resol
         const long long k = (long long)tile * 64 + lane;
         const bool kvalid = k < K;
         const long long kk = kvalid ? k : K - 1;
+        const long long Kin = kargs()->Kin;
+        const long long kin = kk % Kin;              // scenario in the input arrays
+        const int link_up = (int)(kk / Kin) - 1;     // link whose delay this copy raises, or -1
         // t_f and t_b of the stages share one VGPR each (lane s holds stage s); the addend a
         // stage currently needs is kept in an SGPR (add_f below) and switched with v_readlane
         // when the stage changes phase.
-        const int tf_lanes = kargs()->t_f[lane < S ? lane : 0];
-        const int tb_lanes = kargs()->t_b[lane < S ? lane : 0];
-        const int tau0 = uni(kargs()->t_f[0]) + uni(kargs()->t_b[0]);
+        // With per-scenario stage times (VT: compute stragglers) every lane has its own t_f and
+        // t_b; they are then re-read from memory at the phase switches and add_f is per lane.
+        const int tf_lanes = VT ? 0 : kargs()->t_f[lane < S ? lane : 0];
+        const int tb_lanes = VT ? 0 : kargs()->t_b[lane < S ? lane : 0];
+#define ADAPTRA_TF(s) (VT ? kargs()->tfs[(s) * kargs()->Kin + kin] : __builtin_amdgcn_readlane(tf_lanes, (s)))
+#define ADAPTRA_TB(s) (VT ? kargs()->tbs[(s) * kargs()->Kin + kin] : __builtin_amdgcn_readlane(tb_lanes, (s)))
+        const int tau0 = VT ? kargs()->tfs[kin] + kargs()->tbs[kin] : uni(kargs()->t_f[0]) + uni(kargs()->t_b[0]);
         int q[S > 1 ? S - 1 : 1];
         {
-            const int *cf = kargs()->cf, *cb = kargs()->cb, *t_f = kargs()->t_f, *t_b = kargs()->t_b;
+            const int *cf = kargs()->cf, *cb = kargs()->cb;
 #pragma unroll
-            for (int s = 0; s + 1 < S; ++s)
-                q[s] = cf[s * K + kk] + cb[s * K + kk] + uni(t_f[s + 1]) + uni(t_b[s + 1]);
+            for (int s = 0; s + 1 < S; ++s) {
+                int tau_next;
+                if constexpr (VT) tau_next = kargs()->tfs[(s + 1) * Kin + kin] + kargs()->tbs[(s + 1) * Kin + kin];
+                else tau_next = uni(kargs()->t_f[s + 1]) + uni(kargs()->t_b[s + 1]);
+                q[s] = cf[s * Kin + kin] + cb[s * Kin + kin] + tau_next + (s == link_up ? kargs()->sens_delta : 0);
+            }
         }
 
         unsigned long long key = kNoKey;
@@ -454,9 +497,9 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resol
                 L[s] = kNeg;
                 x[s] = 0;
                 soff[s] = bias;   // micro-batch 0 sits in slot 0
-                add_f[s] = __builtin_amdgcn_readlane(tf_lanes, s);
+                add_f[s] = ADAPTRA_TF(s);
             }
-            L[0] = -__builtin_amdgcn_readlane(tf_lanes, 0);
+            L[0] = -add_f[0];
 
 // One forward step of stage s.  x[s] is the value micro-batch m got on stage s-1, read from
 // ring slot m mod D some stages earlier; if the two stages have equal w that value is only
@@ -516,7 +559,7 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resol
             }
             ADAPTRA_B_SWEEP();                    // B(s, 0): each after a forward
 #pragma unroll
-            for (int s = 0; s < S; ++s) add_f[s] += __builtin_amdgcn_readlane(tb_lanes, s);
+            for (int s = 0; s < S; ++s) add_f[s] += ADAPTRA_TB(s);
             // steady rounds r = 1 .. M-1-W: F after B, B after F on every stage
             for (int r = M - 1 - W; r > 0; --r) {
                 stages_up<0, S>(ADAPTRA_STAGE_LAMBDA(si) {
@@ -545,7 +588,7 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resol
                         constexpr int s = decltype(si)::value;
                         int prev = L[s];
                         if (s < done) {                                   // B after B
-                            if (s >= done_before) add_f[s] -= __builtin_amdgcn_readlane(tf_lanes, s);
+                            if (s >= done_before) add_f[s] -= ADAPTRA_TF(s);
                             prev += add_f[s];
                         }
                         L[s] = (s == S - 1) ? prev : imax(prev, carry + q[s < S - 1 ? s : 0]);
@@ -568,7 +611,7 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resol
                         unsigned long long *const hist = kargs()->hist;
 #pragma unroll
                         for (int s = 0; s < S; ++s) {
-                            const int tau_s = __builtin_amdgcn_readlane(tf_lanes, s) + __builtin_amdgcn_readlane(tb_lanes, s);
+                            const int tau_s = ADAPTRA_TF(s) + ADAPTRA_TB(s);
                             int b = (mk - M * tau_s) >> shift;
                             b = b > bins - 1 ? bins - 1 : b;
                             if (lds_hist) atomicAdd(&hist_lds[s * bins + b], 1u);
@@ -594,13 +637,16 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resol
         }
     }
 }
+#undef ADAPTRA_TF
+#undef ADAPTRA_TB
 
 // ---------------------------------------------------------------------------------------
 // status[0] = number of negative entries, status[1] = max time, status[2] = max delay
 __global__ __launch_bounds__(kBlock) void k_check_inputs(KArgs a) {
     const long long nw = (long long)a.S * a.C;
     const long long nc = (long long)(a.S - 1) * a.K;
-    const long long n = nw + 2 * nc + 2 * a.S;
+    const long long nts = a.tfs ? (long long)a.S * a.K : 0;
+    const long long n = nw + 2 * nc + 2 * a.S + 2 * nts;
     const long long stride = (long long)gridDim.x * kBlock;
     int neg = 0, maxt = 0, maxc = 0;
     for (long long i = (long long)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) {
@@ -614,9 +660,14 @@ __global__ __launch_bounds__(kBlock) void k_check_inputs(KArgs a) {
             const int v = a.cb[i - nw - nc];
             neg += v < 0;
             maxc = imax(maxc, v);
-        } else {
+        } else if (i < nw + 2 * nc + 2 * a.S) {
             const long long j = i - nw - 2 * nc;
             const int v = j < a.S ? a.t_f[j] : a.t_b[j - a.S];
+            neg += v < 0;
+            maxt = imax(maxt, v);
+        } else {
+            const long long j = i - nw - 2 * nc - 2 * a.S;
+            const int v = j < nts ? a.tfs[j] : a.tbs[j - nts];
             neg += v < 0;
             maxt = imax(maxt, v);
         }
@@ -643,7 +694,7 @@ __global__ void k_zero_status(KArgs a) {
 struct SeedArgs {
     int S, M, x_max;
     long long K;
-    const int *t_f, *t_b, *cf, *cb, *w_cur;
+    const int *t_f, *t_b, *cf, *cb, *w_cur, *tfs, *tbs;
     int *w_init, *w_adapted;
     unsigned char *not_absorbed;
 };
@@ -663,13 +714,17 @@ __global__ __launch_bounds__(kBlock) void k_seed(SeedArgs a) {
         }
     }
     if (k >= a.K) return;
+    auto tau = [&](int i) -> long long {       // t_f + t_b of stage i as this scenario sees it
+        return a.tfs ? (long long)a.tfs[(long long)i * a.K + k] + a.tbs[(long long)i * a.K + k]
+                     : (long long)a.t_f[i] + a.t_b[i];
+    };
     if (a.w_adapted) {
         int x = 1;
         a.w_adapted[(long long)(S - 1) * a.K + k] = 0;
         const int clip = a.M - 2 * S;
         for (int i = S - 2; i >= 0; --i) {
-            const long long num = (long long)a.t_f[i] + a.t_b[i] + a.cf[(long long)i * a.K + k] + a.cb[(long long)i * a.K + k];
-            const long long den = (long long)a.t_f[i + 1] + a.t_b[i + 1];
+            const long long num = tau(i) + a.cf[(long long)i * a.K + k] + a.cb[(long long)i * a.K + k];
+            const long long den = tau(i + 1);
             long long d = clip;
             if (den != 0) {
                 long long ratio = (num + den - 1) / den;
@@ -684,8 +739,8 @@ __global__ __launch_bounds__(kBlock) void k_seed(SeedArgs a) {
     }
     if (a.not_absorbed) {
         for (int i = 0; i + 1 < S; ++i) {
-            const long long lhs = (long long)a.t_f[i] + a.t_b[i] + a.cf[(long long)i * a.K + k] + a.cb[(long long)i * a.K + k];
-            const long long rhs = ((long long)a.w_cur[i] - a.w_cur[i + 1]) * ((long long)a.t_f[i + 1] + a.t_b[i + 1]);
+            const long long lhs = tau(i) + a.cf[(long long)i * a.K + k] + a.cb[(long long)i * a.K + k];
+            const long long rhs = ((long long)a.w_cur[i] - a.w_cur[i + 1]) * tau(i + 1);
             a.not_absorbed[(long long)i * a.K + k] = lhs <= rhs ? 0 : 1;
         }
     }
@@ -786,6 +841,7 @@ int validate_common(const adaptra_params_t *p, const adaptra_candidates_t *cd,
     if (!plan_workspace(p->S, p->M, cd->n, sc->n, ws)) return ADAPTRA_EINVAL;
     if (!p->t_f || !p->t_b || !cd->w) return ADAPTRA_EINVAL;
     if (p->S > 1 && (!sc->c_fwd || !sc->c_bwd)) return ADAPTRA_EINVAL;
+    if ((sc->t_f == nullptr) != (sc->t_b == nullptr)) return ADAPTRA_EINVAL;
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws->total) return ADAPTRA_EWORKSPACE;
     return ADAPTRA_OK;
 }
@@ -795,8 +851,9 @@ void fill_args(KArgs *a, const adaptra_params_t *p, const adaptra_candidates_t *
     *a = KArgs{};
     a->S = p->S; a->M = p->M;
     a->t_f = p->t_f; a->t_b = p->t_b; a->mem_cap = p->mem_cap;
-    a->C = cd->n; a->K = sc->n;
+    a->C = cd->n; a->K = sc->n; a->Kin = sc->n;
     a->w = cd->w; a->cf = sc->c_fwd; a->cb = sc->c_bwd;
+    a->tfs = sc->t_f; a->tbs = sc->t_b;
     char *base = (char *)workspace;
     a->cand_flag = (unsigned char *)(base + ws.off_flag);
     a->cand_class = (unsigned char *)(base + ws.off_class);
@@ -810,8 +867,8 @@ void fill_args(KArgs *a, const adaptra_params_t *p, const adaptra_candidates_t *
     a->n_chunks = (cd->n + kChunk - 1) / kChunk;
 }
 
-template <int S, bool BEST>
-int launch_fast_one(KArgs a, int w_bound, hipStream_t st) {
+template <int S, bool BEST, bool VT>
+int launch_fast_vt(KArgs a, int w_bound, hipStream_t st) {
     const long long tasks = a.n_chunks * a.n_ktiles;
     const long long blocks = (tasks + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > INT32_MAX) return ADAPTRA_EINVAL;
@@ -832,14 +889,19 @@ int launch_fast_one(KArgs a, int w_bound, hipStream_t st) {
         size_t lds = (size_t)kWavesPerBlock * a.ring_slots * 256;
         if (BEST && a.hist && a.hist_in_lds) lds += (size_t)S * a.hist_bins * 4;
         if (lds > 48 * 1024) {      // above the default dynamic-LDS limit: raise it for this kernel
-            hipError_t e = hipFuncSetAttribute((const void *)k_resolve_scen_lanes<S, BEST>,
+            hipError_t e = hipFuncSetAttribute((const void *)k_resolve_scen_lanes<S, BEST, VT>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return hip_fail(e);
         }
-        hipLaunchKernelGGL((k_resolve_scen_lanes<S, BEST>), dim3((unsigned)blocks), dim3(kBlock), lds, st, a);
+        hipLaunchKernelGGL((k_resolve_scen_lanes<S, BEST, VT>), dim3((unsigned)blocks), dim3(kBlock), lds, st, a);
         ADAPTRA_LAUNCH_CHECK();
     }
     return ADAPTRA_OK;
+}
+
+template <int S, bool BEST>
+int launch_fast_one(const KArgs &a, int w_bound, hipStream_t st) {
+    return a.tfs ? launch_fast_vt<S, BEST, true>(a, w_bound, st) : launch_fast_vt<S, BEST, false>(a, w_bound, st);
 }
 
 template <bool BEST>
@@ -922,7 +984,7 @@ int adaptra_check_inputs(const adaptra_params_t *params, const adaptra_candidate
     fill_args(&a, params, cands, scens, workspace, ws);
     hipLaunchKernelGGL(k_zero_status, dim3(1), dim3(64), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
-    const long long n = (long long)a.S * a.C + 2ll * (a.S - 1) * a.K + 2 * a.S;
+    const long long n = (long long)a.S * a.C + 2ll * (a.S - 1) * a.K + 2 * a.S + (a.tfs ? 2ll * a.S * a.K : 0);
     hipLaunchKernelGGL(k_check_inputs, dim3(grid_for(n, 4096)), dim3(kBlock), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
     int status[4] = {0, 0, 0, 0};
@@ -959,6 +1021,47 @@ int adaptra_eval(const adaptra_params_t *params, const adaptra_candidates_t *can
     const long long tiles = ((a.C + 63) / 64) * ((a.K + 63) / 64);
     if (tiles > INT32_MAX) return ADAPTRA_EINVAL;
     hipLaunchKernelGGL(k_eval_epilogue, dim3((unsigned)tiles), dim3(kBlock), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    return ADAPTRA_OK;
+}
+
+size_t adaptra_sensitivity_workspace_bytes(const adaptra_params_t *params, int64_t n_cand, int64_t n_scen) {
+    Workspace ws;
+    if (!params || n_scen < 1 || n_scen > INT32_MAX / ADAPTRA_MAX_STAGES) return 0;
+    if (!plan_workspace(params->S, params->M, n_cand, n_scen * params->S, &ws)) return 0;
+    return ws.total;
+}
+
+int adaptra_sensitivity(const adaptra_params_t *params, const adaptra_candidates_t *cands,
+                        const adaptra_scenarios_t *scens, int32_t delta,
+                        int32_t *out_makespan, uint8_t *out_feasible, int32_t *out_sens,
+                        void *workspace, size_t workspace_bytes, void *stream) {
+    if (!params || !cands || !scens) return ADAPTRA_EINVAL;
+    if (delta < 1 || scens->n < 1 || scens->n > INT32_MAX / ADAPTRA_MAX_STAGES) return ADAPTRA_EINVAL;
+    if (params->S > 1 && !out_sens) return ADAPTRA_EINVAL;
+    // The same machinery as adaptra_eval on a scenario axis of S blocks of n: the base
+    // scenarios, then one block per link with that link's delay raised.
+    adaptra_scenarios_t wide = *scens;
+    wide.n = scens->n * params->S;
+    Workspace ws;
+    int rc = validate_common(params, cands, &wide, workspace, workspace_bytes, &ws);
+    if (rc) return rc;
+    if (cands->n * scens->n > INT32_MAX) return ADAPTRA_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    KArgs a;
+    fill_args(&a, params, cands, &wide, workspace, ws);
+    a.Kin = scens->n;
+    a.sens_delta = delta;
+    a.out_makespan = out_makespan;
+    a.out_feasible = out_feasible;
+    a.out_bubble = out_sens;
+    hipLaunchKernelGGL(k_zero_status, dim3(1), dim3(64), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_prepass, dim3(grid_for(a.C, INT32_MAX)), dim3(kBlock), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    rc = launch_resolve<false>(a, ws, cands->w_bound, st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_sens_epilogue, dim3(grid_for(a.C * a.Kin, INT32_MAX)), dim3(kBlock), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
     return ADAPTRA_OK;
 }
@@ -1006,12 +1109,14 @@ int adaptra_seed(const adaptra_params_t *params, const adaptra_scenarios_t *scen
     if (S < 1 || S > ADAPTRA_MAX_STAGES || M < 1 || M > ADAPTRA_MAX_MICROBATCHES) return ADAPTRA_EINVAL;
     if (scens->n < 1 || scens->n > INT32_MAX || !params->t_f || !params->t_b) return ADAPTRA_EINVAL;
     if (S > 1 && (!scens->c_fwd || !scens->c_bwd)) return ADAPTRA_EINVAL;
+    if ((scens->t_f == nullptr) != (scens->t_b == nullptr)) return ADAPTRA_EINVAL;
     if (out_w_init && x_max < 1) return ADAPTRA_EINVAL;
     if (out_not_absorbed && !w_current) return ADAPTRA_EINVAL;
     if (!out_w_init && !out_w_adapted && !out_not_absorbed) return ADAPTRA_EINVAL;
     SeedArgs a;
     a.S = S; a.M = M; a.x_max = x_max; a.K = scens->n;
     a.t_f = params->t_f; a.t_b = params->t_b; a.cf = scens->c_fwd; a.cb = scens->c_bwd;
+    a.tfs = scens->t_f; a.tbs = scens->t_b;
     a.w_cur = w_current; a.w_init = out_w_init; a.w_adapted = out_w_adapted; a.not_absorbed = out_not_absorbed;
     hipLaunchKernelGGL(k_seed, dim3(grid_for(a.K, INT32_MAX)), dim3(kBlock), 0, (hipStream_t)stream, a);
     ADAPTRA_LAUNCH_CHECK();

@@ -245,3 +245,18 @@ def sample_pairs(seed: int, n_cand: int, n_scen: int, n: int):
     the oracle cannot sweep."""
     rng = _rng(seed)
     return (rng.integers(0, n_cand, n, dtype=np.int64), rng.integers(0, n_scen, n, dtype=np.int64))
+
+
+def straggler_stage_times(seed: int, wl: Workload, p_slow: float = 0.15, slow_lo: float = 1.1,
+                          slow_hi: float = 4.0):
+    """Per-scenario stage times [S, K] for computation stragglers (Section 2.2): in every
+    scenario each stage is slowed with probability p_slow by a log-uniform factor in
+    [slow_lo, slow_hi] (forward and backward alike), else runs at the workload's t_f / t_b.
+    Input generation only."""
+    rng = _rng(seed)
+    S, K = wl.S, wl.n_scen
+    slow = rng.random((S, K)) < p_slow
+    factor = np.where(slow, slow_lo * (slow_hi / slow_lo) ** rng.random((S, K)), 1.0)
+    t_f = np.rint(wl.t_f[:, None] * factor)
+    t_b = np.rint(wl.t_b[:, None] * factor)
+    return _i32(t_f), _i32(t_b)

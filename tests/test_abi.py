@@ -57,6 +57,6 @@ def test_null_arguments_are_rejected_without_touching_the_gpu(binding):
     assert lib.adaptra_best(None, None, None, None, None, None, None, None, 0, None) == binding.EINVAL
     p = binding.Params(4, 8, 1, 1, None, 0, 0)                        # non-null dummies, never dereferenced
     c = binding.Candidates(10, 1, -1)
-    s = binding.Scenarios(10, 1, 1)
+    s = binding.Scenarios(10, 1, 1, None, None)
     rc = lib.adaptra_eval(ctypes.byref(p), ctypes.byref(c), ctypes.byref(s), 1, None, 1, None, 0, None)
     assert rc == binding.EWORKSPACE

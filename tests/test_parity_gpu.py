@@ -415,3 +415,152 @@ def test_zb_parity(lib, oracle, seed_, S, N, C, K):
         for k in range(0, K, max(1, K // 6)):
             rep = oracle.zb_simulate(S, N, t_f, t_b, t_w, cf[:, k], cb[:, k], order=gen["order"])
             assert mkp[k, c] == rep["makespan"], (c, k)
+
+
+# ----------------------------------------------------------------------------------------
+# Per-scenario stage times (computation stragglers) and link sensitivities
+STAGE_TIME_CASES = [
+    # seed, S, M, C, K, kwargs
+    (60, 1, 9, 40, 70, dict(hist_bins=8, hist_shift=8)),
+    (61, 2, 12, 100, 64, {}),
+    (62, 3, 7, 90, 11, {}),                                    # general kernel only
+    (63, 4, 16, 130, 129, dict(hist_bins=32, hist_shift=8)),
+    (64, 8, 32, 300, 100, dict(d_max=6, hist_bins=64, hist_shift=10)),
+    (65, 8, 90, 100, 64, dict(w_extra=50)),                    # deeper than the LDS ring
+    (66, 16, 48, 200, 65, dict(d_max=4)),
+    (67, 32, 64, 80, 70, dict(d_max=4, hist_bins=16, hist_shift=12)),
+    (68, 64, 80, 30, 5, dict(d_max=2)),
+    (69, 8, 24, 50, 3, {}),                                    # few scenarios
+]
+
+
+def _with_stage_times(binding, wl, tfs, tbs, mode, fn):
+    import torch
+    binding.adaptra_set_kernel_mode(mode)
+    prob = binding.Problem.from_workload(wl, t_f_scen=tfs, t_b_scen=tbs)
+    out = fn(prob)
+    torch.cuda.synchronize()
+    binding.adaptra_set_kernel_mode(0)
+    return [None if t is None else t.cpu().numpy() for t in out]
+
+
+@pytest.mark.parametrize("seed,S,M,C,K,kw", STAGE_TIME_CASES,
+                         ids=[f"S{r[1]}_M{r[2]}_C{r[3]}_K{r[4]}" for r in STAGE_TIME_CASES])
+def test_per_scenario_stage_times_parity(lib, oracle, seed, S, M, C, K, kw):
+    wl = workloads.random_workload(seed, S, M, C, K, **kw)
+    tfs, tbs = workloads.straggler_stage_times(seed + 1000, wl)
+    assert (tfs != wl.t_f[:, None]).any()
+    say(f"stage-time scenarios {wl.name}")
+    ref = oracle.eval_scenario_times(S, M, tfs, tbs, wl.mem_cap, wl.w, wl.c_fwd, wl.c_bwd)
+    rbest = oracle.best_from_eval(ref["makespan"], ref["flag"], ref["bubble"])
+    rhist = oracle.hist_from_eval(ref["bubble"], ref["flag"], wl.hist_bins, wl.hist_shift) if wl.hist_bins else None
+    for mode in (0, 1, 2):
+        say(f"  eval mode {mode}")
+        mk, bub, fl = _with_stage_times(lib, wl, tfs, tbs, mode, lambda p: lib.adaptra_eval(p))
+        assert np.array_equal(fl, ref["flag"])
+        assert np.array_equal(mk, ref["makespan"]), f"makespan mismatch mode {mode}"
+        assert np.array_equal(bub, ref["bubble"]), f"bubble mismatch mode {mode}"
+        say(f"  best mode {mode}")
+        idx, bmk, bbub, hist = _with_stage_times(lib, wl, tfs, tbs, mode, lambda p: lib.adaptra_best(p))
+        assert np.array_equal(idx, rbest["best_idx"]), f"best_idx mismatch mode {mode}"
+        assert np.array_equal(bmk, rbest["best_makespan"])
+        assert np.array_equal(bbub, rbest["best_bubble"])
+        if rhist is not None:
+            assert np.array_equal(hist.astype(np.uint64), rhist)
+
+
+def test_per_scenario_stage_times_checked_and_seeded(lib, oracle):
+    """adaptra_check_inputs scans the per-scenario times too, and adaptra_seed (Algorithm 2,
+    Eq. (1)) uses them."""
+    import torch
+    from oracle import seed as oseed
+    wl = workloads.random_workload(70, 6, 40, 20, 50)
+    np.maximum(wl.w, 0, out=wl.w)                       # the generator plants negative w to test the clamp
+    tfs, tbs = workloads.straggler_stage_times(71, wl, p_slow=0.4)
+    prob = lib.Problem.from_workload(wl, t_f_scen=tfs, t_b_scen=tbs)
+    assert lib.adaptra_check_inputs(prob) == lib.OK
+    w_cur = torch.tensor(oseed.to_w(oseed.get_init_warmup_fwds(wl.S, 12)), dtype=torch.int32, device="cuda:0")
+    w_init, w_ad, na = lib.adaptra_seed(prob, 12, w_current=w_cur, want_not_absorbed=True)
+    torch.cuda.synchronize()
+    w_ad, na = w_ad.cpu().numpy(), na.cpu().numpy()
+    for k in range(wl.n_scen):
+        x = oseed.get_adapted_warmup_fwds(wl.S, wl.M, tfs[:, k], tbs[:, k], wl.c_fwd[:, k], wl.c_bwd[:, k])
+        assert list(w_ad[:, k]) == oseed.to_w(x), k
+        ab = oseed.absorbed(wl.S, tfs[:, k], tbs[:, k], w_cur.cpu().numpy(), wl.c_fwd[:, k], wl.c_bwd[:, k])
+        assert list(na[:, k]) == [0 if a else 1 for a in ab], k
+    bad = tfs.copy()
+    bad[2, 7] = -1
+    prob = lib.Problem.from_workload(wl, t_f_scen=bad, t_b_scen=tbs)
+    assert lib.adaptra_check_inputs(prob) == lib.ERANGE
+    half = lib.Problem.from_workload(wl, t_f_scen=tfs, t_b_scen=None)      # both or neither
+    with pytest.raises(lib.AdaptraError) as e:
+        lib.adaptra_eval(half)
+    assert e.value.code == lib.EINVAL
+
+
+SENS_CASES = [
+    # seed, S, M, C, K, delta, stage times per scenario, kwargs
+    (80, 1, 5, 10, 20, 3, False, {}),
+    (81, 2, 10, 40, 64, 1, False, {}),
+    (82, 3, 9, 30, 17, 25, False, {}),
+    (83, 4, 16, 70, 65, 7, True, {}),
+    (84, 8, 32, 40, 100, 100, False, dict(d_max=6)),
+    (85, 8, 60, 16, 40, 1, True, dict(w_extra=30)),
+    (86, 16, 40, 20, 30, 13, False, dict(d_max=3)),
+    (87, 32, 64, 6, 70, 50, True, dict(d_max=3)),
+    (88, 64, 70, 4, 9, 5, False, dict(d_max=2)),
+    (89, 8, 24, 1, 1, 9, False, {}),
+]
+
+
+@pytest.mark.parametrize("seed,S,M,C,K,delta,vt,kw", SENS_CASES,
+                         ids=[f"S{r[1]}_M{r[2]}_C{r[3]}_K{r[4]}" for r in SENS_CASES])
+def test_sensitivity_parity(lib, oracle, seed, S, M, C, K, delta, vt, kw):
+    wl = workloads.random_workload(seed, S, M, C, K, **kw)
+    tfs, tbs = workloads.straggler_stage_times(seed + 1000, wl) if vt else (None, None)
+    say(f"sensitivity {wl.name} delta {delta} stage-times {vt}")
+    ref = oracle.sensitivity(S, M, wl.t_f, wl.t_b, wl.mem_cap, wl.w, wl.c_fwd, wl.c_bwd, delta,
+                             t_f_scen=tfs, t_b_scen=tbs)
+    assert ref["sens"].shape == (C, S - 1, K)
+    for mode in (0, 1, 2):
+        say(f"  mode {mode}")
+        mk, fl, sens = _with_stage_times(lib, wl, tfs, tbs, mode, lambda p: lib.adaptra_sensitivity(p, delta))
+        assert np.array_equal(fl, ref["flag"])
+        assert np.array_equal(mk, ref["makespan"]), f"makespan mismatch mode {mode}"
+        assert np.array_equal(sens, ref["sens"]), f"sensitivity mismatch mode {mode}"
+
+
+def test_sensitivity_rejects_bad_arguments(lib):
+    wl = workloads.random_workload(90, 4, 8, 5, 6)
+    prob = lib.Problem.from_workload(wl)
+    with pytest.raises(lib.AdaptraError) as e:
+        lib.adaptra_sensitivity(prob, 0)
+    assert e.value.code == lib.EINVAL
+    import torch
+    small = torch.empty(256, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(lib.AdaptraError) as e:
+        lib.adaptra_sensitivity(prob, 1, workspace=small)
+    assert e.value.code == lib.EWORKSPACE
+
+
+def test_sensitivity_full_size_sampled(lib, oracle):
+    """Configuration 2's scenarios against a slice of its candidates, at the launch shape of a
+    real call; the oracle recomputes sampled (candidate, link, scenario) entries one by one."""
+    import torch
+    wl = workloads.config(2)
+    cand = np.arange(0, wl.n_cand, max(1, wl.n_cand // 64))[:64]
+    sub = workloads.Workload(**{**wl.__dict__, "w": np.ascontiguousarray(wl.w[:, cand]), "name": wl.name + "-sens"})
+    say(f"sensitivity {sub.name}: {sub.n_cand} candidates x {sub.n_scen} scenarios x {sub.S - 1} links")
+    prob = lib.Problem.from_workload(sub)
+    mk, fl, sens = lib.adaptra_sensitivity(prob, 10)
+    torch.cuda.synchronize()
+    mk, fl, sens = mk.cpu().numpy(), fl.cpu().numpy(), sens.cpu().numpy()
+    rng = np.random.default_rng(5)
+    ks = rng.integers(0, sub.n_scen, 48)
+    ref = oracle.sensitivity(sub.S, sub.M, sub.t_f, sub.t_b, sub.mem_cap, sub.w,
+                             sub.c_fwd[:, ks], sub.c_bwd[:, ks], 10)
+    assert np.array_equal(mk[:, ks], ref["makespan"])
+    assert np.array_equal(fl[:, ks], ref["flag"])
+    assert np.array_equal(sens[:, :, ks], ref["sens"])
+    live = (fl & 2) == 0
+    assert (sens[np.broadcast_to(live[:, None, :], sens.shape)] >= 0).all()
