@@ -254,6 +254,28 @@ def main():
                      "includes": "output allocation by the binding"}
         del sws, sprob2
 
+    # guided search (neighbourhood descent on batched evaluation) over the same scenarios,
+    # from Algorithm 1's plan; compared with the exhaustive argmin over the workload's candidates
+    search_info = None
+    if not args.no_sens and S > 1:
+        x_max = int(wl.mem_cap[0]) if wl.mem_cap is not None else S
+        w_init, _, _ = binding.adaptra_seed(prob, x_max, want_adapted=False)
+        sws = torch.empty(binding.load().adaptra_search_workspace_bytes(ctypes.byref(prob.params), K, 0),
+                          dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        sw, smk, rounds, evaluated = binding.adaptra_search(prob, w_init, 0, 500, workspace=sws)
+        torch.cuda.synchronize()
+        t_search = time.perf_counter() - t0
+        found = (bmk != 2 ** 31 - 1) & (smk != 2 ** 31 - 1)
+        ratio = (smk[found].double() / bmk[found].double())
+        search_info = {"neighbourhood": 0, "start": "Algorithm 1 at x_max = mem_cap[0]", "rounds": rounds,
+                       "pairs_evaluated": evaluated, "ms": t_search * 1e3,
+                       "evaluations_per_s": evaluated / t_search,
+                       "makespan_vs_exhaustive_over_candidates_mean": float(ratio.mean()) if ratio.numel() else None,
+                       "makespan_vs_exhaustive_over_candidates_max": float(ratio.max()) if ratio.numel() else None}
+        del sws
+
     flags = fl[0].cpu().numpy()                    # the flag depends on the candidate only
     n_live = int(((flags & 2) == 0).sum())
     n_feasible = int((flags == 1).sum())
@@ -295,6 +317,8 @@ def main():
     if vt_info:
         out["stage_time_scenarios"] = vt_info
         out["sensitivity"] = sens_info
+    if search_info:
+        out["search"] = search_info
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))

@@ -21,7 +21,8 @@ ERROR_NAMES = {0: "ADAPTRA_OK", 1: "ADAPTRA_EINVAL", 2: "ADAPTRA_EWORKSPACE", 3:
 FLAG_FEASIBLE, FLAG_DEADLOCK, FLAG_MEMCAP = 1, 2, 4
 INT32_MAX = 2 ** 31 - 1
 
-EXPORTS = ("adaptra_workspace_bytes", "adaptra_check_inputs", "adaptra_eval", "adaptra_best", "adaptra_seed",
+EXPORTS = ("adaptra_workspace_bytes", "adaptra_best_workspace_bytes", "adaptra_search_workspace_bytes", "adaptra_search",
+           "adaptra_check_inputs", "adaptra_eval", "adaptra_best", "adaptra_seed",
            "adaptra_sensitivity_workspace_bytes", "adaptra_sensitivity",
            "adaptra_zb_workspace_bytes", "adaptra_zb_eval",
            "adaptra_set_kernel_mode", "adaptra_set_resolve_events", "adaptra_valu_probe", "adaptra_last_hip_error",
@@ -67,6 +68,13 @@ def load() -> ctypes.CDLL:
         vp, sz = ctypes.c_void_p, ctypes.c_size_t
         lib.adaptra_workspace_bytes.restype = sz
         lib.adaptra_workspace_bytes.argtypes = [P, ctypes.c_int64, ctypes.c_int64]
+        lib.adaptra_best_workspace_bytes.restype = sz
+        lib.adaptra_best_workspace_bytes.argtypes = [P, ctypes.c_int64, ctypes.c_int64]
+        lib.adaptra_search_workspace_bytes.restype = sz
+        lib.adaptra_search_workspace_bytes.argtypes = [P, ctypes.c_int64, ctypes.c_int32]
+        lib.adaptra_search.restype = ctypes.c_int
+        lib.adaptra_search.argtypes = [P, Sc, vp, ctypes.c_int32, ctypes.c_int32, vp, vp,
+                                       ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64), vp, sz, vp]
         lib.adaptra_check_inputs.restype = ctypes.c_int
         lib.adaptra_check_inputs.argtypes = [P, C, Sc, vp, sz, vp]
         lib.adaptra_eval.restype = ctypes.c_int
@@ -252,6 +260,29 @@ def adaptra_sensitivity(prob: Problem, delta: int = 1, *, want_makespan: bool = 
                                     workspace.data_ptr(), workspace.numel(), _stream(stream))
     _raise(rc, "adaptra_sensitivity")
     return mk, fl, sens
+
+
+def adaptra_search(prob: Problem, w_start, neighbourhood: int = 0, max_iters: int = 1000, *, workspace=None,
+                   stream=None):
+    """Run the guided search (synchronous); prob's candidates are ignored.  Returns
+    (w [S,K], makespan [K], rounds, pairs evaluated)."""
+    import torch
+    dev = prob.device
+    _check_i32(w_start, "w_start", (prob.S,))
+    w = torch.empty((prob.S, prob.K), dtype=torch.int32, device=dev)
+    mk = torch.empty(prob.K, dtype=torch.int32, device=dev)
+    if workspace is None:
+        n = int(load().adaptra_search_workspace_bytes(ctypes.byref(prob.params), prob.K, int(neighbourhood)))
+        if n == 0:
+            raise AdaptraError(EINVAL, "adaptra_search_workspace_bytes")
+        workspace = torch.empty(n, dtype=torch.uint8, device=dev)
+    rounds, evaluated = ctypes.c_int32(0), ctypes.c_int64(0)
+    rc = load().adaptra_search(ctypes.byref(prob.params), ctypes.byref(prob.scens), w_start.data_ptr(),
+                               int(neighbourhood), int(max_iters), w.data_ptr(), mk.data_ptr(),
+                               ctypes.byref(rounds), ctypes.byref(evaluated),
+                               workspace.data_ptr(), workspace.numel(), _stream(stream))
+    _raise(rc, "adaptra_search")
+    return w, mk, int(rounds.value), int(evaluated.value)
 
 
 def adaptra_zb_eval(prob: Problem, t_w, plan_scenario: int = -1, *, want_bubble: bool = True,

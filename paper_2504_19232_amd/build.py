@@ -6,7 +6,8 @@ import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
-SOURCES = [os.path.join(_HERE, "csrc", "adaptra.hip"), os.path.join(_HERE, "csrc", "adaptra_zb.hip")]
+SOURCES = [os.path.join(_HERE, "csrc", "adaptra.hip"), os.path.join(_HERE, "csrc", "adaptra_zb.hip"),
+           os.path.join(_HERE, "csrc", "adaptra_search.hip")]
 INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(_HERE, "libadaptra.so")
 
@@ -14,6 +15,7 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
+    "-Wno-int-to-pointer-cast",     # LDS addresses are 32-bit integers on purpose (address space 3)
 ]
 
 

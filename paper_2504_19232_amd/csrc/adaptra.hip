@@ -791,7 +791,7 @@ long long general_thread_count(int S, int M) {
     return nt / kBlock * kBlock;
 }
 
-bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws) {
+bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws, bool with_mkt = true) {
     if (S < 1 || S > ADAPTRA_MAX_STAGES || M < 1 || M > ADAPTRA_MAX_MICROBATCHES) return false;
     if (C < 1 || C > INT32_MAX || K < 1 || K > INT32_MAX) return false;
     ws->wq_stride = (S + 3) & ~3;
@@ -803,7 +803,7 @@ bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws) {
     ws->off_keys = o;    o += align256((size_t)K * 8);
     ws->off_status = o;  o += 256;
     ws->off_scratch = o; o += align256((size_t)ws->general_threads * (2 * S + M) * 4);
-    ws->off_mkt = o;     o += align256((size_t)C * (size_t)K * 4);
+    ws->off_mkt = o;     o += with_mkt ? align256((size_t)C * (size_t)K * 4) : 0;   // last: the search needs none
     ws->total = o;
     return true;
 }
@@ -836,9 +836,9 @@ int grid_for(long long n, long long cap = 1 << 20) {
 
 int validate_common(const adaptra_params_t *p, const adaptra_candidates_t *cd,
                     const adaptra_scenarios_t *sc, void *workspace, size_t workspace_bytes,
-                    Workspace *ws) {
+                    Workspace *ws, bool with_mkt = true) {
     if (!p || !cd || !sc) return ADAPTRA_EINVAL;
-    if (!plan_workspace(p->S, p->M, cd->n, sc->n, ws)) return ADAPTRA_EINVAL;
+    if (!plan_workspace(p->S, p->M, cd->n, sc->n, ws, with_mkt)) return ADAPTRA_EINVAL;
     if (!p->t_f || !p->t_b || !cd->w) return ADAPTRA_EINVAL;
     if (p->S > 1 && (!sc->c_fwd || !sc->c_bwd)) return ADAPTRA_EINVAL;
     if ((sc->t_f == nullptr) != (sc->t_b == nullptr)) return ADAPTRA_EINVAL;
@@ -973,6 +973,12 @@ size_t adaptra_workspace_bytes(const adaptra_params_t *params, int64_t n_cand, i
     return ws.total;
 }
 
+size_t adaptra_best_workspace_bytes(const adaptra_params_t *params, int64_t n_cand, int64_t n_scen) {
+    Workspace ws;
+    if (!params || !plan_workspace(params->S, params->M, n_cand, n_scen, &ws, false)) return 0;
+    return ws.total;
+}
+
 int adaptra_check_inputs(const adaptra_params_t *params, const adaptra_candidates_t *cands,
                          const adaptra_scenarios_t *scens,
                          void *workspace, size_t workspace_bytes, void *stream) {
@@ -1072,7 +1078,7 @@ int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *can
                  uint64_t *out_hist,
                  void *workspace, size_t workspace_bytes, void *stream) {
     Workspace ws;
-    int rc = validate_common(params, cands, scens, workspace, workspace_bytes, &ws);
+    int rc = validate_common(params, cands, scens, workspace, workspace_bytes, &ws, false);
     if (rc) return rc;
     if (!out_best_idx || !out_best_makespan) return ADAPTRA_EINVAL;
     if (params->hist_bins < 0 || params->hist_bins > 65536) return ADAPTRA_EINVAL;

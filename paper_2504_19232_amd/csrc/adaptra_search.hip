@@ -1,0 +1,233 @@
+// adaptra_search.hip -- guided search over warm-up vectors for gfx950 (MI355X).
+//
+// A neighbourhood descent over the slacks Delta_i = w_i - w_{i+1} (the coordinates of the
+// paper's Section 4.2 planning) for schedule spaces too large to enumerate.  The work of a
+// round is one batched evaluation of the analytical model (Section 3.1) -- adaptra_best over
+// a pool of candidates x all scenarios -- so the search runs at the speed of the evaluation
+// kernels; the kernels here only build the pool and move the points.
+//
+//   k_search_init      every scenario's point = w_start clamped, makespan = INT32_MAX
+//   k_search_is_first  per scenario: is it the lowest scenario holding its point?
+//   k_search_compact   ordered list of those scenarios (one block, ballot prefix sums)
+//   k_search_pool      pool[s][d * (moves + 1) + j] = point d after move j, clamped
+//   k_search_advance   a scenario adopts its best pool entry iff strictly better
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "adaptra.h"
+#include "adaptra_internal.h"
+
+namespace {
+
+using adaptra_detail::blocks_for;
+using adaptra_detail::hip_fail;
+using adaptra_detail::kThreadsPerBlock;
+
+constexpr int kMaxSearchScenarios = 32768;
+
+struct SearchArgs {
+    int S, M, nb, n_moves;
+    long long K, C;               // scenarios; pool entries this round
+    const int *w_start;
+    int *cur_w, *cur_mk;          // [S][K], [K]: the outputs double as the state
+    unsigned char *is_first;      // [K]
+    int *list;                    // [K] scenarios that are first holders, ascending
+    int *counters;                // [0] distinct points, [1] scenarios that moved
+    int *pool;                    // [S][C]
+    const int *best_idx, *best_mk;
+};
+
+__device__ __forceinline__ int clamp_w(int w, int M) { return w < 0 ? 0 : (w > M - 1 ? M - 1 : w); }
+
+__global__ void k_search_init(SearchArgs a) {
+    const long long k = (long long)blockIdx.x * kThreadsPerBlock + threadIdx.x;
+    if (k >= a.K) return;
+    for (int s = 0; s < a.S; ++s) a.cur_w[(long long)s * a.K + k] = clamp_w(a.w_start[s], a.M);
+    a.cur_mk[k] = INT32_MAX;
+}
+
+// Scenario k is a first holder iff no lower scenario has the same point.  The scan stops at
+// the first match, so it is short while the points still coincide (the usual case); all
+// lanes of a wavefront read the same j, one broadcast load per stage.
+__global__ void k_search_is_first(SearchArgs a) {
+    const long long k = (long long)blockIdx.x * kThreadsPerBlock + threadIdx.x;
+    if (k == 0) { a.counters[0] = 0; a.counters[1] = 0; }
+    if (k >= a.K) return;
+    bool first = true;
+    for (long long j = 0; j < k && first; ++j) {
+        bool same = true;
+        for (int s = 0; s < a.S && same; ++s) same = a.cur_w[(long long)s * a.K + j] == a.cur_w[(long long)s * a.K + k];
+        if (same) first = false;
+    }
+    a.is_first[k] = first ? 1 : 0;
+}
+
+// One block walks the scenarios in chunks of its size and appends the first holders in
+// ascending order (ballot + popcount inside a wavefront, a small LDS scan across them).
+__global__ __launch_bounds__(1024) void k_search_compact(SearchArgs a) {
+    __shared__ int wave_count[16];
+    __shared__ int base;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (threadIdx.x == 0) base = 0;
+    __syncthreads();
+    for (long long k0 = 0; k0 < a.K; k0 += 1024) {
+        const long long k = k0 + threadIdx.x;
+        const bool first = k < a.K && a.is_first[k];
+        const unsigned long long m = __ballot(first);
+        if (lane == 0) wave_count[wv] = __popcll(m);
+        __syncthreads();
+        int before = base;
+        for (int i = 0; i < wv; ++i) before += wave_count[i];
+        if (first) a.list[before + __popcll(m & ((1ull << lane) - 1ull))] = (int)k;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int t = 0;
+            for (int i = 0; i < 16; ++i) t += wave_count[i];
+            base += t;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) a.counters[0] = base;
+}
+
+// Move j of the neighbourhood: j = 0 keeps the point; otherwise (j - 1) / 2 numbers the stage
+// range [lo, hi] and the parity of j - 1 picks -1 (even) or +1 (odd).
+__device__ __forceinline__ void decode_move(int nb, int S, int j, int *lo, int *hi, int *sign) {
+    if (j == 0) { *lo = 0; *hi = -1; *sign = 0; return; }
+    int r = (j - 1) >> 1;
+    *sign = ((j - 1) & 1) ? 1 : -1;
+    if (nb == 0) { *lo = 0; *hi = r; return; }
+    int a = 0;
+    while (r >= S - a) { r -= S - a; ++a; }      // ranges are numbered a = 0.., b = a..S-1
+    *lo = a; *hi = a + r;
+}
+
+__global__ void k_search_pool(SearchArgs a) {
+    const long long c = (long long)blockIdx.x * kThreadsPerBlock + threadIdx.x;
+    if (c >= a.C) return;
+    const int per_point = a.n_moves + 1;
+    const long long d = c / per_point;
+    const int j = (int)(c % per_point);
+    const long long k = a.list[d];
+    int lo, hi, sign;
+    decode_move(a.nb, a.S, j, &lo, &hi, &sign);
+    for (int s = 0; s < a.S; ++s) {
+        const int w = a.cur_w[(long long)s * a.K + k] + (s >= lo && s <= hi ? sign : 0);
+        a.pool[(long long)s * a.C + c] = clamp_w(w, a.M);
+    }
+}
+
+__global__ void k_search_advance(SearchArgs a) {
+    const long long k = (long long)blockIdx.x * kThreadsPerBlock + threadIdx.x;
+    if (k >= a.K) return;
+    const int bi = a.best_idx[k];
+    if (bi >= 0 && a.best_mk[k] < a.cur_mk[k]) {
+        for (int s = 0; s < a.S; ++s) a.cur_w[(long long)s * a.K + k] = a.pool[(long long)s * a.C + bi];
+        a.cur_mk[k] = a.best_mk[k];
+        atomicAdd(&a.counters[1], 1);
+    }
+}
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct SearchPlan {
+    int n_moves;
+    long long c_max;
+    size_t off_first, off_list, off_counters, off_pool, off_best_idx, off_best_mk, off_best_ws, best_ws_bytes, total;
+};
+
+bool plan_search(const adaptra_params_t *p, long long K, int nb, SearchPlan *pl) {
+    if (!p || p->S < 1 || p->S > ADAPTRA_MAX_STAGES || p->M < 1 || p->M > ADAPTRA_MAX_MICROBATCHES) return false;
+    if (K < 1 || K > kMaxSearchScenarios || (nb != 0 && nb != 1)) return false;
+    pl->n_moves = nb == 0 ? 2 * p->S : p->S * (p->S + 1);
+    pl->c_max = K * (pl->n_moves + 1);
+    if (pl->c_max > INT32_MAX) return false;
+    pl->best_ws_bytes = adaptra_best_workspace_bytes(p, pl->c_max, K);
+    if (pl->best_ws_bytes == 0) return false;
+    size_t o = 0;
+    pl->off_first = o;    o += align256((size_t)K);
+    pl->off_list = o;     o += align256((size_t)K * 4);
+    pl->off_counters = o; o += 256;
+    pl->off_pool = o;     o += align256((size_t)p->S * (size_t)pl->c_max * 4);
+    pl->off_best_idx = o; o += align256((size_t)K * 4);
+    pl->off_best_mk = o;  o += align256((size_t)K * 4);
+    pl->off_best_ws = o;  o += align256(pl->best_ws_bytes);
+    pl->total = o;
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t adaptra_search_workspace_bytes(const adaptra_params_t *params, int64_t n_scen, int32_t neighbourhood) {
+    SearchPlan pl;
+    return plan_search(params, n_scen, neighbourhood, &pl) ? pl.total : 0;
+}
+
+int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *scens,
+                   const int32_t *w_start, int32_t neighbourhood, int32_t max_iters,
+                   int32_t *out_w, int32_t *out_makespan, int32_t *out_rounds, int64_t *out_evaluated,
+                   void *workspace, size_t workspace_bytes, void *stream) {
+    if (!params || !scens || !w_start || !out_w || !out_makespan || max_iters < 1) return ADAPTRA_EINVAL;
+    SearchPlan pl;
+    if (!plan_search(params, scens->n, neighbourhood, &pl)) return ADAPTRA_EINVAL;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < pl.total) return ADAPTRA_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    char *base = (char *)workspace;
+    SearchArgs a{};
+    a.S = params->S; a.M = params->M; a.nb = neighbourhood; a.n_moves = pl.n_moves;
+    a.K = scens->n;
+    a.w_start = w_start;
+    a.cur_w = out_w; a.cur_mk = out_makespan;
+    a.is_first = (unsigned char *)(base + pl.off_first);
+    a.list = (int *)(base + pl.off_list);
+    a.counters = (int *)(base + pl.off_counters);
+    a.pool = (int *)(base + pl.off_pool);
+    int *best_idx = (int *)(base + pl.off_best_idx), *best_mk = (int *)(base + pl.off_best_mk);
+    a.best_idx = best_idx; a.best_mk = best_mk;
+    adaptra_params_t bp = *params;
+    bp.hist_bins = 0; bp.hist_shift = 0;
+    const int kblocks = blocks_for(a.K, INT32_MAX);
+
+    hipLaunchKernelGGL(k_search_init, dim3(kblocks), dim3(kThreadsPerBlock), 0, st, a);
+    ADAPTRA_CHECK_LAUNCH();
+    int rounds = 0;
+    long long evaluated = 0;
+    int counters[2] = {0, 0};
+    for (;;) {
+        // step 1: distinct points (k_search_is_first also clears both counters)
+        hipLaunchKernelGGL(k_search_is_first, dim3(kblocks), dim3(kThreadsPerBlock), 0, st, a);
+        ADAPTRA_CHECK_LAUNCH();
+        hipLaunchKernelGGL(k_search_compact, dim3(1), dim3(1024), 0, st, a);
+        ADAPTRA_CHECK_LAUNCH();
+        hipError_t e = hipMemcpyAsync(counters, a.counters, sizeof(int), hipMemcpyDeviceToHost, st);
+        if (e != hipSuccess) return hip_fail(e);
+        if ((e = hipStreamSynchronize(st)) != hipSuccess) return hip_fail(e);
+        const long long D = counters[0];
+        if (D < 1 || D > a.K) return ADAPTRA_EHIP;            // cannot happen: scenario 0 is always first
+        ++rounds;
+        // step 2: the pool
+        a.C = D * (pl.n_moves + 1);
+        hipLaunchKernelGGL(k_search_pool, dim3(blocks_for(a.C, INT32_MAX)), dim3(kThreadsPerBlock), 0, st, a);
+        ADAPTRA_CHECK_LAUNCH();
+        // step 3: batched evaluation and per-scenario argmin
+        adaptra_candidates_t cd{a.C, a.pool, -1};
+        int rc = adaptra_best(&bp, &cd, scens, best_idx, best_mk, nullptr, nullptr,
+                          base + pl.off_best_ws, pl.best_ws_bytes, stream);
+        if (rc) return rc;
+        evaluated += a.C * a.K;
+        // step 4: move
+        hipLaunchKernelGGL(k_search_advance, dim3(kblocks), dim3(kThreadsPerBlock), 0, st, a);
+        ADAPTRA_CHECK_LAUNCH();
+        e = hipMemcpyAsync(counters, a.counters, 2 * sizeof(int), hipMemcpyDeviceToHost, st);
+        if (e != hipSuccess) return hip_fail(e);
+        if ((e = hipStreamSynchronize(st)) != hipSuccess) return hip_fail(e);
+        if (counters[1] == 0 || rounds >= max_iters) break;
+    }
+    if (out_rounds) *out_rounds = rounds;
+    if (out_evaluated) *out_evaluated = evaluated;
+    return ADAPTRA_OK;
+}
+
+}  // extern "C"

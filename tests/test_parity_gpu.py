@@ -564,3 +564,84 @@ def test_sensitivity_full_size_sampled(lib, oracle):
     assert np.array_equal(sens[:, :, ks], ref["sens"])
     live = (fl & 2) == 0
     assert (sens[np.broadcast_to(live[:, None, :], sens.shape)] >= 0).all()
+
+
+# ----------------------------------------------------------------------------------------
+# Guided search
+SEARCH_CASES = [
+    # seed, S, M, K, neighbourhood, max_iters, stage times per scenario, kwargs
+    (100, 1, 6, 9, 0, 50, False, {}),
+    (101, 2, 60, 7, 0, 50, False, dict(c_hi=60, cap=False)),
+    (102, 3, 12, 5, 1, 50, False, {}),                     # general kernel (S = 3, K < 6)
+    (103, 4, 16, 70, 0, 50, False, {}),
+    (104, 4, 16, 33, 1, 50, True, {}),
+    (105, 8, 32, 64, 0, 50, False, dict(c_hi=3000)),
+    (106, 8, 32, 20, 1, 4, False, dict(c_hi=3000)),        # stopped by max_iters
+    (107, 16, 40, 12, 0, 50, True, dict(c_hi=2000, cap=False)),
+    (108, 5, 20, 1100, 0, 50, False, {}),                  # more scenarios than one compaction chunk
+]
+
+
+@pytest.mark.parametrize("seed,S,M,K,nb,iters,vt,kw", SEARCH_CASES,
+                         ids=[f"S{r[1]}_M{r[2]}_K{r[3]}_nb{r[4]}" for r in SEARCH_CASES])
+def test_guided_search_parity(lib, oracle, seed, S, M, K, nb, iters, vt, kw):
+    import torch
+    from oracle import search as osearch
+    wl = workloads.random_workload(seed, S, M, 4, K, **kw)
+    tfs, tbs = workloads.straggler_stage_times(seed + 1000, wl) if vt else (None, None)
+    start = np.arange(S - 1, -1, -1, dtype=np.int32)        # plain 1F1B
+    cap = None if wl.mem_cap is None else np.maximum(wl.mem_cap, start + 1).astype(np.int32)
+    wl.mem_cap = cap
+    say(f"search {wl.name} neighbourhood {nb}")
+    ref = osearch.search(S, M, wl.t_f, wl.t_b, cap, start, wl.c_fwd, wl.c_bwd, neighbourhood=nb,
+                         max_iters=iters, t_f_scen=tfs, t_b_scen=tbs)
+    for mode in (0, 1):
+        lib.adaptra_set_kernel_mode(mode)
+        prob = lib.Problem.from_workload(wl, t_f_scen=tfs, t_b_scen=tbs)
+        w, mk, rounds, evaluated = lib.adaptra_search(prob, torch.from_numpy(start).cuda(), nb, iters)
+        lib.adaptra_set_kernel_mode(0)
+        assert rounds == ref["rounds"], f"mode {mode}"
+        assert evaluated == ref["evaluated"]
+        assert np.array_equal(mk.cpu().numpy(), ref["makespan"])
+        assert np.array_equal(w.cpu().numpy(), ref["w"])
+
+
+def test_guided_search_arguments(lib):
+    import torch
+    wl = workloads.random_workload(110, 4, 8, 3, 6)
+    prob = lib.Problem.from_workload(wl)
+    start = torch.zeros(4, dtype=torch.int32, device="cuda:0")
+    for bad in (dict(neighbourhood=2), dict(max_iters=0)):
+        with pytest.raises(lib.AdaptraError) as e:
+            lib.adaptra_search(prob, start, **bad)
+        assert e.value.code == lib.EINVAL
+    with pytest.raises(lib.AdaptraError) as e:
+        lib.adaptra_search(prob, start, workspace=torch.empty(512, dtype=torch.uint8, device="cuda:0"))
+    assert e.value.code == lib.EWORKSPACE
+
+
+@pytest.mark.parametrize("index", [1, 2])
+def test_guided_search_against_exhaustive_argmin(lib, oracle, index):
+    """Configurations 1 and 2: the search, started from Algorithm 1's plan under the
+    configuration's memory caps, against adaptra_best over the configuration's own candidate
+    set.  The search looks at vectors outside that set too, so it may win; what must hold is
+    that every point it returns is feasible and priced exactly as the oracle prices it, and
+    that it does not lose by much where the candidate set contains the optimum."""
+    import torch
+    from oracle import seed as oseed
+    wl = workloads.config(index)
+    S, M, K = wl.S, wl.M, wl.n_scen
+    x_max = int(wl.mem_cap[0]) if wl.mem_cap is not None else S
+    start = np.array(oseed.to_w(oseed.get_init_warmup_fwds(S, x_max)), dtype=np.int32)
+    prob = lib.Problem.from_workload(wl)
+    idx, bmk, _, _ = lib.adaptra_best(prob)
+    w, mk, rounds, evaluated = lib.adaptra_search(prob, torch.from_numpy(start).cuda(), 1, 200)
+    torch.cuda.synchronize()
+    w, mk, bmk = w.cpu().numpy(), mk.cpu().numpy().astype(np.int64), bmk.cpu().numpy().astype(np.int64)
+    say(f"  config {index}: {rounds} rounds, {evaluated} pairs; search/best makespan ratio "
+        f"mean {np.mean(mk / bmk):.4f} max {np.max(mk / bmk):.4f}; search wins {int((mk < bmk).sum())}/{K}")
+    ref = oracle.eval_pairs(S, M, wl.t_f, wl.t_b, wl.mem_cap, w, wl.c_fwd, wl.c_bwd,
+                            pair_cand=np.arange(K), pair_scen=np.arange(K), want_bubble=False)
+    assert np.all(ref["flag"] == 1)
+    assert np.array_equal(ref["makespan"].astype(np.int64), mk)
+    assert np.max(mk / bmk) < 1.05
