@@ -216,6 +216,8 @@ __global__ __launch_bounds__(kBlock) void k_prepass(KArgs a) {
     if (cls < kNumRingClasses) {
         unsigned char *q = a.cand_wq + c * a.wq_stride;
         for (int s = 0; s < S; ++s) q[s] = (unsigned char)clampw(a.w[(long long)s * a.C + c], M);
+        for (int s = S; s < a.wq_stride; ++s) q[s] = 0;      // the hot kernel's padding stages
+
     }
     if (!dead) atomicAdd(&class_count[cls == kClassDeep ? kNumRingClasses : cls], 1);
     }
@@ -419,7 +421,7 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
 // pipelined: each is issued several stages (or, for the first stages, a whole backward
 // sweep) ahead of its use, so the LDS latency does not stall every stage.
 template <int S, bool BEST, bool VT>
-__global__ __launch_bounds__(kBlock, S >= 32 ? (VT ? 3 : ADAPTRA_WAVES32) : 6) void k_resolve_scen_lanes(KArgs) {
+__global__ __launch_bounds__(kBlock, S >= 32 ? (VT ? 3 : ADAPTRA_WAVES32) : (S >= 16 && VT ? 5 : 6)) void k_resolve_scen_lanes(KArgs) {
     // The arguments are read through kargs() where they are needed (see there), never
     // through the by-value parameter.
     extern __shared__ int lds[];
@@ -431,9 +433,14 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? (VT ? 3 : ADAPTRA_WAVES32) : 6) v
     // LDS byte address of this lane's column of the wave's ring, plus ring_bytes (un-bias)
     const unsigned ring = (unsigned)(size_t)(lds_int *)lds + (unsigned)wv * ring_bytes + (unsigned)lane * 4u + ring_bytes;
     unsigned *const hist_lds = (unsigned *)((char *)lds + kWavesPerBlock * ring_bytes);
+    // S is the kernel's stage count; a pipeline with fewer stages is padded at its end
+    // with stages of zero duration behind links of zero delay and with w = 0.  Such a stage
+    // finishes F(m) the moment the stage before it does and starts B(m) at once, so the last
+    // real stage sees exactly its own rule (B after its own F) and no time changes.  The real
+    // count is kargs()->S.
     const bool lds_hist = BEST && kargs()->hist && kargs()->hist_in_lds;
     if (lds_hist) {
-        const int n = S * kargs()->hist_bins;
+        const int n = kargs()->S * kargs()->hist_bins;
         for (int i = threadIdx.x; i < n; i += kBlock) hist_lds[i] = 0;
         __syncthreads();
     }
@@ -454,20 +461,24 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? (VT ? 3 : ADAPTRA_WAVES32) : 6) v
         // when the stage changes phase.
         // With per-scenario stage times (VT: compute stragglers) every lane has its own t_f and
         // t_b; they are then re-read from memory at the phase switches and add_f is per lane.
-        const int tf_lanes = VT ? 0 : kargs()->t_f[lane < S ? lane : 0];
-        const int tb_lanes = VT ? 0 : kargs()->t_b[lane < S ? lane : 0];
-#define ADAPTRA_TF(s) (VT ? kargs()->tfs[(s) * kargs()->Kin + kin] : __builtin_amdgcn_readlane(tf_lanes, (s)))
-#define ADAPTRA_TB(s) (VT ? kargs()->tbs[(s) * kargs()->Kin + kin] : __builtin_amdgcn_readlane(tb_lanes, (s)))
+        const int tf_lanes = VT || lane >= kargs()->S ? 0 : kargs()->t_f[lane];
+        const int tb_lanes = VT || lane >= kargs()->S ? 0 : kargs()->t_b[lane];
+#define ADAPTRA_TF(s) (VT ? ((s) < kargs()->S ? kargs()->tfs[(s) * kargs()->Kin + kin] : 0) : __builtin_amdgcn_readlane(tf_lanes, (s)))
+#define ADAPTRA_TB(s) (VT ? ((s) < kargs()->S ? kargs()->tbs[(s) * kargs()->Kin + kin] : 0) : __builtin_amdgcn_readlane(tb_lanes, (s)))
         const int tau0 = VT ? kargs()->tfs[kin] + kargs()->tbs[kin] : uni(kargs()->t_f[0]) + uni(kargs()->t_b[0]);
         int q[S > 1 ? S - 1 : 1];
         {
             const int *cf = kargs()->cf, *cb = kargs()->cb;
 #pragma unroll
             for (int s = 0; s + 1 < S; ++s) {
-                int tau_next;
-                if constexpr (VT) tau_next = kargs()->tfs[(s + 1) * Kin + kin] + kargs()->tbs[(s + 1) * Kin + kin];
-                else tau_next = uni(kargs()->t_f[s + 1]) + uni(kargs()->t_b[s + 1]);
-                q[s] = cf[s * Kin + kin] + cb[s * Kin + kin] + tau_next + (s == link_up ? kargs()->sens_delta : 0);
+                if (s + 1 < kargs()->S) {
+                    int tau_next;
+                    if constexpr (VT) tau_next = kargs()->tfs[(s + 1) * Kin + kin] + kargs()->tbs[(s + 1) * Kin + kin];
+                    else tau_next = uni(kargs()->t_f[s + 1]) + uni(kargs()->t_b[s + 1]);
+                    q[s] = cf[s * Kin + kin] + cb[s * Kin + kin] + tau_next + (s == link_up ? kargs()->sens_delta : 0);
+                } else {
+                    q[s] = 0;
+                }
             }
         }
 
@@ -611,11 +622,13 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? (VT ? 3 : ADAPTRA_WAVES32) : 6) v
                         unsigned long long *const hist = kargs()->hist;
 #pragma unroll
                         for (int s = 0; s < S; ++s) {
-                            const int tau_s = ADAPTRA_TF(s) + ADAPTRA_TB(s);
-                            int b = (mk - M * tau_s) >> shift;
-                            b = b > bins - 1 ? bins - 1 : b;
-                            if (lds_hist) atomicAdd(&hist_lds[s * bins + b], 1u);
-                            else atomicAdd(&hist[s * bins + b], 1ull);
+                            if (s < kargs()->S) {
+                                const int tau_s = ADAPTRA_TF(s) + ADAPTRA_TB(s);
+                                int b = (mk - M * tau_s) >> shift;
+                                b = b > bins - 1 ? bins - 1 : b;
+                                if (lds_hist) atomicAdd(&hist_lds[s * bins + b], 1u);
+                                else atomicAdd(&hist[s * bins + b], 1ull);
+                            }
                         }
                     }
                 }
@@ -629,7 +642,7 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? (VT ? 3 : ADAPTRA_WAVES32) : 6) v
     }
     if (lds_hist) {
         __syncthreads();
-        const int n = S * kargs()->hist_bins;
+        const int n = kargs()->S * kargs()->hist_bins;
         unsigned long long *const hist = kargs()->hist;
         for (int i = threadIdx.x; i < n; i += kBlock) {
             const unsigned cnt = hist_lds[i];
@@ -775,6 +788,15 @@ hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// The hot kernel exists for 2, 4, 8, 16 and 32 stages; a pipeline with another stage count
+// up to 32 runs in the next larger one, padded with stages that take no time (see the
+// kernel).  0: no hot kernel (more than 32 stages).
+int hot_kernel_stages(int S) {
+    for (int p = 2; p <= 32; p *= 2)
+        if (S <= p) return p;
+    return 0;
+}
+
 struct Workspace {
     size_t off_flag, off_class, off_wq, off_keys, off_status, off_scratch, off_mkt, total;
     int wq_stride;
@@ -794,7 +816,7 @@ long long general_thread_count(int S, int M) {
 bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws, bool with_mkt = true) {
     if (S < 1 || S > ADAPTRA_MAX_STAGES || M < 1 || M > ADAPTRA_MAX_MICROBATCHES) return false;
     if (C < 1 || C > INT32_MAX || K < 1 || K > INT32_MAX) return false;
-    ws->wq_stride = (S + 3) & ~3;
+    ws->wq_stride = (hot_kernel_stages(S) + 3) & ~3;
     ws->general_threads = general_thread_count(S, M);
     size_t o = 0;
     ws->off_flag = o;    o += align256((size_t)C);
@@ -808,13 +830,12 @@ bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws, bool 
     return true;
 }
 
-bool fast_kernel_supports(int S) { return S == 2 || S == 4 || S == 8 || S == 16 || S == 32; }
 
 // The hot kernel puts scenarios on lanes, so its time per candidate does not depend on how
 // many of the 64 lanes carry a scenario, while the general kernel's grows with the number of
 // scenarios; measured on 16 384 candidates (S = 8 and 16) they cross between 4 and 8 scenarios.
 bool use_fast(int S, long long K) {
-    if (g_kernel_mode == 1 || !fast_kernel_supports(S)) return false;
+    if (g_kernel_mode == 1 || hot_kernel_stages(S) == 0) return false;
     if (g_kernel_mode == 2) return true;
     return K >= 6;
 }
@@ -887,7 +908,7 @@ int launch_fast_vt(KArgs a, int w_bound, hipStream_t st) {
         a.cls_hi = cls;
         a.ring_slots = 8 * (cls + 1);
         size_t lds = (size_t)kWavesPerBlock * a.ring_slots * 256;
-        if (BEST && a.hist && a.hist_in_lds) lds += (size_t)S * a.hist_bins * 4;
+        if (BEST && a.hist && a.hist_in_lds) lds += (size_t)a.S * a.hist_bins * 4;
         if (lds > 48 * 1024) {      // above the default dynamic-LDS limit: raise it for this kernel
             hipError_t e = hipFuncSetAttribute((const void *)k_resolve_scen_lanes<S, BEST, VT>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -906,7 +927,7 @@ int launch_fast_one(const KArgs &a, int w_bound, hipStream_t st) {
 
 template <bool BEST>
 int launch_fast(const KArgs &a, int w_bound, hipStream_t st) {
-    switch (a.S) {
+    switch (hot_kernel_stages(a.S)) {
         case 2: return launch_fast_one<2, BEST>(a, w_bound, st);
         case 4: return launch_fast_one<4, BEST>(a, w_bound, st);
         case 8: return launch_fast_one<8, BEST>(a, w_bound, st);

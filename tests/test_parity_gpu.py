@@ -80,7 +80,7 @@ RAGGED = [
     (1, 1, 1, 5, 3, {}),
     (2, 1, 7, 70, 65, dict(hist_bins=8, hist_shift=6)),
     (3, 2, 3, 33, 64, {}),
-    (4, 3, 5, 100, 7, {}),                      # S without a register kernel
+    (4, 3, 5, 100, 7, {}),                      # 3 stages: runs padded in the 4-stage kernel
     (5, 4, 8, 257, 129, dict(hist_bins=16, hist_shift=8)),
     (6, 4, 1, 64, 64, {}),                      # a single micro-batch
     (7, 5, 12, 130, 40, dict(cap=False)),
@@ -101,6 +101,13 @@ RAGGED = [
     (22, 8, 16, 1, 1, dict()),                  # one pair
     (23, 16, 40, 1000, 192, dict(d_max=3, hist_bins=5, hist_shift=11)),   # three full scenario tiles
     (24, 2, 2, 4000, 100, dict(d_max=1)),
+    # stage counts between the hot kernel's sizes (padded with zero-time stages)
+    (25, 6, 20, 300, 33, dict(hist_bins=32, hist_shift=7)),
+    (26, 12, 48, 200, 70, dict(d_max=3, hist_bins=16, hist_shift=9)),
+    (27, 17, 30, 50, 64, dict(d_max=3)),
+    (28, 24, 64, 100, 65, dict(d_max=3, c_hi=20000)),
+    (29, 31, 40, 64, 64, dict(d_max=3, hist_bins=200, hist_shift=8)),
+    (30, 33, 40, 20, 10, dict(d_max=2)),        # beyond the hot kernel: general kernel
 ]
 
 
@@ -431,6 +438,8 @@ STAGE_TIME_CASES = [
     (67, 32, 64, 80, 70, dict(d_max=4, hist_bins=16, hist_shift=12)),
     (68, 64, 80, 30, 5, dict(d_max=2)),
     (69, 8, 24, 50, 3, {}),                                    # few scenarios
+    (59, 12, 30, 60, 40, dict(d_max=3, hist_bins=8, hist_shift=10)),   # padded to 16 stages
+    (58, 24, 50, 30, 64, dict(d_max=3)),                       # padded to 32 stages
 ]
 
 
@@ -572,7 +581,7 @@ SEARCH_CASES = [
     # seed, S, M, K, neighbourhood, max_iters, stage times per scenario, kwargs
     (100, 1, 6, 9, 0, 50, False, {}),
     (101, 2, 60, 7, 0, 50, False, dict(c_hi=60, cap=False)),
-    (102, 3, 12, 5, 1, 50, False, {}),                     # general kernel (S = 3, K < 6)
+    (102, 3, 12, 5, 1, 50, False, {}),                     # general kernel (K < 6)
     (103, 4, 16, 70, 0, 50, False, {}),
     (104, 4, 16, 33, 1, 50, True, {}),
     (105, 8, 32, 64, 0, 50, False, dict(c_hi=3000)),
