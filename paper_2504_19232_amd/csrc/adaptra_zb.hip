@@ -13,15 +13,23 @@
 // by the ready times already posted to it (an op's ready time is posted when its producer
 // STARTS, since the finish time is then known), so the lane repeatedly takes the stage whose
 // next action is earliest (ties to the lower stage), starts that op, posts the ready times it
-// creates and refreshes the next-action times of the three stages involved.  Ready times
-// posted later are strictly later than the current time because forward and backward ops last
-// at least 1 us (a precondition of this entry point), so the decision at the earliest action
+// creates and refreshes the next-action times of the stages involved.  Ready times posted
+// later are strictly later than the current time because forward and backward ops last at
+// least 1 us (a precondition of this entry point), so the decision at the earliest action
 // time can never be overturned.  Within a type ops run in micro-batch order and their ready
-// times are non-decreasing, so "the lowest available micro-batch" is a per-type cursor.
+// times are non-decreasing, so "the lowest available micro-batch" is a per-type cursor, and
+// the ready times of one (stage, type) form a queue: posted in micro-batch order, consumed in
+// micro-batch order.
 //
-// State per lane lives in global scratch laid out [index][thread] (coalesced across lanes):
-//   ready[S][3][N], busy[S], quota[S], cursor[S][3], act_time[S], act_type[S]
-// and, for plan replay, the generated order [C][S][3N] of the plan scenario.
+// Where the state lives.  The queues (up to N entries each) are in global scratch, laid out
+// [index][thread] so that a wavefront's access is one 256-byte line.  Everything a decision
+// needs is on chip, in LDS laid out [array][stage][lane] (conflict-free for any per-lane
+// stage index): per stage the busy-until time, the cached next-action time, the three
+// cursors, the warm-up quota x, and the HEAD of each of the three queues (the ready time of
+// the cursor's micro-batch, or "not posted yet").  A post that lands on the head goes straight
+// to LDS and never to memory; a step touches global memory only to append behind a head and
+// to fetch the next head after a consume -- about three accesses instead of the forty of a
+// version that kept all state in memory.  One wavefront per block, 9 S KiB / 4 of LDS each.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -30,8 +38,9 @@
 
 namespace {
 
-using adaptra_detail::kThreadsPerBlock;
 constexpr int kInf = INT32_MAX;
+constexpr int kZbBlock = 64;          // one wavefront per block: LDS, not threads, bounds the occupancy
+constexpr int kZbArrays = 9;          // busy, act, nF, nB, nW, headF, headB, headW, x
 
 struct ZbArgs {
     int S, N;
@@ -41,62 +50,78 @@ struct ZbArgs {
     long long plan_scenario;      // -1: every pair generates under its own scenario
     int phase;                    // 0: generate (+ outputs unless a plan is wanted), 1: record plans, 2: replay plans
     int *out_makespan, *out_bubble;
-    int *scratch;                 // [per_thread][threads]
+    int *scratch;                 // queues [S][3][N][threads]
     int *plans;                   // [C][S][3N], ops as type * N + m
     long long threads;
-};
-
-struct Lane {
-    int *base;
-    long long nt;
-    int S, N;
-    __device__ int &ready(int i, int ty, int m) const { return base[(((long long)i * 3 + ty) * N + m) * nt]; }
-    __device__ int &busy(int i) const { return base[((long long)3 * S * N + i) * nt]; }
-    __device__ int &quota(int i) const { return base[((long long)3 * S * N + S + i) * nt]; }
-    __device__ int &cursor(int i, int ty) const { return base[((long long)3 * S * N + 2 * S + i * 3 + ty) * nt]; }
-    __device__ int &act_time(int i) const { return base[((long long)3 * S * N + 5 * S + i) * nt]; }
-    __device__ int &act_type(int i) const { return base[((long long)3 * S * N + 6 * S + i) * nt]; }
 };
 
 __device__ __forceinline__ int imin(int a, int b) { return a < b ? a : b; }
 __device__ __forceinline__ int imax2(int a, int b) { return a > b ? a : b; }
 
-// Next action of stage i from what has been posted so far: the time it can act and the op type
-// it will then run (Algorithm 3), or kInf if nothing it may run has been posted yet.
-// With a plan, the next op is the plan's, whatever its type.
-__device__ void refresh_action(const Lane &L, int i, const int *plan, int done_i) {
-    const int N = L.N;
-    if (plan) {
-        if (done_i >= 3 * N) { L.act_time(i) = kInf; return; }
-        const int op = plan[done_i];
-        const int ty = op / N, m = op % N;
-        const int r = L.ready(i, ty, m);
-        L.act_type(i) = ty;
-        L.act_time(i) = r == kInf ? kInf : imax2(L.busy(i), r);
-        return;
-    }
-    const int cf = L.cursor(i, 0), cb = L.cursor(i, 1), cw = L.cursor(i, 2);
-    const int rf = cf < N ? L.ready(i, 0, cf) : kInf;
-    const int rb = cb < N ? L.ready(i, 1, cb) : kInf;
-    const int rw = cw < N ? L.ready(i, 2, cw) : kInf;
-    const int busy = L.busy(i);
-    if (L.quota(i) > 0) {                                   // warm-up: forwards only
-        L.act_type(i) = 0;
-        L.act_time(i) = rf == kInf ? kInf : imax2(busy, rf);
-        return;
-    }
-    const int first = imin(rb, imin(rf, rw));
-    if (first == kInf) { L.act_time(i) = kInf; return; }
-    const int t = imax2(busy, first);
-    L.act_time(i) = t;
-    L.act_type(i) = rb <= t ? 1 : (rf <= t ? 0 : 2);         // priority B > F > W among those ready at t
-}
+// The lane's view of its state.
+struct Lane {
+    int *lds;                     // this lane's column: element (array, stage) at lds[(array * S + stage) * 64]
+    const int *dur_table;         // LDS copy of t_f, t_b, t_w: [3][S]
+    int *queue;                   // this thread's column of the global queues
+    long long nt;
+    int S, N;
+    __device__ int &busy(int i) const { return lds[(0 * S + i) * 64]; }
+    __device__ int &act(int i) const { return lds[(1 * S + i) * 64]; }
+    __device__ int &count(int i, int ty) const { return lds[((2 + ty) * S + i) * 64]; }
+    __device__ int &head(int i, int ty) const { return lds[((5 + ty) * S + i) * 64]; }
+    __device__ int &quota(int i) const { return lds[(8 * S + i) * 64]; }
+    __device__ int &ready(int i, int ty, int m) const { return queue[(((long long)i * 3 + ty) * N + m) * nt]; }
+    __device__ int cursor(int i, int ty) const { return count(i, ty); }
+    __device__ void advance(int i, int ty) const { count(i, ty) += 1; }
+    __device__ int x(int i) const { return quota(i); }
+    __device__ int done(int i) const { return count(i, 0) + count(i, 1) + count(i, 2); }
 
-__global__ __launch_bounds__(kThreadsPerBlock) void k_zb(ZbArgs a) {
-    const long long tid = (long long)blockIdx.x * kThreadsPerBlock + threadIdx.x;
+    // Ready times of (i, ty) posted so far: a forward of stage i is posted when the forward of
+    // stage i-1 starts (stage 0: all at time 0), a backward when the backward of stage i+1
+    // starts (last stage: when its own forward starts), a weight op when the stage's own
+    // backward starts.
+    __device__ int posted(int i, int ty) const {
+        if (ty == 0) return i == 0 ? N : cursor(i - 1, 0);
+        if (ty == 1) return i == S - 1 ? cursor(i, 0) : cursor(i + 1, 1);
+        return cursor(i, 1);
+    }
+    // Appends the ready time r of micro-batch m to the queue of (i, ty).
+    __device__ void post(int i, int ty, int m, int r) const {
+        if (m == cursor(i, ty)) head(i, ty) = r;
+        else ready(i, ty, m) = r;
+    }
+    // Next action of stage i from what has been posted so far (Algorithm 3): the time it can
+    // act, or kInf if nothing it may run has been posted yet.  With a plan the next op is the
+    // plan's, whatever its type.
+    __device__ void refresh(int i, const int *plan) const {
+        const int b = busy(i);
+        if (plan) {
+            const int d = done(i);
+            if (d >= 3 * N) { act(i) = kInf; return; }
+            const int r = head(i, plan[d] / N);
+            act(i) = r == kInf ? kInf : imax2(b, r);
+            return;
+        }
+        const int rf = head(i, 0);
+        if (cursor(i, 0) < x(i)) {                              // warm-up: forwards only
+            act(i) = rf == kInf ? kInf : imax2(b, rf);
+            return;
+        }
+        const int first = imin(head(i, 1), imin(rf, head(i, 2)));
+        act(i) = first == kInf ? kInf : imax2(b, first);
+    }
+};
+
+__global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
+    extern __shared__ int zb_lds[];
+    const long long tid = (long long)blockIdx.x * kZbBlock + threadIdx.x;
     const int S = a.S, N = a.N;
     const long long n_items = a.phase == 1 ? a.C : a.C * a.K;
-    Lane L{a.scratch + tid, a.threads, S, N};
+    int *const dur_table = zb_lds + kZbArrays * S * 64;
+    for (int i = threadIdx.x; i < 3 * S; i += kZbBlock)
+        dur_table[i] = i < S ? a.t_f[i] : (i < 2 * S ? a.t_b[i - S] : a.t_w[i - 2 * S]);
+    __syncthreads();
+    const Lane L{zb_lds + threadIdx.x, dur_table, a.scratch + tid, a.threads, S, N};
     for (long long item = tid; item < n_items; item += a.threads) {
         const long long c = a.phase == 1 ? item : item % a.C;
         const long long k = a.phase == 1 ? a.plan_scenario : item / a.C;
@@ -104,52 +129,51 @@ __global__ __launch_bounds__(kThreadsPerBlock) void k_zb(ZbArgs a) {
         int *record = a.phase == 1 ? a.plans + c * (long long)S * 3 * N : nullptr;
         // set-up: nothing posted except the forwards of stage 0 (available at time 0)
         for (int i = 0; i < S; ++i) {
-            for (int m = 0; m < N; ++m) {
-                L.ready(i, 0, m) = i == 0 ? 0 : kInf;
-                L.ready(i, 1, m) = kInf;
-                L.ready(i, 2, m) = kInf;
-            }
             int wi = a.w[(long long)i * a.C + c];
             wi = wi < 0 ? 0 : (wi > N - 1 ? N - 1 : wi);
             L.busy(i) = 0;
-            L.quota(i) = wi + 1;                              // x_i = w_i + 1 warm-up forwards
-            L.cursor(i, 0) = 0; L.cursor(i, 1) = 0; L.cursor(i, 2) = 0;
+            L.count(i, 0) = 0; L.count(i, 1) = 0; L.count(i, 2) = 0;
+            L.quota(i) = wi + 1;                                // x_i = w_i + 1 warm-up forwards
+            L.head(i, 0) = i == 0 ? 0 : kInf;
+            L.head(i, 1) = kInf;
+            L.head(i, 2) = kInf;
         }
-        for (int i = 0; i < S; ++i) refresh_action(L, i, plan_base ? plan_base + (long long)i * 3 * N : nullptr, 0);
+        for (int i = 0; i < S; ++i) L.refresh(i, plan_base ? plan_base + (long long)i * 3 * N : nullptr);
 
         const int total = 3 * S * N;
         int makespan = 0;
         for (int step = 0; step < total; ++step) {
-            int best = 0, best_t = L.act_time(0);
-            for (int i = 1; i < S; ++i) {
-                const int t = L.act_time(i);
-                if (t < best_t) { best_t = t; best = i; }
+            int i = 0, t = L.act(0);
+            for (int j = 1; j < S; ++j) {
+                const int tj = L.act(j);
+                if (tj < t) { t = tj; i = j; }
             }
-            if (best_t == kInf) { makespan = kInf; break; }   // cannot happen for valid input
-            const int i = best, ty = L.act_type(i);
-            const int done_i = L.cursor(i, 0) + L.cursor(i, 1) + L.cursor(i, 2);
-            int m;
-            if (plan_base) m = plan_base[(long long)i * 3 * N + done_i] % N;
-            else m = L.cursor(i, ty);
-            const int dur = ty == 0 ? a.t_f[i] : (ty == 1 ? a.t_b[i] : a.t_w[i]);
-            const int fin = best_t + dur;
+            if (t == kInf) { makespan = kInf; break; }          // cannot happen for valid input
+            const int *plan_i = plan_base ? plan_base + (long long)i * 3 * N : nullptr;
+            const int done_i = L.done(i);
+            int ty;
+            if (plan_i) ty = plan_i[done_i] / N;
+            else if (L.cursor(i, 0) < L.x(i)) ty = 0;
+            else ty = L.head(i, 1) <= t ? 1 : (L.head(i, 0) <= t ? 0 : 2);   // priority B > F > W among those ready at t
+            const int m = L.cursor(i, ty);
+            const int dur = L.dur_table[ty * S + i];
+            const int fin = t + dur;
             L.busy(i) = fin;
             makespan = imax2(makespan, fin);
-            L.cursor(i, ty) += 1;
-            if (ty == 0 && L.quota(i) > 0) L.quota(i) -= 1;
             if (record) record[(long long)i * 3 * N + done_i] = ty * N + m;
-            int touched_lo = i, touched_hi = i;
+            // consume: the queue's next entry becomes the head (stage 0's forwards are all ready at 0)
+            L.advance(i, ty);
+            if (m + 1 < L.posted(i, ty)) L.head(i, ty) = (ty == 0 && i == 0) ? 0 : L.ready(i, ty, m + 1);
+            else L.head(i, ty) = kInf;
+            int lo = i, hi = i;
             if (ty == 0) {
-                if (i < S - 1) { L.ready(i + 1, 0, m) = fin + a.cf[(long long)i * a.K + k]; touched_hi = i + 1; }
-                else L.ready(i, 1, m) = fin;
+                if (i < S - 1) { L.post(i + 1, 0, m, fin + a.cf[(long long)i * a.K + k]); hi = i + 1; }
+                else L.post(i, 1, m, fin);
             } else if (ty == 1) {
-                L.ready(i, 2, m) = fin;
-                if (i > 0) { L.ready(i - 1, 1, m) = fin + a.cb[(long long)(i - 1) * a.K + k]; touched_lo = i - 1; }
+                L.post(i, 2, m, fin);
+                if (i > 0) { L.post(i - 1, 1, m, fin + a.cb[(long long)(i - 1) * a.K + k]); lo = i - 1; }
             }
-            for (int j = touched_lo; j <= touched_hi; ++j) {
-                const int dj = j == i ? done_i + 1 : L.cursor(j, 0) + L.cursor(j, 1) + L.cursor(j, 2);
-                refresh_action(L, j, plan_base ? plan_base + (long long)j * 3 * N : nullptr, dj);
-            }
+            for (int j = lo; j <= hi; ++j) L.refresh(j, plan_base ? plan_base + (long long)j * 3 * N : nullptr);
         }
         if (a.phase != 1) {
             const long long P = a.C * a.K;
@@ -157,7 +181,7 @@ __global__ __launch_bounds__(kThreadsPerBlock) void k_zb(ZbArgs a) {
             if (a.out_bubble)
                 for (int i = 0; i < S; ++i)
                     a.out_bubble[(long long)i * P + item] =
-                        makespan == kInf ? kInf : makespan - N * (a.t_f[i] + a.t_b[i] + a.t_w[i]);
+                        makespan == kInf ? kInf : makespan - N * (dur_table[i] + dur_table[S + i] + dur_table[2 * S + i]);
         }
     }
 }
@@ -172,11 +196,17 @@ struct ZbPlan {
 bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
     if (S < 1 || S > ADAPTRA_MAX_STAGES || N < 1 || N > ADAPTRA_MAX_MICROBATCHES) return false;
     if (C < 1 || C > INT32_MAX || K < 1 || K > INT32_MAX) return false;
-    const long long per_thread = (3ll * S * N + 7ll * S) * 4;
-    long long nt = (512ll << 20) / per_thread;               // about 512 MiB of lane state at most
-    if (nt > 65536) nt = 65536;
-    if (nt < 1024) nt = 1024;
-    nt = nt / kThreadsPerBlock * kThreadsPerBlock;
+    // Enough threads to fill the chip at the occupancy the LDS state allows (at most 160 KiB
+    // per CU, 32 wavefronts per CU, 256 CUs), within about 2 GiB of queue memory.
+    const long long per_thread = 3ll * S * N * 4;
+    const long long lds_per_wave = (long long)kZbArrays * S * 64 * 4 + 3ll * S * 4;
+    long long waves_per_cu = (160ll << 10) / lds_per_wave;
+    if (waves_per_cu > 32) waves_per_cu = 32;
+    if (waves_per_cu < 1) return false;
+    long long nt = 256 * waves_per_cu * kZbBlock;
+    const long long cap = (2048ll << 20) / per_thread / kZbBlock * kZbBlock;
+    if (nt > cap) nt = cap;
+    if (nt < 16 * kZbBlock) nt = 16 * kZbBlock;
     p->threads = nt;
     size_t o = 0;
     p->off_scratch = o; o += align256((size_t)nt * per_thread);
@@ -218,26 +248,28 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
     a.plans = (int *)((char *)workspace + p.off_plans);
     a.threads = p.threads;
     const long long P = a.C * a.K;
-    if (plan_scenario < 0) {
-        a.phase = 0;
-        const long long n = P < a.threads ? P : a.threads;
-        a.threads = (n + kThreadsPerBlock - 1) / kThreadsPerBlock * kThreadsPerBlock;
-        hipLaunchKernelGGL(k_zb, dim3((unsigned)(a.threads / kThreadsPerBlock)), dim3(kThreadsPerBlock), 0, st, a);
+    const size_t lds = (size_t)kZbArrays * a.S * 64 * 4 + (size_t)3 * a.S * 4;
+    if (lds > 48 * 1024) {                                   // above the default dynamic-LDS limit
+        hipError_t e = hipFuncSetAttribute((const void *)k_zb, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return adaptra_detail::hip_fail(e);
+    }
+    const long long full = p.threads;
+    auto launch = [&](long long items) -> int {              // threads: a multiple of the block, at most `full`
+        const long long n = items < full ? items : full;
+        a.threads = (n + kZbBlock - 1) / kZbBlock * kZbBlock;
+        hipLaunchKernelGGL(k_zb, dim3((unsigned)(a.threads / kZbBlock)), dim3(kZbBlock), lds, st, a);
         ADAPTRA_CHECK_LAUNCH();
         return ADAPTRA_OK;
+    };
+    if (plan_scenario < 0) {
+        a.phase = 0;
+        return launch(P);
     }
-    const long long full = a.threads;
     a.phase = 1;                                             // one plan per candidate, under the plan scenario
-    long long n = a.C < full ? a.C : full;
-    a.threads = (n + kThreadsPerBlock - 1) / kThreadsPerBlock * kThreadsPerBlock;
-    hipLaunchKernelGGL(k_zb, dim3((unsigned)(a.threads / kThreadsPerBlock)), dim3(kThreadsPerBlock), 0, st, a);
-    ADAPTRA_CHECK_LAUNCH();
+    int rc = launch(a.C);
+    if (rc) return rc;
     a.phase = 2;                                             // every pair replays its candidate's plan
-    n = P < full ? P : full;
-    a.threads = (n + kThreadsPerBlock - 1) / kThreadsPerBlock * kThreadsPerBlock;
-    hipLaunchKernelGGL(k_zb, dim3((unsigned)(a.threads / kThreadsPerBlock)), dim3(kThreadsPerBlock), 0, st, a);
-    ADAPTRA_CHECK_LAUNCH();
-    return ADAPTRA_OK;
+    return launch(P);
 }
 
 }  // extern "C"

@@ -392,7 +392,9 @@ def test_zb_paper_example_on_gpu(lib):
 
 
 ZB_CASES = [(1, 1, 1, 3, 2), (2, 2, 3, 9, 5), (3, 4, 8, 40, 21), (4, 8, 16, 70, 33), (5, 5, 7, 300, 4),
-            (6, 16, 12, 20, 10), (7, 3, 40, 10, 64)]
+            (6, 16, 12, 20, 10), (7, 3, 40, 10, 64),
+            (8, 32, 10, 6, 70),           # per-wavefront state above the default LDS limit
+            (9, 64, 6, 150, 130)]         # the largest S; more pairs than resident threads
 
 
 @pytest.mark.parametrize("seed_,S,N,C,K", ZB_CASES, ids=[f"S{c[1]}_N{c[2]}_C{c[3]}_K{c[4]}" for c in ZB_CASES])
@@ -407,11 +409,14 @@ def test_zb_parity(lib, oracle, seed_, S, N, C, K):
     cb = rng.integers(0, 400, (max(S - 1, 0), K))
     prob, t_w_d = _zb_problem(b, S, N, t_f, t_b, t_w, w, cf, cb)
     x = np.clip(w, 0, N - 1) + 1
-    ref = oracle.zb_batch(S, N, t_f, t_b, t_w, x, cf, cb)
+    # the oracle sweeps every pair, or -- where that takes too long -- whole scenarios from
+    # both ends of the pair range
+    ks = np.arange(K) if S * N * C * K < 4_000_000 else np.unique(np.r_[0, K // 2, np.arange(K - 20, K, 3)])
+    ref = oracle.zb_batch(S, N, t_f, t_b, t_w, x, cf[:, ks], cb[:, ks])
     mk, bub = b.adaptra_zb_eval(prob, t_w_d, -1)
     torch.cuda.synchronize()
-    assert np.array_equal(mk.cpu().numpy(), ref["makespan"])
-    assert np.array_equal(bub.cpu().numpy(), ref["idle"])
+    assert np.array_equal(mk.cpu().numpy()[ks], ref["makespan"])
+    assert np.array_equal(bub.cpu().numpy()[:, ks], ref["idle"])
     # fixed plans generated under scenario 1 (or 0), replayed under every scenario
     kp = 1 if K > 1 else 0
     mkp, _ = b.adaptra_zb_eval(prob, t_w_d, kp, want_bubble=False)
