@@ -42,8 +42,12 @@
  *     The library allocates no device memory and keeps no state between calls
  *     except the option set by adaptra_set_kernel_mode.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     adaptra_eval and adaptra_best only enqueue work on it and return; they do
- *     not synchronise.  Outputs are valid once the stream has drained.
+ *     adaptra_eval, adaptra_best, adaptra_seed, adaptra_sensitivity and
+ *     adaptra_zb_eval only enqueue kernels on it and return; they do not
+ *     synchronise, allocate or record memset nodes, so a caller may capture them
+ *     into a HIP graph (after one eager call, which sets the kernels' shared-memory
+ *     limits).  Outputs are valid once the stream has drained.
+ *     adaptra_check_inputs and adaptra_search wait for the stream.
  *   - Return value: ADAPTRA_OK or one of the error codes below.  Per-pair
  *     conditions (deadlock, memory cap) are data, not errors.
  */

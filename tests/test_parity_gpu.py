@@ -659,3 +659,58 @@ def test_guided_search_against_exhaustive_argmin(lib, oracle, index):
     assert np.all(ref["flag"] == 1)
     assert np.array_equal(ref["makespan"].astype(np.int64), mk)
     assert np.max(mk / bmk) < 1.05
+
+
+# ----------------------------------------------------------------------------------------
+def test_eval_and_best_replay_from_a_hip_graph(lib, oracle):
+    """The entry points only enqueue kernels (no allocation, no memset node, no host wait), so a
+    caller may capture them into a HIP graph.  The graph is replayed several times, with eager
+    work and synchronisations of the same library between the replays and with the inputs
+    changed in place, and every replay is checked against the oracle."""
+    import torch
+    wl = workloads.random_workload(120, 8, 24, 300, 70, hist_bins=16, hist_shift=9)
+    prob = lib.Problem.from_workload(wl, w_bound=int(np.clip(wl.w, 0, wl.M - 1).max()))
+    ws = lib.alloc_workspace(prob)
+    dev = prob.device
+    mk = torch.empty((prob.K, prob.C), dtype=torch.int32, device=dev)
+    bub = torch.empty((prob.S, prob.K, prob.C), dtype=torch.int32, device=dev)
+    fl = torch.empty((prob.K, prob.C), dtype=torch.uint8, device=dev)
+    bidx = torch.empty(prob.K, dtype=torch.int32, device=dev)
+    bmk = torch.empty(prob.K, dtype=torch.int32, device=dev)
+    bbub = torch.empty((prob.K, prob.S), dtype=torch.int32, device=dev)
+    hist = torch.empty((prob.S, prob.hist_bins), dtype=torch.int64, device=dev)
+
+    def enqueue():
+        lib.adaptra_eval(prob, mk, bub, fl, workspace=ws)
+        lib.adaptra_best(prob, bidx, bmk, bbub, hist, workspace=ws)
+
+    enqueue()                                   # eager warm-up (sets the kernels' LDS attributes)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            enqueue()
+    torch.cuda.synchronize()
+    c_fwd_dev = prob.tensors[3]
+    for replay in range(4):
+        say(f"  replay {replay}")
+        if replay:                              # new delays, written in place, and eager work in between
+            wl.c_fwd[:] = (wl.c_fwd.astype(np.int64) * (replay + 1) % 4001).astype(np.int32)
+            c_fwd_dev.copy_(torch.from_numpy(wl.c_fwd))
+            other = workloads.random_workload(121 + replay, 4, 8, 50, 64)
+            gpu_eval(lib, other)
+        for t in (mk, bub, bmk, bidx):
+            t.fill_(-7)
+        graph.replay()
+        torch.cuda.synchronize()
+        ref = oracle.eval_workload(wl)
+        rbest = oracle.best_from_eval(ref["makespan"], ref["flag"], ref["bubble"])
+        assert np.array_equal(mk.cpu().numpy(), ref["makespan"])
+        assert np.array_equal(bub.cpu().numpy(), ref["bubble"])
+        assert np.array_equal(fl.cpu().numpy(), ref["flag"])
+        assert np.array_equal(bidx.cpu().numpy(), rbest["best_idx"])
+        assert np.array_equal(bmk.cpu().numpy(), rbest["best_makespan"])
+        assert np.array_equal(bbub.cpu().numpy(), rbest["best_bubble"])
+        assert np.array_equal(hist.cpu().numpy().astype(np.uint64),
+                              oracle.hist_from_eval(ref["bubble"], ref["flag"], wl.hist_bins, wl.hist_shift))
