@@ -714,3 +714,38 @@ def test_eval_and_best_replay_from_a_hip_graph(lib, oracle):
         assert np.array_equal(bbub.cpu().numpy(), rbest["best_bubble"])
         assert np.array_equal(hist.cpu().numpy().astype(np.uint64),
                               oracle.hist_from_eval(ref["bubble"], ref["flag"], wl.hist_bins, wl.hist_shift))
+
+
+def test_many_small_random_problems(lib, oracle):
+    """A sweep of small random shapes (every stage count from 1 to 20, M from 1, ragged C and
+    K, with and without caps, histograms and per-scenario stage times) in every kernel mode."""
+    rng = np.random.default_rng(2025)
+    for trial in range(120):
+        S = int(rng.integers(1, 21))
+        M = int(rng.integers(1, 14))
+        C = int(rng.integers(1, 140))
+        K = int(rng.integers(1, 80))
+        kw = dict(d_max=int(rng.integers(0, 4)), cap=bool(rng.integers(0, 2)))
+        if rng.integers(0, 2):
+            kw.update(hist_bins=int(rng.integers(1, 40)), hist_shift=int(rng.integers(0, 12)))
+        wl = workloads.random_workload(5000 + trial, S, M, C, K, **kw)
+        vt = bool(rng.integers(0, 3) == 0)
+        tfs, tbs = workloads.straggler_stage_times(6000 + trial, wl, p_slow=0.3) if vt else (None, None)
+        if vt:
+            ref = oracle.eval_scenario_times(S, M, tfs, tbs, wl.mem_cap, wl.w, wl.c_fwd, wl.c_bwd)
+        else:
+            ref = oracle.eval_workload(wl)
+        rbest = oracle.best_from_eval(ref["makespan"], ref["flag"], ref["bubble"])
+        rhist = oracle.hist_from_eval(ref["bubble"], ref["flag"], wl.hist_bins, wl.hist_shift) if wl.hist_bins else None
+        for mode in (0, 1, 2):
+            tag = f"trial {trial} {wl.name} stage-times {vt} mode {mode}"
+            mk, bub, fl = _with_stage_times(lib, wl, tfs, tbs, mode, lambda p: lib.adaptra_eval(p))
+            assert np.array_equal(fl, ref["flag"]), tag
+            assert np.array_equal(mk, ref["makespan"]), tag
+            assert np.array_equal(bub, ref["bubble"]), tag
+            idx, bmk, bbub, hist = _with_stage_times(lib, wl, tfs, tbs, mode, lambda p: lib.adaptra_best(p))
+            assert np.array_equal(idx, rbest["best_idx"]), tag
+            assert np.array_equal(bmk, rbest["best_makespan"]), tag
+            assert np.array_equal(bbub, rbest["best_bubble"]), tag
+            if rhist is not None:
+                assert np.array_equal(hist.astype(np.uint64), rhist), tag
