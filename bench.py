@@ -259,16 +259,16 @@ def main():
     search_info = None
     if not args.no_sens and S > 1:
         w_init = torch.arange(S - 1, -1, -1, dtype=torch.int32, device=dev)   # plain 1F1B: fits every cap here
-        sws = torch.empty(binding.load().adaptra_search_workspace_bytes(ctypes.byref(prob.params), K, 0),
+        sws = torch.empty(binding.load().adaptra_search_workspace_bytes(ctypes.byref(prob.params), K, 1),
                           dtype=torch.uint8, device=dev)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        sw, smk, rounds, evaluated = binding.adaptra_search(prob, w_init, 0, 500, workspace=sws)
+        sw, smk, rounds, evaluated = binding.adaptra_search(prob, w_init, 1, 500, workspace=sws)
         torch.cuda.synchronize()
         t_search = time.perf_counter() - t0
         found = (bmk != 2 ** 31 - 1) & (smk != 2 ** 31 - 1)
         ratio = (smk[found].double() / bmk[found].double())
-        search_info = {"neighbourhood": 0, "start": "plain 1F1B, w_s = S - 1 - s", "rounds": rounds,
+        search_info = {"neighbourhood": 1, "start": "plain 1F1B, w_s = S - 1 - s", "rounds": rounds,
                        "pairs_evaluated": evaluated, "ms": t_search * 1e3,
                        "evaluations_per_s": evaluated / t_search,
                        "makespan_vs_exhaustive_over_candidates_mean": float(ratio.mean()) if ratio.numel() else None,

@@ -198,23 +198,23 @@ int adaptra_sensitivity(const adaptra_params_t *params, const adaptra_candidates
 /* Guided search for schedule spaces that cannot be enumerated (4-7 choices per stage make
  * 5^31 vectors at S = 32): a neighbourhood descent over the slacks Delta_i = w_i - w_{i+1}
  * -- the coordinates Section 4.2's algorithms plan with -- in which every round is one batched
- * evaluation (adaptra_best) of a pool of candidates under all scenarios.  Every scenario keeps a
- * current point, all starting from w_start (clamped into [0, M-1]; e.g. Algorithm 1's plan from
- * adaptra_seed), with makespan INT32_MAX until the first round has priced it.  One round:
- *   1. the distinct current points, ordered by the lowest scenario holding each;
- *   2. the pool: per distinct point, itself, then its neighbours in move order, clamped;
- *   3. adaptra_best over pool x scenarios (feasible entries only, ties to the lowest index);
- *   4. a scenario moves to its best pool entry iff that is strictly better than what it has.
- * It ends after the first round without a move, or after max_iters rounds.
+ * evaluation of all scenarios' neighbourhoods.  Every scenario descends on its own from
+ * w_start (clamped into [0, M-1]; e.g. Algorithm 1's plan from adaptra_seed), with makespan
+ * INT32_MAX until the first round has priced it.  One round, for every scenario k:
+ *   1. its pool: its current point, then the point's neighbours in move order, clamped;
+ *   2. every pool entry is evaluated under scenario k; the best is the feasible entry of
+ *      smallest makespan, ties to the lowest pool index;
+ *   3. the scenario moves to its best entry iff that is strictly better than what it has.
+ * It ends after the first round without a move anywhere, or after max_iters rounds.
  *   neighbourhood 0: for l = 0..S-1: -1, then +1, on stages 0..l      (2 S moves)
  *   neighbourhood 1: for a = 0..S-1, b = a..S-1: -1, then +1, on stages a..b   (S (S+1) moves)
  *   out_w          DEVICE int32 [S][n_scen]: the point each scenario ended on
  *   out_makespan   DEVICE int32 [n_scen]: its makespan; INT32_MAX if no feasible point was seen
  *   out_rounds     HOST int32: rounds run (may be NULL)
- *   out_evaluated  HOST int64: pairs evaluated in total (may be NULL)
+ *   out_evaluated  HOST int64: pairs evaluated in total, rounds * n_scen * (moves + 1) (may be NULL)
  * params->mem_cap and per-scenario stage times are honoured; the histogram fields are ignored.
- * n_scen <= 32768 and n_scen * (moves + 1) <= 2^31 - 1.  SYNCHRONOUS: each round waits for the
- * stream (the host needs the pool size and whether anything moved). */
+ * n_scen * (moves + 1) <= 2^31 - 1.  SYNCHRONOUS: each round waits for the stream (the host
+ * needs to know whether anything moved). */
 size_t adaptra_search_workspace_bytes(const adaptra_params_t *params, int64_t n_scen, int32_t neighbourhood);
 int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *scens,
                    const int32_t *w_start, int32_t neighbourhood, int32_t max_iters,

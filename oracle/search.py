@@ -6,15 +6,16 @@ evaluation of the paper's analytical model (Section 3.1; the coordinates are the
 Delta_i = w_i - w_{i+1} that Section 4.2's algorithms plan with).  This file states the
 procedure step by step on top of the oracle's simulator; it shares nothing with the GPU path.
 
-Procedure.  Every scenario k keeps a current point w^k (all start from the same vector) and
-its makespan (INT32_MAX before the first round).  One round:
-  1. the distinct current points, in order of the lowest scenario that holds each;
-  2. the pool: for each distinct point, itself and then its neighbours in move order, every
-     entry clamped into [0, M-1];
-  3. every pool entry is evaluated under every scenario; a scenario's best is the feasible
+Procedure.  Every scenario k descends on its own: it keeps a current point w^k (all start
+from the same vector) and its makespan (INT32_MAX before the first round).  One round:
+  1. scenario k's pool: its point, then the point's neighbours in move order, every entry
+     clamped into [0, M-1];
+  2. every pool entry is evaluated under scenario k; the scenario's best is the feasible
      entry of smallest makespan, ties to the lowest pool index;
-  4. a scenario moves to its best entry iff that is strictly better than what it has.
-The search stops after the first round in which no scenario moved, or after max_iters rounds.
+  3. the scenario moves to its best entry iff that is strictly better than what it has.
+The search stops after the first round in which no scenario moved, or after max_iters rounds
+(a scenario that has stopped moving keeps being evaluated until all have: its result does
+not change).
 
 Moves.  neighbourhood 0: for l = 0..S-1, subtract then add 1 on stages 0..l (slack Delta_l
 one down / up, everything upstream shifted along).  neighbourhood 1: for a = 0..S-1, for
@@ -54,34 +55,42 @@ def search(S: int, M: int, t_f, t_b, mem_cap, w_start, c_fwd, c_bwd, *, neighbou
     cur_mk = np.full(K, INT32_MAX, dtype=np.int64)
     rounds = 0
     evaluated = 0
+    per_point = len(mv) + 1
     while rounds < max_iters:
         rounds += 1
-        distinct = []                                   # step 1
-        seen = set()
+        pool = []                                       # step 1
         for k in range(K):
-            key = tuple(cur[:, k])
-            if key not in seen:
-                seen.add(key)
-                distinct.append(np.array(key, dtype=np.int64))
-        pool = []                                       # step 2
-        for p in distinct:
+            p = cur[:, k]
             pool.append(p.copy())
             for a, b, sign in mv:
                 q = p.copy()
                 q[a:b + 1] += sign
                 pool.append(np.clip(q, 0, M - 1))
         pool = np.stack(pool, axis=1)
-        if t_f_scen is None:                            # step 3
-            r = oracle.eval_pairs(S, M, t_f, t_b, mem_cap, pool, c_fwd, c_bwd, want_bubble=False)
+        n = pool.shape[1]
+        owner = np.arange(n) // per_point
+        if t_f_scen is None:                            # step 2
+            r = oracle.eval_pairs(S, M, t_f, t_b, mem_cap, pool, c_fwd, c_bwd, pair_cand=np.arange(n),
+                                  pair_scen=owner, want_bubble=False)
+            mk, fl = r["makespan"], r["flag"]
         else:
-            r = oracle.eval_scenario_times(S, M, t_f_scen, t_b_scen, mem_cap, pool, c_fwd, c_bwd, want_bubble=False)
-        evaluated += pool.shape[1] * K
-        best = oracle.best_from_eval(r["makespan"], r["flag"])
-        moved = 0                                       # step 4
+            mk = np.empty(n, dtype=np.int64)
+            fl = np.empty(n, dtype=np.uint8)
+            for k in range(K):
+                sl = slice(k * per_point, (k + 1) * per_point)
+                r = oracle.eval_pairs(S, M, np.asarray(t_f_scen)[:, k], np.asarray(t_b_scen)[:, k], mem_cap,
+                                      pool[:, sl], c_fwd[:, k:k + 1], np.asarray(c_bwd)[:, k:k + 1],
+                                      want_bubble=False)
+                mk[sl], fl[sl] = r["makespan"][0], r["flag"][0]
+        evaluated += n
+        moved = 0                                       # step 3
         for k in range(K):
-            if best["best_idx"][k] >= 0 and best["best_makespan"][k] < cur_mk[k]:
-                cur[:, k] = pool[:, best["best_idx"][k]]
-                cur_mk[k] = best["best_makespan"][k]
+            sl = slice(k * per_point, (k + 1) * per_point)
+            best = oracle.best_from_eval(mk[sl][None, :], fl[sl][None, :])
+            j = int(best["best_idx"][0])
+            if j >= 0 and best["best_makespan"][0] < cur_mk[k]:
+                cur[:, k] = pool[:, k * per_point + j]
+                cur_mk[k] = best["best_makespan"][0]
                 moved += 1
         if moved == 0:
             break

@@ -72,6 +72,7 @@ struct KArgs {
     int hist_bins, hist_shift, hist_in_lds;
     int *scratch;
     int cls_lo, cls_hi, ring_slots, general_all;
+    int pair_div;                          // > 0: candidate c is evaluated under scenario c / pair_div only
     long long n_chunks;
     int n_ktiles;
     int *status;                           // [0..3] input check, [16..24] candidates per ring class
@@ -332,11 +333,12 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
         if (mine == 0) return;
     }
     const long long ctiles = (a.C + 63) / 64;
-    const long long ntiles = a.K * ctiles;
+    const long long ntiles = a.pair_div ? ctiles : a.K * ctiles;
     const long long nwaves = NT >> 6;
     for (long long tile = tid >> 6; tile < ntiles; tile += nwaves) {
-        const long long k = tile / ctiles;
         const long long c = (tile % ctiles) * 64 + lane;
+        // paired mode (the guided search): every candidate has its own scenario
+        const long long k = a.pair_div ? (c < a.C ? c / a.pair_div : 0) : tile / ctiles;
         const long long kin = k % a.Kin;             // scenario in the input arrays
         const int link_up = (int)(k / a.Kin) - 1;    // link whose forward delay this copy raises, or -1
         bool run = false;
@@ -390,8 +392,12 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
             }
         }
         if (BEST) {
-            key = wave_min_u64(key);
-            if (lane == 0 && key != kNoKey) atomicMin(&a.keys[k], key);
+            if (a.pair_div) {
+                if (key != kNoKey) atomicMin(&a.keys[k], key);
+            } else {
+                key = wave_min_u64(key);
+                if (lane == 0 && key != kNoKey) atomicMin(&a.keys[k], key);
+            }
         }
     }
 }
@@ -940,7 +946,7 @@ int launch_fast(const KArgs &a, int w_bound, hipStream_t st) {
 template <bool BEST>
 int launch_general(KArgs a, const Workspace &ws, bool all, hipStream_t st) {
     a.general_all = all ? 1 : 0;
-    const long long ntiles = a.K * ((a.C + 63) / 64);
+    const long long ntiles = (a.pair_div ? 1 : a.K) * ((a.C + 63) / 64);
     long long threads = ntiles * 64;
     if (threads > ws.general_threads) threads = ws.general_threads;
     const int blocks = (int)((threads + kBlock - 1) / kBlock);
@@ -960,7 +966,7 @@ int record_event(hipEvent_t ev, hipStream_t st) {
 template <bool BEST>
 int launch_resolve(KArgs a, const Workspace &ws, int w_bound, hipStream_t st) {
     int rc;
-    if (use_fast(a.S, a.K)) {
+    if (use_fast(a.S, a.K) && !a.pair_div) {
         a.cls_hi = kNumRingClasses - 1;
         if (w_bound >= 0) {
             const int wb = w_bound > a.M - 1 ? a.M - 1 : w_bound;
@@ -1098,6 +1104,20 @@ int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *can
                  int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
                  uint64_t *out_hist,
                  void *workspace, size_t workspace_bytes, void *stream) {
+    return adaptra_detail::best(params, cands, scens, 0, out_best_idx, out_best_makespan, out_best_bubble,
+                                out_hist, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"
+
+// adaptra_best proper.  pair_div > 0 (the guided search): candidate c belongs to scenario
+// c / pair_div and is evaluated under that scenario only, by the general kernel (its lanes
+// carry candidates, so each may have a scenario of its own).
+int adaptra_detail::best(const adaptra_params_t *params, const adaptra_candidates_t *cands,
+                         const adaptra_scenarios_t *scens, int pair_div,
+                         int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
+                         uint64_t *out_hist,
+                         void *workspace, size_t workspace_bytes, void *stream) {
     Workspace ws;
     int rc = validate_common(params, cands, scens, workspace, workspace_bytes, &ws, false);
     if (rc) return rc;
@@ -1115,6 +1135,8 @@ int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *can
     a.hist_bins = params->hist_bins;
     a.hist_shift = params->hist_shift;
     a.hist_in_lds = (size_t)a.S * a.hist_bins * 4 <= (size_t)kMaxLdsHistBytes;
+    if (pair_div < 0 || (pair_div > 0 && (cands->n + pair_div - 1) / pair_div > scens->n)) return ADAPTRA_EINVAL;
+    a.pair_div = pair_div;
     hipLaunchKernelGGL(k_zero_status, dim3(1), dim3(64), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_prepass, dim3(grid_for(a.C, INT32_MAX)), dim3(kBlock), 0, st, a);
@@ -1127,6 +1149,8 @@ int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *can
     ADAPTRA_LAUNCH_CHECK();
     return ADAPTRA_OK;
 }
+
+extern "C" {
 
 int adaptra_seed(const adaptra_params_t *params, const adaptra_scenarios_t *scens, int32_t x_max,
                  const int32_t *w_current, int32_t *out_w_init, int32_t *out_w_adapted,

@@ -4,6 +4,9 @@
 #define ADAPTRA_INTERNAL_H
 
 #include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "adaptra.h"
 
 namespace adaptra_detail {
 
@@ -11,6 +14,12 @@ constexpr int kThreadsPerBlock = 256;
 
 // Records the hipError_t for adaptra_last_hip_error and returns ADAPTRA_EHIP.
 int hip_fail(hipError_t e);
+
+// adaptra_best with one more argument: pair_div > 0 evaluates candidate c under scenario
+// c / pair_div only (0: every candidate under every scenario).
+int best(const adaptra_params_t *params, const adaptra_candidates_t *cands, const adaptra_scenarios_t *scens,
+         int pair_div, int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
+         uint64_t *out_hist, void *workspace, size_t workspace_bytes, void *stream);
 
 inline int blocks_for(long long n, long long cap) {
     long long g = (n + kThreadsPerBlock - 1) / kThreadsPerBlock;

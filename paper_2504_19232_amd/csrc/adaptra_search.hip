@@ -1,15 +1,14 @@
 // adaptra_search.hip -- guided search over warm-up vectors for gfx950 (MI355X).
 //
 // A neighbourhood descent over the slacks Delta_i = w_i - w_{i+1} (the coordinates of the
-// paper's Section 4.2 planning) for schedule spaces too large to enumerate.  The work of a
-// round is one batched evaluation of the analytical model (Section 3.1) -- adaptra_best over
-// a pool of candidates x all scenarios -- so the search runs at the speed of the evaluation
-// kernels; the kernels here only build the pool and move the points.
+// paper's Section 4.2 planning) for schedule spaces too large to enumerate.  Every scenario
+// descends on its own; the work of a round is one batched evaluation of the analytical model
+// (Section 3.1) over all scenarios' neighbourhoods at once -- the search of adaptra_best in
+// its paired form, candidate c under scenario c / (moves + 1) -- so the kernels here only
+// build the pool and move the points.
 //
 //   k_search_init      every scenario's point = w_start clamped, makespan = INT32_MAX
-//   k_search_is_first  per scenario: is it the lowest scenario holding its point?
-//   k_search_compact   ordered list of those scenarios (one block, ballot prefix sums)
-//   k_search_pool      pool[s][d * (moves + 1) + j] = point d after move j, clamped
+//   k_search_pool      pool[s][k * (moves + 1) + j] = point of scenario k after move j, clamped
 //   k_search_advance   a scenario adopts its best pool entry iff strictly better
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -23,16 +22,12 @@ using adaptra_detail::blocks_for;
 using adaptra_detail::hip_fail;
 using adaptra_detail::kThreadsPerBlock;
 
-constexpr int kMaxSearchScenarios = 32768;
-
 struct SearchArgs {
     int S, M, nb, n_moves;
-    long long K, C;               // scenarios; pool entries this round
+    long long K, C;               // scenarios; pool entries = K * (n_moves + 1)
     const int *w_start;
     int *cur_w, *cur_mk;          // [S][K], [K]: the outputs double as the state
-    unsigned char *is_first;      // [K]
-    int *list;                    // [K] scenarios that are first holders, ascending
-    int *counters;                // [0] distinct points, [1] scenarios that moved
+    int *counters;                // [0] scenarios that moved in this round
     int *pool;                    // [S][C]
     const int *best_idx, *best_mk;
 };
@@ -44,50 +39,6 @@ __global__ void k_search_init(SearchArgs a) {
     if (k >= a.K) return;
     for (int s = 0; s < a.S; ++s) a.cur_w[(long long)s * a.K + k] = clamp_w(a.w_start[s], a.M);
     a.cur_mk[k] = INT32_MAX;
-}
-
-// Scenario k is a first holder iff no lower scenario has the same point.  The scan stops at
-// the first match, so it is short while the points still coincide (the usual case); all
-// lanes of a wavefront read the same j, one broadcast load per stage.
-__global__ void k_search_is_first(SearchArgs a) {
-    const long long k = (long long)blockIdx.x * kThreadsPerBlock + threadIdx.x;
-    if (k == 0) { a.counters[0] = 0; a.counters[1] = 0; }
-    if (k >= a.K) return;
-    bool first = true;
-    for (long long j = 0; j < k && first; ++j) {
-        bool same = true;
-        for (int s = 0; s < a.S && same; ++s) same = a.cur_w[(long long)s * a.K + j] == a.cur_w[(long long)s * a.K + k];
-        if (same) first = false;
-    }
-    a.is_first[k] = first ? 1 : 0;
-}
-
-// One block walks the scenarios in chunks of its size and appends the first holders in
-// ascending order (ballot + popcount inside a wavefront, a small LDS scan across them).
-__global__ __launch_bounds__(1024) void k_search_compact(SearchArgs a) {
-    __shared__ int wave_count[16];
-    __shared__ int base;
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    if (threadIdx.x == 0) base = 0;
-    __syncthreads();
-    for (long long k0 = 0; k0 < a.K; k0 += 1024) {
-        const long long k = k0 + threadIdx.x;
-        const bool first = k < a.K && a.is_first[k];
-        const unsigned long long m = __ballot(first);
-        if (lane == 0) wave_count[wv] = __popcll(m);
-        __syncthreads();
-        int before = base;
-        for (int i = 0; i < wv; ++i) before += wave_count[i];
-        if (first) a.list[before + __popcll(m & ((1ull << lane) - 1ull))] = (int)k;
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            int t = 0;
-            for (int i = 0; i < 16; ++i) t += wave_count[i];
-            base += t;
-        }
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) a.counters[0] = base;
 }
 
 // Move j of the neighbourhood: j = 0 keeps the point; otherwise (j - 1) / 2 numbers the stage
@@ -106,9 +57,9 @@ __global__ void k_search_pool(SearchArgs a) {
     const long long c = (long long)blockIdx.x * kThreadsPerBlock + threadIdx.x;
     if (c >= a.C) return;
     const int per_point = a.n_moves + 1;
-    const long long d = c / per_point;
+    const long long k = c / per_point;
     const int j = (int)(c % per_point);
-    const long long k = a.list[d];
+    if (c == 0) a.counters[0] = 0;        // nobody has moved yet in this round
     int lo, hi, sign;
     decode_move(a.nb, a.S, j, &lo, &hi, &sign);
     for (int s = 0; s < a.S; ++s) {
@@ -124,7 +75,7 @@ __global__ void k_search_advance(SearchArgs a) {
     if (bi >= 0 && a.best_mk[k] < a.cur_mk[k]) {
         for (int s = 0; s < a.S; ++s) a.cur_w[(long long)s * a.K + k] = a.pool[(long long)s * a.C + bi];
         a.cur_mk[k] = a.best_mk[k];
-        atomicAdd(&a.counters[1], 1);
+        atomicAdd(&a.counters[0], 1);
     }
 }
 
@@ -133,20 +84,18 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 struct SearchPlan {
     int n_moves;
     long long c_max;
-    size_t off_first, off_list, off_counters, off_pool, off_best_idx, off_best_mk, off_best_ws, best_ws_bytes, total;
+    size_t off_counters, off_pool, off_best_idx, off_best_mk, off_best_ws, best_ws_bytes, total;
 };
 
 bool plan_search(const adaptra_params_t *p, long long K, int nb, SearchPlan *pl) {
     if (!p || p->S < 1 || p->S > ADAPTRA_MAX_STAGES || p->M < 1 || p->M > ADAPTRA_MAX_MICROBATCHES) return false;
-    if (K < 1 || K > kMaxSearchScenarios || (nb != 0 && nb != 1)) return false;
+    if (K < 1 || K > INT32_MAX || (nb != 0 && nb != 1)) return false;
     pl->n_moves = nb == 0 ? 2 * p->S : p->S * (p->S + 1);
     pl->c_max = K * (pl->n_moves + 1);
     if (pl->c_max > INT32_MAX) return false;
     pl->best_ws_bytes = adaptra_best_workspace_bytes(p, pl->c_max, K);
     if (pl->best_ws_bytes == 0) return false;
     size_t o = 0;
-    pl->off_first = o;    o += align256((size_t)K);
-    pl->off_list = o;     o += align256((size_t)K * 4);
     pl->off_counters = o; o += 256;
     pl->off_pool = o;     o += align256((size_t)p->S * (size_t)pl->c_max * 4);
     pl->off_best_idx = o; o += align256((size_t)K * 4);
@@ -180,50 +129,38 @@ int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *sc
     a.K = scens->n;
     a.w_start = w_start;
     a.cur_w = out_w; a.cur_mk = out_makespan;
-    a.is_first = (unsigned char *)(base + pl.off_first);
-    a.list = (int *)(base + pl.off_list);
     a.counters = (int *)(base + pl.off_counters);
     a.pool = (int *)(base + pl.off_pool);
+    a.C = pl.c_max;
     int *best_idx = (int *)(base + pl.off_best_idx), *best_mk = (int *)(base + pl.off_best_mk);
     a.best_idx = best_idx; a.best_mk = best_mk;
     adaptra_params_t bp = *params;
     bp.hist_bins = 0; bp.hist_shift = 0;
     const int kblocks = blocks_for(a.K, INT32_MAX);
+    const adaptra_candidates_t pool{a.C, a.pool, -1};
 
     hipLaunchKernelGGL(k_search_init, dim3(kblocks), dim3(kThreadsPerBlock), 0, st, a);
     ADAPTRA_CHECK_LAUNCH();
     int rounds = 0;
     long long evaluated = 0;
-    int counters[2] = {0, 0};
     for (;;) {
-        // step 1: distinct points (k_search_is_first also clears both counters)
-        hipLaunchKernelGGL(k_search_is_first, dim3(kblocks), dim3(kThreadsPerBlock), 0, st, a);
-        ADAPTRA_CHECK_LAUNCH();
-        hipLaunchKernelGGL(k_search_compact, dim3(1), dim3(1024), 0, st, a);
-        ADAPTRA_CHECK_LAUNCH();
-        hipError_t e = hipMemcpyAsync(counters, a.counters, sizeof(int), hipMemcpyDeviceToHost, st);
-        if (e != hipSuccess) return hip_fail(e);
-        if ((e = hipStreamSynchronize(st)) != hipSuccess) return hip_fail(e);
-        const long long D = counters[0];
-        if (D < 1 || D > a.K) return ADAPTRA_EHIP;            // cannot happen: scenario 0 is always first
         ++rounds;
-        // step 2: the pool
-        a.C = D * (pl.n_moves + 1);
+        // step 1: every scenario's point and its neighbours
         hipLaunchKernelGGL(k_search_pool, dim3(blocks_for(a.C, INT32_MAX)), dim3(kThreadsPerBlock), 0, st, a);
         ADAPTRA_CHECK_LAUNCH();
-        // step 3: batched evaluation and per-scenario argmin
-        adaptra_candidates_t cd{a.C, a.pool, -1};
-        int rc = adaptra_best(&bp, &cd, scens, best_idx, best_mk, nullptr, nullptr,
-                          base + pl.off_best_ws, pl.best_ws_bytes, stream);
+        // step 2: each pool entry under its own scenario, and the best entry per scenario
+        int rc = adaptra_detail::best(&bp, &pool, scens, pl.n_moves + 1, best_idx, best_mk, nullptr, nullptr,
+                                      base + pl.off_best_ws, pl.best_ws_bytes, stream);
         if (rc) return rc;
-        evaluated += a.C * a.K;
-        // step 4: move
+        evaluated += a.C;
+        // step 3: move
         hipLaunchKernelGGL(k_search_advance, dim3(kblocks), dim3(kThreadsPerBlock), 0, st, a);
         ADAPTRA_CHECK_LAUNCH();
-        e = hipMemcpyAsync(counters, a.counters, 2 * sizeof(int), hipMemcpyDeviceToHost, st);
+        int moved = 0;
+        hipError_t e = hipMemcpyAsync(&moved, a.counters, sizeof(int), hipMemcpyDeviceToHost, st);
         if (e != hipSuccess) return hip_fail(e);
         if ((e = hipStreamSynchronize(st)) != hipSuccess) return hip_fail(e);
-        if (counters[1] == 0 || rounds >= max_iters) break;
+        if (moved == 0 || rounds >= max_iters) break;
     }
     if (out_rounds) *out_rounds = rounds;
     if (out_evaluated) *out_evaluated = evaluated;

@@ -93,18 +93,35 @@ def test_result_is_a_local_optimum_and_bounded_by_the_exhaustive_one(oracle, nb)
     assert reached >= 0.5 * total          # a heuristic, but not a useless one on small pipelines
 
 
-def test_scenarios_share_the_pool(oracle):
-    """Scenario 1 has no delay at all and would stay put on its own; it may still not end
-    worse than where it started, and scenario 0's descent is not disturbed by it."""
+def test_scenarios_descend_independently(oracle):
+    """The result for a scenario is what the search finds on that scenario alone; only the
+    number of rounds is shared (the slowest descent's)."""
+    rng = np.random.default_rng(77)
+    S, M, K = 4, 14, 7
+    t_f, t_b = rng.integers(5, 30, S), rng.integers(5, 50, S)
+    cf, cb = rng.integers(0, 300, (S - 1, K)), rng.integers(0, 300, (S - 1, K))
+    cap = np.full(S, M)
+    start = np.arange(S - 1, -1, -1)
+    for nb in (0, 1):
+        together = osearch.search(S, M, t_f, t_b, cap, start, cf, cb, neighbourhood=nb)
+        rounds = []
+        for k in range(K):
+            alone = osearch.search(S, M, t_f, t_b, cap, start, cf[:, k:k + 1], cb[:, k:k + 1], neighbourhood=nb)
+            assert np.array_equal(alone["w"][:, 0], together["w"][:, k])
+            assert alone["makespan"][0] == together["makespan"][k]
+            rounds.append(alone["rounds"])
+        assert together["rounds"] == max(rounds)
+        assert together["evaluated"] == together["rounds"] * K * (len(osearch.moves(S, nb)) + 1)
+
+
+def test_a_scenario_without_delays_stays_where_it_is(oracle):
     S, M = 2, 60
     t = np.full(S, 10)
-    cf = np.array([[25, 0]])
-    r = osearch.search(S, M, t, t, np.full(S, M), np.array([1, 0]), cf, cf)
-    assert list(r["w"][:, 0]) == [4, 0]
-    assert r["makespan"][1] == (M + S - 1) * 20
-    alone = osearch.search(S, M, t, t, np.full(S, M), np.array([1, 0]), cf[:, 1:], cf[:, 1:])
+    z = np.zeros((1, 1), dtype=np.int64)
+    alone = osearch.search(S, M, t, t, np.full(S, M), np.array([1, 0]), z, z)
     # round 1 prices the start (its makespan was unknown), round 2 finds nothing better
     assert alone["rounds"] == 2 and list(alone["w"][:, 0]) == [1, 0]
+    assert alone["makespan"][0] == (M + S - 1) * 20
 
 
 def test_infeasible_start_without_feasible_neighbour(oracle):

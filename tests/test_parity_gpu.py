@@ -592,7 +592,7 @@ SEARCH_CASES = [
     (105, 8, 32, 64, 0, 50, False, dict(c_hi=3000)),
     (106, 8, 32, 20, 1, 4, False, dict(c_hi=3000)),        # stopped by max_iters
     (107, 16, 40, 12, 0, 50, True, dict(c_hi=2000, cap=False)),
-    (108, 5, 20, 1100, 0, 50, False, {}),                  # more scenarios than one compaction chunk
+    (108, 5, 20, 1100, 0, 50, False, {}),                  # many scenarios
 ]
 
 
