@@ -246,10 +246,13 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
                     void *workspace, size_t workspace_bytes, void *stream);
 
 /* Kernel selection, process-wide; for tests and measurements.
- *   0  automatic (default): register/LDS kernel where S and the scenario count suit
- *      it, the general kernel otherwise
+ *   0  automatic (default): the register/LDS kernel with scenarios on the lanes where the
+ *      stage count (<= 32) and the scenario count (>= 6) suit it, else the kernel with
+ *      candidates on the lanes and its state on chip; the general kernel for what fits
+ *      neither (more than 32 stages, warm-ups deeper than the LDS ring)
  *   1  general kernel only (any S, M, warm-up depth)
- *   2  register/LDS kernel wherever its limits allow, regardless of lane efficiency
+ *   2  scenario-lanes kernel wherever its limits allow, regardless of lane efficiency
+ *   3  candidate-lanes kernel wherever its limits allow
  * Returns the previous mode, or -1 for an unknown mode (nothing changes). */
 int adaptra_set_kernel_mode(int mode);
 

@@ -11,6 +11,8 @@
 //   k_resolve_scen_lanes the hot kernel: one wavefront = one candidate at a time x 64
 //                        scenarios (one per lane); stage frontiers in VGPRs, the forward
 //                        frontier of the in-flight micro-batches in an LDS ring
+//   k_resolve_cand_lanes few scenarios, or a scenario per candidate: one lane per pair,
+//                        stage frontiers and link delays in VGPRs, micro-batch ring in LDS
 //   k_resolve_general    any S / M / warm-up depth: one lane per pair (64 candidates of one
 //                        scenario per wavefront), state in global scratch, DPP argmin
 //   k_eval_epilogue      after the resolve kernels: flag byte and bubbles of every pair,
@@ -77,6 +79,7 @@ struct KArgs {
     int n_ktiles;
     int *status;                           // [0..3] input check, [16..24] candidates per ring class
     int *mk_t;                             // eval: makespan, candidate-major [C][K]
+    int *tpad;                             // t_f at [0..63], t_b at [64..127], zero beyond stage S-1
 };
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -192,6 +195,10 @@ __device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v)
 __global__ __launch_bounds__(kBlock) void k_prepass(KArgs a) {
     __shared__ int class_count[kNumRingClasses + 1];
     if (threadIdx.x <= kNumRingClasses) class_count[threadIdx.x] = 0;
+    if (blockIdx.x == 0 && threadIdx.x < 128) {             // stage times padded with zeros (candidate-lanes kernel)
+        const int i = threadIdx.x & 63;
+        a.tpad[threadIdx.x] = i < a.S ? (threadIdx.x < 64 ? a.t_f[i] : a.t_b[i]) : 0;
+    }
     __syncthreads();
     long long c = (long long)blockIdx.x * kBlock + threadIdx.x;
     if (c < a.C) {
@@ -397,6 +404,141 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
             } else {
                 key = wave_min_u64(key);
                 if (lane == 0 && key != kNoKey) atomicMin(&a.keys[k], key);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Candidate-lanes kernel: lane = candidate, like the general kernel, but with the state on
+// chip, for the problems the hot kernel's mapping does not fit: fewer scenarios than would
+// fill its lanes, and the guided search's paired form (a scenario per candidate).
+//   last[S]              VGPRs (the stage loops are unrolled: static indices)
+//   c_fwd, c_bwd         VGPRs, 2 (S - 1) per lane (the scenario may differ per lane)
+//   w                    S bytes packed into S / 4 VGPRs
+//   fwd[m]               LDS ring [slot][lane], D slots per wavefront as in the hot kernel,
+//                        slot = m mod D with a per-lane index (bank = lane: conflict-free)
+// Plain form of the Section 3.1 recurrence (see the general kernel).  All lanes walk the
+// rounds r = -max w[0] .. M-1 together; a lane's forward step of stage s counts only if its
+// micro-batch w[s] + r exists (a select, no divergence).  The write of a step that does not
+// count lands in a slot no live micro-batch uses: slots of live micro-batches differ from it
+// by less than D.  Ring reads follow the previous stage's write in program order, so a link
+// with equal w needs no special case.  S is padded as in the hot kernel.
+template <int S, bool BEST, bool VT>
+__global__ __launch_bounds__(kBlock, S >= 32 ? 4 : 6) void k_resolve_cand_lanes(KArgs) {
+    // The arguments are read through kargs() where they are needed (see there): kept in SGPRs
+    // across the round loop they would crowd out the loop's own scalars.
+    extern __shared__ int lds[];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int D = kargs()->ring_slots, M = kargs()->M;
+    int *const ring = lds + wv * D * 64 + lane;          // slot i of this lane at ring[i * 64]
+    const long long ctiles = (kargs()->C + 63) / 64;
+    const long long ntiles = kargs()->pair_div ? ctiles : kargs()->K * ctiles;
+    const long long nwaves = (long long)gridDim.x * kWavesPerBlock;
+    // Stage times come from the zero-padded table, re-read in blocks of 16 stages inside the
+    // round loop (scalar loads, a cache hit each): kept for all stages they would take 2 S
+    // SGPRs, more than there are at S = 32.
+    constexpr int kTimesBlock = 16;
+    typedef __attribute__((address_space(4))) int ConstInt;   // written by k_prepass, constant here
+    for (long long tile = (long long)blockIdx.x * kWavesPerBlock + wv; tile < ntiles; tile += nwaves) {
+        const long long c = (tile % ctiles) * 64 + lane;
+        const long long k = kargs()->pair_div ? (c < kargs()->C ? c / kargs()->pair_div : 0) : tile / ctiles;
+        const long long kin = k % kargs()->Kin;
+        const int link_up = (int)(k / kargs()->Kin) - 1;
+        bool run = false;
+        if (c < kargs()->C) {
+            const int flag = kargs()->cand_flag[c];
+            const int cls = kargs()->cand_class[c];
+            run = (BEST ? (flag == ADAPTRA_FLAG_FEASIBLE) : !(flag & ADAPTRA_FLAG_DEADLOCK)) &&
+                  cls >= kargs()->cls_lo && cls <= kargs()->cls_hi;
+        }
+        if (__ballot(run) == 0ull) continue;
+        // w of the lane's candidate, four stages per register; lanes that do not run get w = 0
+        // (their ring indices must still stay inside the ring)
+        unsigned wpk[(S + 3) / 4];
+#pragma unroll
+        for (int i = 0; i < (S + 3) / 4; ++i)
+            wpk[i] = run ? *(const unsigned *)(kargs()->cand_wq + c * kargs()->wq_stride + 4 * i) : 0u;
+        int cf[S > 1 ? S - 1 : 1], cb[S > 1 ? S - 1 : 1], last[S];
+#pragma unroll
+        for (int s = 0; s < S; ++s) last[s] = 0;
+#pragma unroll
+        for (int s = 0; s + 1 < S; ++s) {
+            const bool real = s + 1 < kargs()->S;
+            cf[s] = real ? kargs()->cf[(long long)s * kargs()->Kin + kin] + (s == link_up ? kargs()->sens_delta : 0) : 0;
+            cb[s] = real ? kargs()->cb[(long long)s * kargs()->Kin + kin] : 0;
+        }
+        int w0max = (int)(wpk[0] & 0xffu);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) w0max = imax(w0max, __shfl_xor(w0max, off));
+        w0max = uni(w0max);
+        int b = w0max == 0 ? 0 : D - w0max;              // (-w0max) mod D: the ring slot of micro-batch r
+        for (int r = -w0max; r < M; ++r) {
+#pragma unroll
+            for (int h = 0; h < S; h += kTimesBlock) {   // forward sweep
+                const ConstInt *tf = (const ConstInt *)kargs()->tpad + h;      // scalar loads             // load this block's times here, not before the loops
+#pragma unroll
+                for (int j = 0; j < kTimesBlock && h + j < S; ++j) {
+                    const int s = h + j;
+                    const int ws = (int)((wpk[s / 4] >> (8 * (s % 4))) & 0xffu);
+                    const bool valid = (unsigned)(ws + r) < (unsigned)M;
+                    unsigned slot = (unsigned)(ws + b);
+                    slot = slot < slot - (unsigned)D ? slot : slot - (unsigned)D;      // mod D (w < D, b < D)
+                    int *const p = ring + slot * 64;
+                    int t_f_s;
+                    if constexpr (VT) t_f_s = s < kargs()->S ? kargs()->tfs[(long long)s * kargs()->Kin + kin] : 0;
+                    else t_f_s = tf[j];
+                    int fin;
+                    if (s == 0) fin = last[0] + t_f_s;
+                    else fin = imax(last[s], *p + cf[s - 1]) + t_f_s;
+                    last[s] = valid ? fin : last[s];
+                    if (s < S - 1) *p = fin;
+                }
+            }
+            if (r >= 0) {                                // backward sweep
+                int carry = 0;
+#pragma unroll
+                for (int h = (S - 1) / kTimesBlock * kTimesBlock; h >= 0; h -= kTimesBlock) {
+                    const ConstInt *tb = (const ConstInt *)kargs()->tpad + 64 + h;
+#pragma unroll
+                    for (int j = kTimesBlock - 1; j >= 0; --j) {
+                        const int s = h + j;
+                        if (s > S - 1) continue;
+                        int t_b_s;
+                        if constexpr (VT) t_b_s = s < kargs()->S ? kargs()->tbs[(long long)s * kargs()->Kin + kin] : 0;
+                        else t_b_s = tb[j];
+                        const int arrive = s == S - 1 ? 0 : carry + cb[s < S - 1 ? s : 0];
+                        last[s] = imax(last[s], arrive) + t_b_s;
+                        carry = last[s];
+                    }
+                }
+            }
+            b = b + 1 == D ? 0 : b + 1;
+        }
+        const int mk = last[0];                          // B(0, M-1) is the last op of all
+        unsigned long long key = kNoKey;
+        if (run) {
+            if (BEST) {
+                key = ((unsigned long long)(unsigned)mk << 32) | (unsigned)c;
+                if (kargs()->hist) {
+                    for (int s = 0; s < kargs()->S; ++s) {
+                        const int tau_s = kargs()->tfs ? kargs()->tfs[(long long)s * kargs()->Kin + kin] + kargs()->tbs[(long long)s * kargs()->Kin + kin]
+                                                : kargs()->t_f[s] + kargs()->t_b[s];
+                        int bin = (mk - M * tau_s) >> kargs()->hist_shift;
+                        bin = bin > kargs()->hist_bins - 1 ? kargs()->hist_bins - 1 : bin;
+                        atomicAdd(&kargs()->hist[s * kargs()->hist_bins + bin], 1ull);
+                    }
+                }
+            } else {
+                kargs()->mk_t[c * kargs()->K + k] = mk;        // transposed and completed by k_eval_epilogue
+            }
+        }
+        if (BEST) {
+            if (kargs()->pair_div) {
+                if (key != kNoKey) atomicMin(&kargs()->keys[k], key);
+            } else {
+                key = wave_min_u64(key);
+                if (lane == 0 && key != kNoKey) atomicMin(&kargs()->keys[k], key);
             }
         }
     }
@@ -804,7 +946,7 @@ int hot_kernel_stages(int S) {
 }
 
 struct Workspace {
-    size_t off_flag, off_class, off_wq, off_keys, off_status, off_scratch, off_mkt, total;
+    size_t off_flag, off_class, off_wq, off_keys, off_status, off_tpad, off_scratch, off_mkt, total;
     int wq_stride;
     long long general_threads;
 };
@@ -830,6 +972,7 @@ bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws, bool 
     ws->off_wq = o;      o += align256((size_t)C * ws->wq_stride);
     ws->off_keys = o;    o += align256((size_t)K * 8);
     ws->off_status = o;  o += 256;
+    ws->off_tpad = o;    o += 512;
     ws->off_scratch = o; o += align256((size_t)ws->general_threads * (2 * S + M) * 4);
     ws->off_mkt = o;     o += with_mkt ? align256((size_t)C * (size_t)K * 4) : 0;   // last: the search needs none
     ws->total = o;
@@ -841,9 +984,16 @@ bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws, bool 
 // many of the 64 lanes carry a scenario, while the general kernel's grows with the number of
 // scenarios; measured on 16 384 candidates (S = 8 and 16) they cross between 4 and 8 scenarios.
 bool use_fast(int S, long long K) {
-    if (g_kernel_mode == 1 || hot_kernel_stages(S) == 0) return false;
+    if (g_kernel_mode == 1 || g_kernel_mode == 3 || hot_kernel_stages(S) == 0) return false;
     if (g_kernel_mode == 2) return true;
     return K >= 6;
+}
+// With too few scenarios for the hot kernel's lanes (and in the search's paired form) the
+// candidate-lanes kernel takes what fits its ring; mode 1 keeps everything on the general one.
+// (Per-scenario stage times cost it a load per step; from 16 stages on that variant runs out
+// of registers and the general kernel keeps those problems.)
+bool use_cand_lanes(int S, bool stage_times) {
+    return g_kernel_mode != 1 && hot_kernel_stages(S) != 0 && !(stage_times && hot_kernel_stages(S) >= 16);
 }
 
 int hip_fail(hipError_t e) { return adaptra_detail::hip_fail(e); }
@@ -888,6 +1038,7 @@ void fill_args(KArgs *a, const adaptra_params_t *p, const adaptra_candidates_t *
     a->wq_stride = ws.wq_stride;
     a->keys = (unsigned long long *)(base + ws.off_keys);
     a->status = (int *)(base + ws.off_status);
+    a->tpad = (int *)(base + ws.off_tpad);
     a->scratch = (int *)(base + ws.off_scratch);
     a->mk_t = (int *)(base + ws.off_mkt);
     a->n_ktiles = (int)((sc->n + 63) / 64);
@@ -943,6 +1094,50 @@ int launch_fast(const KArgs &a, int w_bound, hipStream_t st) {
     }
 }
 
+template <int S, bool BEST, bool VT>
+int launch_cand_lanes_one(KArgs a, int w_bound, hipStream_t st) {
+    const long long ntiles = (a.pair_div ? 1 : a.K) * ((a.C + 63) / 64);
+    long long blocks = (ntiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks > 256 * 32) blocks = 256 * 32;            // the tiles are walked in a loop
+    int first = 0, last = kNumRingClasses - 1;
+    bool single = false;
+    if (w_bound >= 0) {
+        int wb = w_bound > a.M - 1 ? a.M - 1 : w_bound;
+        last = (wb + 8) / 8 - 1;
+        if (last > kNumRingClasses - 1) last = kNumRingClasses - 1;
+        single = true;
+    }
+    for (int cls = single ? last : first; cls <= last; ++cls) {
+        a.cls_lo = single ? 0 : cls;
+        a.cls_hi = cls;
+        a.ring_slots = 8 * (cls + 1);
+        const size_t lds = (size_t)kWavesPerBlock * a.ring_slots * 256;
+        if (lds > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute((const void *)k_resolve_cand_lanes<S, BEST, VT>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        hipLaunchKernelGGL((k_resolve_cand_lanes<S, BEST, VT>), dim3((unsigned)blocks), dim3(kBlock), lds, st, a);
+        ADAPTRA_LAUNCH_CHECK();
+    }
+    return ADAPTRA_OK;
+}
+
+template <bool BEST>
+int launch_cand_lanes(const KArgs &a, int w_bound, hipStream_t st) {
+#define ADAPTRA_CASE(S_)                                                                         \
+    case S_:                                                                                     \
+        if constexpr (S_ < 16) {                                                                 \
+            if (a.tfs) return launch_cand_lanes_one<S_, BEST, true>(a, w_bound, st);             \
+        }                                                                                        \
+        return launch_cand_lanes_one<S_, BEST, false>(a, w_bound, st);
+    switch (hot_kernel_stages(a.S)) {
+        ADAPTRA_CASE(2) ADAPTRA_CASE(4) ADAPTRA_CASE(8) ADAPTRA_CASE(16) ADAPTRA_CASE(32)
+        default: return ADAPTRA_EINVAL;
+    }
+#undef ADAPTRA_CASE
+}
+
 template <bool BEST>
 int launch_general(KArgs a, const Workspace &ws, bool all, hipStream_t st) {
     a.general_all = all ? 1 : 0;
@@ -966,7 +1161,8 @@ int record_event(hipEvent_t ev, hipStream_t st) {
 template <bool BEST>
 int launch_resolve(KArgs a, const Workspace &ws, int w_bound, hipStream_t st) {
     int rc;
-    if (use_fast(a.S, a.K) && !a.pair_div) {
+    if ((use_fast(a.S, a.K) && !a.pair_div) || use_cand_lanes(a.S, a.tfs != nullptr)) {
+        const bool hot = use_fast(a.S, a.K) && !a.pair_div;
         a.cls_hi = kNumRingClasses - 1;
         if (w_bound >= 0) {
             const int wb = w_bound > a.M - 1 ? a.M - 1 : w_bound;
@@ -975,7 +1171,7 @@ int launch_resolve(KArgs a, const Workspace &ws, int w_bound, hipStream_t st) {
         }
         const int general_from = a.cls_hi;               // classes above it go to the general kernel
         if ((rc = record_event(g_ev_before, st))) return rc;
-        if ((rc = launch_fast<BEST>(a, w_bound, st))) return rc;
+        if ((rc = hot ? launch_fast<BEST>(a, w_bound, st) : launch_cand_lanes<BEST>(a, w_bound, st))) return rc;
         if ((rc = record_event(g_ev_after, st))) return rc;
         a.cls_hi = general_from;
         return launch_general<BEST>(a, ws, false, st);   // too deep for the ring, or beyond w_bound
@@ -1175,7 +1371,7 @@ int adaptra_seed(const adaptra_params_t *params, const adaptra_scenarios_t *scen
 }
 
 int adaptra_set_kernel_mode(int mode) {
-    if (mode < 0 || mode > 2) return -1;
+    if (mode < 0 || mode > 3) return -1;
     const int prev = g_kernel_mode;
     g_kernel_mode = mode;
     return prev;
