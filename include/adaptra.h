@@ -246,10 +246,10 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
                     void *workspace, size_t workspace_bytes, void *stream);
 
 /* Kernel selection, process-wide; for tests and measurements.
- *   0  automatic (default): the register/LDS kernel with scenarios on the lanes where the
- *      stage count (<= 32) and the scenario count (>= 6) suit it, else the kernel with
- *      candidates on the lanes and its state on chip; the general kernel for what fits
- *      neither (more than 32 stages, warm-ups deeper than the LDS ring)
+ *   0  automatic (default): up to 32 stages, the register/LDS kernel with scenarios on the
+ *      lanes from 32 scenarios on, below that the kernel with candidates on the lanes (the
+ *      measured crossover); the general kernel for what fits neither (more than 32 stages,
+ *      warm-ups deeper than the LDS ring)
  *   1  general kernel only (any S, M, warm-up depth)
  *   2  scenario-lanes kernel wherever its limits allow, regardless of lane efficiency
  *   3  candidate-lanes kernel wherever its limits allow

@@ -38,7 +38,7 @@ constexpr int kNeg = -(1 << 30);          // "no earlier op": below every shifte
 #ifndef ADAPTRA_CHUNK
 #define ADAPTRA_CHUNK 16
 #endif
-constexpr int kChunk = ADAPTRA_CHUNK;      // candidates one wavefront works through
+constexpr int kChunk = ADAPTRA_CHUNK;      // candidates one wavefront works through, at most
 #ifndef ADAPTRA_WPB
 #define ADAPTRA_WPB 4
 #endif
@@ -76,6 +76,7 @@ struct KArgs {
     int cls_lo, cls_hi, ring_slots, general_all;
     int pair_div;                          // > 0: candidate c is evaluated under scenario c / pair_div only
     long long n_chunks;
+    int chunk;                             // candidates per wavefront of the hot kernel (1..kChunk)
     int n_ktiles;
     int *status;                           // [0..3] input check, [16..24] candidates per ring class
     int *mk_t;                             // eval: makespan, candidate-major [C][K]
@@ -595,7 +596,7 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? (VT ? 3 : ADAPTRA_WAVES32) : (S >
 
     const long long task = (long long)blockIdx.x * kWavesPerBlock + wv;
     const int tile = (int)(task % kargs()->n_ktiles);
-    const long long c0 = (task / kargs()->n_ktiles) * kChunk;
+    const long long c0 = (task / kargs()->n_ktiles) * kargs()->chunk;
     if (c0 < kargs()->C) {
         const long long K = kargs()->K;
         const long long k = (long long)tile * 64 + lane;
@@ -632,7 +633,8 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? (VT ? 3 : ADAPTRA_WAVES32) : (S >
 
         unsigned long long key = kNoKey;
         const long long c_left = kargs()->C - c0;
-        const int c_end = (int)(c_left < kChunk ? c_left : kChunk);
+        const int chunk = kargs()->chunk;
+        const int c_end = (int)(c_left < chunk ? c_left : chunk);
         for (int ci = 0; ci < c_end; ++ci) {
             const long long c = c0 + ci;
             {
@@ -980,20 +982,27 @@ bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws, bool 
 }
 
 
-// The hot kernel puts scenarios on lanes, so its time per candidate does not depend on how
-// many of the 64 lanes carry a scenario, while the general kernel's grows with the number of
-// scenarios; measured on 16 384 candidates (S = 8 and 16) they cross between 4 and 8 scenarios.
-bool use_fast(int S, long long K) {
-    if (g_kernel_mode == 1 || g_kernel_mode == 3 || hot_kernel_stages(S) == 0) return false;
-    if (g_kernel_mode == 2) return true;
-    return K >= 6;
-}
-// With too few scenarios for the hot kernel's lanes (and in the search's paired form) the
-// candidate-lanes kernel takes what fits its ring; mode 1 keeps everything on the general one.
-// (Per-scenario stage times cost it a load per step; from 16 stages on that variant runs out
-// of registers and the general kernel keeps those problems.)
-bool use_cand_lanes(int S, bool stage_times) {
-    return g_kernel_mode != 1 && hot_kernel_stages(S) != 0 && !(stage_times && hot_kernel_stages(S) >= 16);
+// Which of the two on-chip kernels runs (the general kernel takes what neither can: more than
+// 32 stages, warm-ups deeper than the ring).  The scenario-lanes kernel spends 6 VALU ops per
+// stage and round on 64 scenarios whether or not all 64 lanes carry one; the candidate-lanes
+// kernel spends 13 on 64 pairs.  Measured on 8 192 candidates of configurations 1-3 they cross
+// at 28-32 scenarios for every stage count.  The candidate-lanes kernel is also the only one
+// for the search's paired form; with per-scenario stage times it runs out of registers from
+// 16 stages on, and the scenario-lanes kernel then wins from 6 scenarios against the general one.
+enum ResolveKernel { kScenarioLanes, kCandidateLanes, kGeneralOnly };
+ResolveKernel choose_kernel(int S, long long K, bool stage_times, bool paired) {
+    const bool sized = hot_kernel_stages(S) != 0;
+    const bool scen_ok = sized && !paired;
+    const bool cand_ok = sized && !(stage_times && hot_kernel_stages(S) >= 16);
+    switch (g_kernel_mode) {
+        case 1: return kGeneralOnly;
+        case 2: return scen_ok ? kScenarioLanes : kGeneralOnly;
+        case 3: return cand_ok ? kCandidateLanes : kGeneralOnly;
+        default: break;
+    }
+    if (scen_ok && (K >= 32 || (!cand_ok && K >= 6))) return kScenarioLanes;
+    if (cand_ok) return kCandidateLanes;
+    return kGeneralOnly;
 }
 
 int hip_fail(hipError_t e) { return adaptra_detail::hip_fail(e); }
@@ -1042,7 +1051,15 @@ void fill_args(KArgs *a, const adaptra_params_t *p, const adaptra_candidates_t *
     a->scratch = (int *)(base + ws.off_scratch);
     a->mk_t = (int *)(base + ws.off_mkt);
     a->n_ktiles = (int)((sc->n + 63) / 64);
-    a->n_chunks = (cd->n + kChunk - 1) / kChunk;
+    // A wavefront of the hot kernel works through `chunk` candidates in a row, which amortises
+    // its per-scenario set-up; a small problem takes shorter chunks so that there are still
+    // enough wavefronts (about two per SIMD slot) to fill the chip.
+    {
+        const long long want_waves = 8192;
+        long long chunk = cd->n * a->n_ktiles / want_waves;
+        a->chunk = (int)(chunk < 1 ? 1 : (chunk > kChunk ? kChunk : chunk));
+    }
+    a->n_chunks = (cd->n + a->chunk - 1) / a->chunk;
 }
 
 template <int S, bool BEST, bool VT>
@@ -1161,8 +1178,9 @@ int record_event(hipEvent_t ev, hipStream_t st) {
 template <bool BEST>
 int launch_resolve(KArgs a, const Workspace &ws, int w_bound, hipStream_t st) {
     int rc;
-    if ((use_fast(a.S, a.K) && !a.pair_div) || use_cand_lanes(a.S, a.tfs != nullptr)) {
-        const bool hot = use_fast(a.S, a.K) && !a.pair_div;
+    const ResolveKernel which = choose_kernel(a.S, a.K, a.tfs != nullptr, a.pair_div != 0);
+    if (which != kGeneralOnly) {
+        const bool hot = which == kScenarioLanes;
         a.cls_hi = kNumRingClasses - 1;
         if (w_bound >= 0) {
             const int wb = w_bound > a.M - 1 ? a.M - 1 : w_bound;
