@@ -27,7 +27,7 @@ struct SearchArgs {
     long long K, C;               // scenarios; pool entries = K * (n_moves + 1)
     const int *w_start;
     int *cur_w, *cur_mk;          // [S][K], [K]: the outputs double as the state
-    int *counters;                // [0] scenarios that moved in this round
+    int *counters;                // [0] scenarios that moved in this round, [1] largest w[0] any point has had
     int *pool;                    // [S][C]
     const int *best_idx, *best_mk;
 };
@@ -76,6 +76,7 @@ __global__ void k_search_advance(SearchArgs a) {
         for (int s = 0; s < a.S; ++s) a.cur_w[(long long)s * a.K + k] = a.pool[(long long)s * a.C + bi];
         a.cur_mk[k] = a.best_mk[k];
         atomicAdd(&a.counters[0], 1);
+        atomicMax(&a.counters[1], a.cur_w[k]);           // w is non-increasing over the stages of a feasible point
     }
 }
 
@@ -137,10 +138,28 @@ int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *sc
     adaptra_params_t bp = *params;
     bp.hist_bins = 0; bp.hist_shift = 0;
     const int kblocks = blocks_for(a.K, INT32_MAX);
-    const adaptra_candidates_t pool{a.C, a.pool, -1};
+    // An upper bound on every w in the pool lets the evaluation run as a single launch with the
+    // smallest ring that fits: the largest w[0] any point has had (kept on the device, read
+    // back with the round's move count), plus one for the move.
+    int w_top = 0;
+    {
+        int w_host[ADAPTRA_MAX_STAGES];
+        hipError_t e = hipMemcpyAsync(w_host, w_start, sizeof(int) * a.S, hipMemcpyDeviceToHost, st);
+        if (e != hipSuccess) return hip_fail(e);
+        if ((e = hipStreamSynchronize(st)) != hipSuccess) return hip_fail(e);
+        for (int s = 0; s < a.S; ++s) {
+            const int w = w_host[s] < 0 ? 0 : (w_host[s] > a.M - 1 ? a.M - 1 : w_host[s]);
+            w_top = w > w_top ? w : w_top;
+        }
+    }
 
     hipLaunchKernelGGL(k_search_init, dim3(kblocks), dim3(kThreadsPerBlock), 0, st, a);
     ADAPTRA_CHECK_LAUNCH();
+    {
+        hipError_t e = hipMemcpyAsync(a.counters + 1, &w_top, sizeof(int), hipMemcpyHostToDevice, st);
+        if (e != hipSuccess) return hip_fail(e);
+        if ((e = hipStreamSynchronize(st)) != hipSuccess) return hip_fail(e);     // w_top is on this stack
+    }
     int rounds = 0;
     long long evaluated = 0;
     for (;;) {
@@ -149,6 +168,8 @@ int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *sc
         hipLaunchKernelGGL(k_search_pool, dim3(blocks_for(a.C, INT32_MAX)), dim3(kThreadsPerBlock), 0, st, a);
         ADAPTRA_CHECK_LAUNCH();
         // step 2: each pool entry under its own scenario, and the best entry per scenario
+        const int w_bound = w_top + 1 > a.M - 1 ? a.M - 1 : w_top + 1;
+        const adaptra_candidates_t pool{a.C, a.pool, w_bound};
         int rc = adaptra_detail::best(&bp, &pool, scens, pl.n_moves + 1, best_idx, best_mk, nullptr, nullptr,
                                       base + pl.off_best_ws, pl.best_ws_bytes, stream);
         if (rc) return rc;
@@ -156,11 +177,12 @@ int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *sc
         // step 3: move
         hipLaunchKernelGGL(k_search_advance, dim3(kblocks), dim3(kThreadsPerBlock), 0, st, a);
         ADAPTRA_CHECK_LAUNCH();
-        int moved = 0;
-        hipError_t e = hipMemcpyAsync(&moved, a.counters, sizeof(int), hipMemcpyDeviceToHost, st);
+        int back[2] = {0, 0};
+        hipError_t e = hipMemcpyAsync(back, a.counters, sizeof(back), hipMemcpyDeviceToHost, st);
         if (e != hipSuccess) return hip_fail(e);
         if ((e = hipStreamSynchronize(st)) != hipSuccess) return hip_fail(e);
-        if (moved == 0 || rounds >= max_iters) break;
+        w_top = back[1];
+        if (back[0] == 0 || rounds >= max_iters) break;
     }
     if (out_rounds) *out_rounds = rounds;
     if (out_evaluated) *out_evaluated = evaluated;
