@@ -275,6 +275,20 @@ def main():
                        "makespan_vs_exhaustive_over_candidates_max": float(ratio.max()) if ratio.numel() else None}
         del sws
 
+    # the online decision (one measured scenario, all candidates): latency of adaptra_best alone
+    online_info = None
+    if not args.no_sens and S > 1:
+        one = binding.Problem(M, prob.tensors[0], prob.tensors[1], prob.tensors[2],
+                              prob.tensors[3][:, :1].contiguous(), prob.tensors[4][:, :1].contiguous(),
+                              prob.tensors[5], w_bound=w_bound)
+        oidx = torch.empty(1, dtype=torch.int32, device=dev)
+        omk = torch.empty(1, dtype=torch.int32, device=dev)
+        binding.adaptra_best(one, oidx, omk, None, None, want_bubble=False, workspace=ws)
+        t_one = timed(lambda: binding.adaptra_best(one, oidx, omk, None, None, want_bubble=False, workspace=ws), n=20)
+        online_info = {"candidates": C, "scenarios": 1, "best_ms": t_one * 1e3,
+                       "kernel": "candidate lanes (fewer than 32 scenarios)"}
+        del one
+
     flags = fl[0].cpu().numpy()                    # the flag depends on the candidate only
     n_live = int(((flags & 2) == 0).sum())
     n_feasible = int((flags == 1).sum())
@@ -319,6 +333,8 @@ def main():
         out["sensitivity"] = sens_info
     if search_info:
         out["search"] = search_info
+    if online_info:
+        out["online_decision"] = online_info
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
