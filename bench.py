@@ -2,10 +2,12 @@
 """Benchmark of the batched pipeline-schedule evaluation on one MI355X.
 
 A step is one pass of the whole hot path over one batch of synthetic input that is already
-resident in HBM: adaptra_eval (feasibility pre-pass, max-plus recurrence for every pair,
-makespan + per-stage bubbles + flag byte) followed by adaptra_best (pre-pass, recurrence over
-the feasible pairs, per-scenario argmin, winner's bubbles, histogram if the configuration
-asks for one).  `value` counts each (candidate, scenario) pair once per step.
+resident in HBM: adaptra_eval_best -- feasibility pre-pass, max-plus recurrence for every
+pair, makespan + per-stage bubbles + flag byte, per-scenario argmin over the feasible
+candidates, winner's bubbles, histogram if the configuration asks for one.  Every pair is
+resolved once; `--two-calls` times adaptra_eval followed by adaptra_best instead (the same
+outputs, the feasible pairs resolved a second time by the search).  `value` counts each
+(candidate, scenario) pair once per step.
 
 Prints ONE JSON line (see the fields below).  `roofline` prices the dominant kernel (the
 recurrence kernel of adaptra_eval) against the integer-VALU peak: 3 int32 operations per
@@ -103,6 +105,9 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload index 0..4 (default 3: S=32, M=128, 2^26 pairs)")
     ap.add_argument("--no-bubble", action="store_true", help="skip adaptra_eval's [S][K][C] bubble output")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="step = adaptra_eval then adaptra_best (feasible pairs resolved twice) instead of "
+                         "adaptra_eval_best")
     ap.add_argument("--no-zb", action="store_true", help="skip the ZeroBubble (F/B/W) side measurement")
     ap.add_argument("--no-sens", action="store_true",
                     help="skip the per-scenario stage time and link sensitivity side measurements")
@@ -141,8 +146,12 @@ def main():
     hist = torch.empty((S, wl.hist_bins), dtype=torch.int64, device=dev) if wl.hist_bins else None
 
     def step():
-        binding.adaptra_eval(prob, mk, bub, fl, want_bubble=bub is not None, workspace=ws)
-        binding.adaptra_best(prob, bidx, bmk, bbub, hist, workspace=ws)
+        if args.two_calls:
+            binding.adaptra_eval(prob, mk, bub, fl, want_bubble=bub is not None, workspace=ws)
+            binding.adaptra_best(prob, bidx, bmk, bbub, hist, workspace=ws)
+        else:       # the same outputs, every pair resolved once
+            binding.adaptra_eval_best(prob, mk, bub, fl, bidx, bmk, bbub, hist, want_bubble=bub is not None,
+                                      workspace=ws)
 
     if args.copy_calibration:
         src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
@@ -162,9 +171,13 @@ def main():
     t0 = time.perf_counter()
     for i in range(args.steps):
         binding.adaptra_set_resolve_events(pairs[i][0], pairs[i][1])
-        binding.adaptra_eval(prob, mk, bub, fl, want_bubble=bub is not None, workspace=ws)
-        binding.adaptra_set_resolve_events(None, None)
-        binding.adaptra_best(prob, bidx, bmk, bbub, hist, workspace=ws)
+        if args.two_calls:
+            binding.adaptra_eval(prob, mk, bub, fl, want_bubble=bub is not None, workspace=ws)
+            binding.adaptra_set_resolve_events(None, None)
+            binding.adaptra_best(prob, bidx, bmk, bbub, hist, workspace=ws)
+        else:
+            step()
+            binding.adaptra_set_resolve_events(None, None)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     kernel_ms = [evs.elapsed_ms(a, b) for a, b in pairs]
@@ -310,11 +323,14 @@ def main():
         "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {wl.name}: S={S}, M={M}, {C} candidates x {K} scenarios "
-                               f"= {C * K} pairs; step = adaptra_eval (makespan"
-                               f"{'' if args.no_bubble else ' + bubbles'} + flags) + adaptra_best",
+                               f"= {C * K} pairs; step = "
+                               + (f"adaptra_eval (makespan{'' if args.no_bubble else ' + bubbles'} + flags) + adaptra_best"
+                                  if args.two_calls else
+                                  f"adaptra_eval_best (makespan{'' if args.no_bubble else ' + bubbles'} + flags + "
+                                  f"per-scenario argmin + histogram, every pair resolved once)"),
                    "pairs": C * K, "not_deadlocked_candidates": n_live, "feasible_candidates": n_feasible,
                    "w_bound": w_bound, "kernel_mode": args.kernel_mode, "inputs_sha256": wl.sha256()},
-        "resolved_ops_per_s": (ops_eval + ops_best) / (dt / args.steps),
+        "resolved_ops_per_s": (ops_eval + (ops_best if args.two_calls else 0)) / (dt / args.steps),
         "eval": {"ms": t_eval * 1e3, "evaluations_per_s": C * K / t_eval, "resolved_ops_per_s": ops_eval / t_eval},
         "best": {"ms": t_best * 1e3, "evaluations_per_s": C * K / t_best, "resolved_ops_per_s": ops_best / t_best},
         "roofline": {"bound": "alu", "kernel": f"k_resolve_scen_lanes<{hot_S}, false, false>",

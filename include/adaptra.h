@@ -42,8 +42,8 @@
  *     The library allocates no device memory and keeps no state between calls
  *     except the option set by adaptra_set_kernel_mode.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     adaptra_eval, adaptra_best, adaptra_seed, adaptra_sensitivity and
- *     adaptra_zb_eval only enqueue kernels on it and return; they do not
+ *     adaptra_eval, adaptra_best, adaptra_eval_best, adaptra_seed,
+ *     adaptra_sensitivity and adaptra_zb_eval only enqueue kernels on it and return; they do not
  *     synchronise, allocate or record memset nodes, so a caller may capture them
  *     into a HIP graph (after one eager call, which sets the kernels' shared-memory
  *     limits).  Outputs are valid once the stream has drained.
@@ -151,6 +151,18 @@ int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *can
                  int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
                  uint64_t *out_hist,
                  void *workspace, size_t workspace_bytes, void *stream);
+
+/* adaptra_eval and adaptra_best in one call, every pair resolved once: the search and the
+ * histogram read the makespans the evaluation has just produced instead of running the
+ * recurrence again for the feasible candidates.  Arguments, layouts and results are those of
+ * the two calls (out_bubble, out_best_bubble and out_hist optional as there); the workspace
+ * is adaptra_workspace_bytes.  Asynchronous on `stream`. */
+int adaptra_eval_best(const adaptra_params_t *params, const adaptra_candidates_t *cands,
+                      const adaptra_scenarios_t *scens,
+                      int32_t *out_makespan, int32_t *out_bubble, uint8_t *out_feasible,
+                      int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
+                      uint64_t *out_hist,
+                      void *workspace, size_t workspace_bytes, void *stream);
 
 /* The paper's analytic planning (Section 4.2), one result per scenario, as a cheap seed and
  * as the reference point for the exhaustive search of adaptra_best.  Every output is

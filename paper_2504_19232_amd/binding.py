@@ -22,7 +22,7 @@ FLAG_FEASIBLE, FLAG_DEADLOCK, FLAG_MEMCAP = 1, 2, 4
 INT32_MAX = 2 ** 31 - 1
 
 EXPORTS = ("adaptra_workspace_bytes", "adaptra_best_workspace_bytes", "adaptra_search_workspace_bytes", "adaptra_search",
-           "adaptra_check_inputs", "adaptra_eval", "adaptra_best", "adaptra_seed",
+           "adaptra_check_inputs", "adaptra_eval", "adaptra_best", "adaptra_eval_best", "adaptra_seed",
            "adaptra_sensitivity_workspace_bytes", "adaptra_sensitivity",
            "adaptra_zb_workspace_bytes", "adaptra_zb_eval",
            "adaptra_set_kernel_mode", "adaptra_set_resolve_events", "adaptra_valu_probe", "adaptra_last_hip_error",
@@ -81,6 +81,8 @@ def load() -> ctypes.CDLL:
         lib.adaptra_eval.argtypes = [P, C, Sc, vp, vp, vp, vp, sz, vp]
         lib.adaptra_best.restype = ctypes.c_int
         lib.adaptra_best.argtypes = [P, C, Sc, vp, vp, vp, vp, vp, sz, vp]
+        lib.adaptra_eval_best.restype = ctypes.c_int
+        lib.adaptra_eval_best.argtypes = [P, C, Sc, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.adaptra_seed.restype = ctypes.c_int
         lib.adaptra_seed.argtypes = [P, Sc, ctypes.c_int32, vp, vp, vp, vp, vp]
         lib.adaptra_sensitivity_workspace_bytes.restype = sz
@@ -224,6 +226,37 @@ def adaptra_best(prob: Problem, out_best_idx=None, out_best_makespan=None, out_b
                              _ptr(out_hist), ws.data_ptr(), ws.numel(), _stream(stream))
     _raise(rc, "adaptra_best")
     return out_best_idx, out_best_makespan, out_best_bubble, out_hist
+
+
+def adaptra_eval_best(prob: Problem, out_makespan=None, out_bubble=None, out_feasible=None, out_best_idx=None,
+                      out_best_makespan=None, out_best_bubble=None, out_hist=None, *, want_bubble: bool = True,
+                      workspace=None, stream=None):
+    """Enqueue evaluation and search in one pass; returns the outputs of adaptra_eval followed by
+    those of adaptra_best: (makespan, bubble | None, feasible, best_idx, best_makespan,
+    best_bubble | None, hist | None)."""
+    import torch
+    dev = prob.device
+    if out_makespan is None:
+        out_makespan = torch.empty((prob.K, prob.C), dtype=torch.int32, device=dev)
+    if out_feasible is None:
+        out_feasible = torch.empty((prob.K, prob.C), dtype=torch.uint8, device=dev)
+    if out_bubble is None and want_bubble:
+        out_bubble = torch.empty((prob.S, prob.K, prob.C), dtype=torch.int32, device=dev)
+    if out_best_idx is None:
+        out_best_idx = torch.empty(prob.K, dtype=torch.int32, device=dev)
+    if out_best_makespan is None:
+        out_best_makespan = torch.empty(prob.K, dtype=torch.int32, device=dev)
+    if out_best_bubble is None and want_bubble:
+        out_best_bubble = torch.empty((prob.K, prob.S), dtype=torch.int32, device=dev)
+    if out_hist is None and prob.hist_bins > 0:
+        out_hist = torch.empty((prob.S, prob.hist_bins), dtype=torch.int64, device=dev)
+    ws = alloc_workspace(prob) if workspace is None else workspace
+    rc = load().adaptra_eval_best(ctypes.byref(prob.params), ctypes.byref(prob.cands), ctypes.byref(prob.scens),
+                                  out_makespan.data_ptr(), _ptr(out_bubble), out_feasible.data_ptr(),
+                                  out_best_idx.data_ptr(), out_best_makespan.data_ptr(), _ptr(out_best_bubble),
+                                  _ptr(out_hist), ws.data_ptr(), ws.numel(), _stream(stream))
+    _raise(rc, "adaptra_eval_best")
+    return out_makespan, out_bubble, out_feasible, out_best_idx, out_best_makespan, out_best_bubble, out_hist
 
 
 def adaptra_seed(prob: Problem, x_max: int = 1, w_current=None, *, want_init: bool = True,

@@ -19,6 +19,7 @@
 //                        sentinels for deadlocked pairs (one coalesced streaming pass)
 //   k_sens_epilogue      adaptra_sensitivity: differences against the base scenarios
 //   k_best_init / k_best_finalize   search keys and histogram set-up / decoding
+//   k_best_from_eval     adaptra_eval_best: the search over the makespans the evaluation left
 //   k_check_inputs       range scan for adaptra_check_inputs
 //   k_seed               the paper's analytic planning (Algorithm 1, Algorithm 2, Eq. (1))
 //
@@ -299,6 +300,49 @@ __global__ __launch_bounds__(kBlock) void k_best_init(KArgs a) {
     for (long long i = (long long)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) {
         if (i < a.K) a.keys[i] = kNoKey;
         else a.hist[i - a.K] = 0ull;
+    }
+}
+
+// The search over makespans that adaptra_eval's resolve kernels have just left in mk_t[C][K]
+// (adaptra_eval_best): nothing is resolved twice.  One wavefront = 64 scenarios (lanes) x a
+// run of 64 candidates; only the rows of feasible candidates are read (coalesced along the
+// scenario axis).  Keys and histogram as in the resolve kernels' search.
+__global__ __launch_bounds__(kBlock) void k_best_from_eval(KArgs a) {
+    extern __shared__ unsigned hist_lds_scan[];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const bool lds_hist = a.hist && a.hist_in_lds;
+    if (lds_hist) {
+        for (int i = threadIdx.x; i < a.S * a.hist_bins; i += kBlock) hist_lds_scan[i] = 0;
+        __syncthreads();
+    }
+    const long long ktiles = (a.K + 63) / 64;
+    const long long task = (long long)blockIdx.x * kWavesPerBlock + wv;
+    const long long k = (task % ktiles) * 64 + lane;
+    const long long c0 = (task / ktiles) * 64;
+    const bool kvalid = k < a.K;
+    unsigned long long key = kNoKey;
+    for (long long c = c0; c < c0 + 64 && c < a.C; ++c) {
+        if (uni(a.cand_flag[c]) != ADAPTRA_FLAG_FEASIBLE || !kvalid) continue;
+        const int mk = a.mk_t[c * a.K + k];
+        const unsigned long long cand = ((unsigned long long)(unsigned)mk << 32) | (unsigned)c;
+        key = cand < key ? cand : key;
+        if (a.hist) {
+            for (int s = 0; s < a.S; ++s) {
+                const int tau_s = a.tfs ? a.tfs[(long long)s * a.K + k] + a.tbs[(long long)s * a.K + k] : a.t_f[s] + a.t_b[s];
+                int b = (mk - a.M * tau_s) >> a.hist_shift;
+                b = b > a.hist_bins - 1 ? a.hist_bins - 1 : b;
+                if (lds_hist) atomicAdd(&hist_lds_scan[s * a.hist_bins + b], 1u);
+                else atomicAdd(&a.hist[s * a.hist_bins + b], 1ull);
+            }
+        }
+    }
+    if (key != kNoKey) atomicMin(&a.keys[k], key);
+    if (lds_hist) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < a.S * a.hist_bins; i += kBlock) {
+            const unsigned cnt = hist_lds_scan[i];
+            if (cnt) atomicAdd(&a.hist[i], (unsigned long long)cnt);
+        }
     }
 }
 
@@ -1268,6 +1312,58 @@ int adaptra_eval(const adaptra_params_t *params, const adaptra_candidates_t *can
     const long long tiles = ((a.C + 63) / 64) * ((a.K + 63) / 64);
     if (tiles > INT32_MAX) return ADAPTRA_EINVAL;
     hipLaunchKernelGGL(k_eval_epilogue, dim3((unsigned)tiles), dim3(kBlock), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    return ADAPTRA_OK;
+}
+
+int adaptra_eval_best(const adaptra_params_t *params, const adaptra_candidates_t *cands,
+                      const adaptra_scenarios_t *scens,
+                      int32_t *out_makespan, int32_t *out_bubble, uint8_t *out_feasible,
+                      int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
+                      uint64_t *out_hist,
+                      void *workspace, size_t workspace_bytes, void *stream) {
+    Workspace ws;
+    int rc = validate_common(params, cands, scens, workspace, workspace_bytes, &ws);
+    if (rc) return rc;
+    if (!out_makespan || !out_feasible || !out_best_idx || !out_best_makespan) return ADAPTRA_EINVAL;
+    if (params->hist_bins < 0 || params->hist_bins > 65536) return ADAPTRA_EINVAL;
+    if (params->hist_bins > 0 && (!out_hist || params->hist_shift < 0 || params->hist_shift > 30))
+        return ADAPTRA_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    KArgs a;
+    fill_args(&a, params, cands, scens, workspace, ws);
+    a.out_makespan = out_makespan;
+    a.out_bubble = out_bubble;
+    a.out_feasible = out_feasible;
+    a.best_idx = out_best_idx;
+    a.best_makespan = out_best_makespan;
+    a.best_bubble = out_best_bubble;
+    a.hist = params->hist_bins > 0 ? (unsigned long long *)out_hist : nullptr;
+    a.hist_bins = params->hist_bins;
+    a.hist_shift = params->hist_shift;
+    a.hist_in_lds = (size_t)a.S * a.hist_bins * 4 <= (size_t)kMaxLdsHistBytes;
+    hipLaunchKernelGGL(k_zero_status, dim3(1), dim3(64), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_prepass, dim3(grid_for(a.C, INT32_MAX)), dim3(kBlock), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_best_init, dim3(grid_for(a.K + (long long)a.S * a.hist_bins, 4096)), dim3(kBlock), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    // the evaluation: the resolve kernels must not see the search's outputs (they would search too)
+    KArgs e = a;
+    e.hist = nullptr;
+    rc = launch_resolve<false>(e, ws, cands->w_bound, st);
+    if (rc) return rc;
+    const long long tiles = ((a.C + 63) / 64) * ((a.K + 63) / 64);
+    if (tiles > INT32_MAX) return ADAPTRA_EINVAL;
+    hipLaunchKernelGGL(k_eval_epilogue, dim3((unsigned)tiles), dim3(kBlock), 0, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    // the search, over the makespans just computed
+    const long long tasks = ((a.K + 63) / 64) * ((a.C + 63) / 64);
+    const size_t lds = a.hist && a.hist_in_lds ? (size_t)a.S * a.hist_bins * 4 : 0;
+    hipLaunchKernelGGL(k_best_from_eval, dim3((unsigned)((tasks + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(kBlock),
+                       lds, st, a);
+    ADAPTRA_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_best_finalize, dim3(grid_for(a.K, INT32_MAX)), dim3(kBlock), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
     return ADAPTRA_OK;
 }

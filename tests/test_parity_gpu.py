@@ -66,6 +66,19 @@ def check_full(binding, oracle, wl, modes=(0, 1, 2, 3)):
         assert np.array_equal(bbub, rbest["best_bubble"])
         if rhist is not None:
             assert np.array_equal(hist, rhist), f"histogram mismatch mode {mode}"
+        say(f"  {wl.name}: eval + best in one call, mode {mode}")
+        import torch
+        binding.adaptra_set_kernel_mode(mode)
+        out = binding.adaptra_eval_best(binding.Problem.from_workload(wl))
+        torch.cuda.synchronize()
+        binding.adaptra_set_kernel_mode(0)
+        mk, bub, fl, idx, bmk, bbub, hist = [None if t is None else t.cpu().numpy() for t in out]
+        assert np.array_equal(fl, ref["flag"]) and np.array_equal(mk, ref["makespan"])
+        assert np.array_equal(bub, ref["bubble"])
+        assert np.array_equal(idx, rbest["best_idx"]), f"fused best_idx mismatch mode {mode}"
+        assert np.array_equal(bmk, rbest["best_makespan"]) and np.array_equal(bbub, rbest["best_bubble"])
+        if rhist is not None:
+            assert np.array_equal(hist.astype(np.uint64), rhist), f"fused histogram mismatch mode {mode}"
 
 
 @pytest.mark.parametrize("index", [0, 1])
@@ -172,6 +185,17 @@ def _sampled_parity(lib, oracle, index, n_sample, full_scenarios):
             b = np.minimum(wl.hist_bins - 1, (mk[ok].astype(np.int64) - wl.M * tau[s]) >> wl.hist_shift)
             want[s] = np.bincount(b, minlength=wl.hist_bins).astype(np.uint64)
         assert np.array_equal(hist, want)
+    # (c') the one-call form gives the same evaluation and the same search
+    say("  adaptra_eval_best vs the two calls")
+    import torch
+    out = lib.adaptra_eval_best(lib.Problem.from_workload(wl, w_bound=int(np.clip(wl.w, 0, wl.M - 1).max())),
+                                want_bubble=False)
+    torch.cuda.synchronize()
+    assert np.array_equal(out[0].cpu().numpy(), mk) and np.array_equal(out[2].cpu().numpy(), fl)
+    assert np.array_equal(out[3].cpu().numpy(), idx) and np.array_equal(out[4].cpu().numpy(), bmk)
+    if wl.hist_bins:
+        assert np.array_equal(out[6].cpu().numpy().astype(np.uint64), hist)
+    del out
     # (b) whole scenarios through the oracle, search included
     for k in full_scenarios:
         say(f"  oracle on all {wl.n_cand} candidates of scenario {k}")
