@@ -773,3 +773,16 @@ def test_many_small_random_problems(lib, oracle):
             assert np.array_equal(bbub, rbest["best_bubble"]), tag
             if rhist is not None:
                 assert np.array_equal(hist.astype(np.uint64), rhist), tag
+
+
+def test_readme_example_runs(lib):
+    import torch
+    from paper_2504_19232_amd import binding
+    wl = workloads.config(1)
+    prob = binding.Problem.from_workload(wl)
+    mk, bubble, flag, best_idx, best_mk, best_bubble, hist = binding.adaptra_eval_best(prob)
+    w_init, w_adapted, _ = binding.adaptra_seed(prob, x_max=8)
+    w, makespan, rounds, pairs = binding.adaptra_search(prob, w_init, neighbourhood=1)
+    torch.cuda.synchronize()
+    assert mk.shape == (wl.n_scen, wl.n_cand) and w.shape == (wl.S, wl.n_scen) and rounds >= 1
+    assert pairs == rounds * wl.n_scen * (wl.S * (wl.S + 1) + 1)
