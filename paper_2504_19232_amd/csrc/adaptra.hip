@@ -47,7 +47,7 @@ constexpr int kWavesPerBlock = ADAPTRA_WPB;
 constexpr int kBlock = 64 * kWavesPerBlock;
 constexpr int kClassDead = 255;           // deadlocked: never resolved
 constexpr int kClassDeep = 254;           // warm-up depth beyond the LDS ring: general kernel
-constexpr int kNumRingClasses = 8;        // ring of 8 * (class + 1) slots
+constexpr int kNumRingClasses = 16;       // ring of 8 * (class + 1) slots: up to 128 slots = 32 KiB per wavefront
 constexpr int kMaxLdsHistBytes = 16384;
 #ifndef ADAPTRA_PD
 #define ADAPTRA_PD 4
@@ -79,7 +79,7 @@ struct KArgs {
     long long n_chunks;
     int chunk;                             // candidates per wavefront of the hot kernel (1..kChunk)
     int n_ktiles;
-    int *status;                           // [0..3] input check, [16..24] candidates per ring class
+    int *status;                           // [0..3] input check, [16..32] candidates per ring class
     int *mk_t;                             // eval: makespan, candidate-major [C][K]
     int *tpad;                             // t_f at [0..63], t_b at [64..127], zero beyond stage S-1
 };
@@ -885,7 +885,7 @@ __global__ __launch_bounds__(kBlock) void k_check_inputs(KArgs a) {
 }
 
 __global__ void k_zero_status(KArgs a) {
-    if (threadIdx.x < 32) a.status[threadIdx.x] = 0;
+    a.status[threadIdx.x] = 0;      // launched with 64 threads: all of status
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1106,25 +1106,35 @@ void fill_args(KArgs *a, const adaptra_params_t *p, const adaptra_candidates_t *
     a->n_chunks = (cd->n + a->chunk - 1) / a->chunk;
 }
 
+// The ring classes a launch covers.  With a bound on w one launch takes every class up to the
+// bound's, with exactly the ring the bound needs; without, five launches with rings of 8, 16,
+// 32, 64 and 128 slots share the classes (empty ones exit at once).
+struct ClassRange {
+    int lo, hi;
+};
+int ring_launches(int w_bound, int M, ClassRange out[5]) {
+    if (w_bound >= 0) {
+        const int wb = w_bound > M - 1 ? M - 1 : w_bound;
+        int last = (wb + 8) / 8 - 1;
+        if (last > kNumRingClasses - 1) last = kNumRingClasses - 1;
+        out[0] = {0, last};
+        return 1;
+    }
+    out[0] = {0, 0}; out[1] = {1, 1}; out[2] = {2, 3}; out[3] = {4, 7}; out[4] = {8, kNumRingClasses - 1};
+    return 5;
+}
+
 template <int S, bool BEST, bool VT>
 int launch_fast_vt(KArgs a, int w_bound, hipStream_t st) {
     const long long tasks = a.n_chunks * a.n_ktiles;
     const long long blocks = (tasks + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > INT32_MAX) return ADAPTRA_EINVAL;
-    // With a bound on w one launch covers every ring class up to the bound's; without,
-    // one launch per class, each with the smallest ring that fits its candidates.
-    int first = 0, last = kNumRingClasses - 1;
-    bool single = false;
-    if (w_bound >= 0) {
-        int wb = w_bound > a.M - 1 ? a.M - 1 : w_bound;
-        last = (wb + 8) / 8 - 1;
-        if (last > kNumRingClasses - 1) last = kNumRingClasses - 1;
-        single = true;
-    }
-    for (int cls = single ? last : first; cls <= last; ++cls) {
-        a.cls_lo = single ? 0 : cls;
-        a.cls_hi = cls;
-        a.ring_slots = 8 * (cls + 1);
+    ClassRange ranges[5];
+    const int n_launches = ring_launches(w_bound, a.M, ranges);
+    for (int i = 0; i < n_launches; ++i) {
+        a.cls_lo = ranges[i].lo;
+        a.cls_hi = ranges[i].hi;
+        a.ring_slots = 8 * (a.cls_hi + 1);
         size_t lds = (size_t)kWavesPerBlock * a.ring_slots * 256;
         if (BEST && a.hist && a.hist_in_lds) lds += (size_t)a.S * a.hist_bins * 4;
         if (lds > 48 * 1024) {      // above the default dynamic-LDS limit: raise it for this kernel
@@ -1160,18 +1170,12 @@ int launch_cand_lanes_one(KArgs a, int w_bound, hipStream_t st) {
     const long long ntiles = (a.pair_div ? 1 : a.K) * ((a.C + 63) / 64);
     long long blocks = (ntiles + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 256 * 32) blocks = 256 * 32;            // the tiles are walked in a loop
-    int first = 0, last = kNumRingClasses - 1;
-    bool single = false;
-    if (w_bound >= 0) {
-        int wb = w_bound > a.M - 1 ? a.M - 1 : w_bound;
-        last = (wb + 8) / 8 - 1;
-        if (last > kNumRingClasses - 1) last = kNumRingClasses - 1;
-        single = true;
-    }
-    for (int cls = single ? last : first; cls <= last; ++cls) {
-        a.cls_lo = single ? 0 : cls;
-        a.cls_hi = cls;
-        a.ring_slots = 8 * (cls + 1);
+    ClassRange ranges[5];
+    const int n_launches = ring_launches(w_bound, a.M, ranges);
+    for (int i = 0; i < n_launches; ++i) {
+        a.cls_lo = ranges[i].lo;
+        a.cls_hi = ranges[i].hi;
+        a.ring_slots = 8 * (a.cls_hi + 1);
         const size_t lds = (size_t)kWavesPerBlock * a.ring_slots * 256;
         if (lds > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute((const void *)k_resolve_cand_lanes<S, BEST, VT>,

@@ -98,7 +98,7 @@ RAGGED = [
     (6, 4, 1, 64, 64, {}),                      # a single micro-batch
     (7, 5, 12, 130, 40, dict(cap=False)),
     (8, 8, 32, 1000, 64, dict(d_max=7, hist_bins=64, hist_shift=10)),
-    (9, 8, 100, 300, 100, dict(w_extra=60)),    # warm-up deeper than the LDS ring
+    (9, 8, 100, 300, 100, dict(w_extra=60)),    # deep warm-ups: the largest ring classes
     (10, 8, 9, 200, 64, dict(w_extra=20)),      # w above M-1 everywhere: clamped
     (11, 16, 64, 500, 70, dict(d_max=4)),
     (12, 16, 20, 77, 128, dict(w_extra=3, hist_bins=300, hist_shift=7)),   # histogram too wide for LDS
@@ -121,6 +121,8 @@ RAGGED = [
     (28, 24, 64, 100, 65, dict(d_max=3, c_hi=20000)),
     (29, 31, 40, 64, 64, dict(d_max=3, hist_bins=200, hist_shift=8)),
     (30, 33, 40, 20, 10, dict(d_max=2)),        # beyond the hot kernel: general kernel
+    (31, 4, 400, 40, 64, dict(w_extra=300)),    # warm-ups deeper than the 128-slot LDS ring: general kernel
+    (32, 8, 160, 30, 3, dict(w_extra=120)),     # the same with few scenarios
 ]
 
 
@@ -462,7 +464,7 @@ STAGE_TIME_CASES = [
     (62, 3, 7, 90, 11, {}),                                    # general kernel only
     (63, 4, 16, 130, 129, dict(hist_bins=32, hist_shift=8)),
     (64, 8, 32, 300, 100, dict(d_max=6, hist_bins=64, hist_shift=10)),
-    (65, 8, 90, 100, 64, dict(w_extra=50)),                    # deeper than the LDS ring
+    (65, 8, 90, 100, 64, dict(w_extra=50)),                    # deep warm-ups
     (66, 16, 48, 200, 65, dict(d_max=4)),
     (67, 32, 64, 80, 70, dict(d_max=4, hist_bins=16, hist_shift=12)),
     (68, 64, 80, 30, 5, dict(d_max=2)),
