@@ -91,7 +91,7 @@ typedef struct adaptra_candidates {
     int64_t n;               /* 1..2^31-1 */
     const int32_t *w;        /* DEVICE [S][n] */
     int32_t w_bound;         /* optional promise: no w exceeds this value; -1 = unknown.
-                              * It only sizes the on-chip ring of the register/LDS kernel
+                              * It only sizes the LDS ring of the on-chip kernels
                               * (one launch instead of one per ring depth).  Candidates
                               * that break the promise are still evaluated correctly,
                               * by the general kernel. */

@@ -379,7 +379,7 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
     int *last = a.scratch + tid;
     int *wl = a.scratch + (long long)S * NT + tid;
     int *fwd = a.scratch + 2ll * S * NT + tid;
-    if (!a.general_all) {      // only the candidates the register/LDS kernel left over: often none
+    if (!a.general_all) {      // only the candidates the on-chip kernels left over: often none
         int mine = 0;
         for (int cls = a.cls_hi + 1; cls <= kNumRingClasses; ++cls) mine += a.status[16 + cls];
         if (mine == 0) return;
@@ -398,7 +398,7 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
             const int flag = a.cand_flag[c];
             const int cls = a.cand_class[c];
             run = BEST ? (flag == ADAPTRA_FLAG_FEASIBLE) : !(flag & ADAPTRA_FLAG_DEADLOCK);
-            if (!a.general_all && cls <= a.cls_hi) run = false;   // the register/LDS kernel's share
+            if (!a.general_all && cls <= a.cls_hi) run = false;   // the on-chip kernels' share
         }
         unsigned long long key = kNoKey;
         if (run) {
@@ -1125,7 +1125,7 @@ int ring_launches(int w_bound, int M, ClassRange out[5]) {
 }
 
 template <int S, bool BEST, bool VT>
-int launch_fast_vt(KArgs a, int w_bound, hipStream_t st) {
+int launch_scen_lanes_one(KArgs a, int w_bound, hipStream_t st) {
     const long long tasks = a.n_chunks * a.n_ktiles;
     const long long blocks = (tasks + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > INT32_MAX) return ADAPTRA_EINVAL;
@@ -1149,18 +1149,18 @@ int launch_fast_vt(KArgs a, int w_bound, hipStream_t st) {
 }
 
 template <int S, bool BEST>
-int launch_fast_one(const KArgs &a, int w_bound, hipStream_t st) {
-    return a.tfs ? launch_fast_vt<S, BEST, true>(a, w_bound, st) : launch_fast_vt<S, BEST, false>(a, w_bound, st);
+int launch_scen_lanes_sized(const KArgs &a, int w_bound, hipStream_t st) {
+    return a.tfs ? launch_scen_lanes_one<S, BEST, true>(a, w_bound, st) : launch_scen_lanes_one<S, BEST, false>(a, w_bound, st);
 }
 
 template <bool BEST>
-int launch_fast(const KArgs &a, int w_bound, hipStream_t st) {
+int launch_scen_lanes(const KArgs &a, int w_bound, hipStream_t st) {
     switch (hot_kernel_stages(a.S)) {
-        case 2: return launch_fast_one<2, BEST>(a, w_bound, st);
-        case 4: return launch_fast_one<4, BEST>(a, w_bound, st);
-        case 8: return launch_fast_one<8, BEST>(a, w_bound, st);
-        case 16: return launch_fast_one<16, BEST>(a, w_bound, st);
-        case 32: return launch_fast_one<32, BEST>(a, w_bound, st);
+        case 2: return launch_scen_lanes_sized<2, BEST>(a, w_bound, st);
+        case 4: return launch_scen_lanes_sized<4, BEST>(a, w_bound, st);
+        case 8: return launch_scen_lanes_sized<8, BEST>(a, w_bound, st);
+        case 16: return launch_scen_lanes_sized<16, BEST>(a, w_bound, st);
+        case 32: return launch_scen_lanes_sized<32, BEST>(a, w_bound, st);
         default: return ADAPTRA_EINVAL;
     }
 }
@@ -1221,7 +1221,7 @@ int record_event(hipEvent_t ev, hipStream_t st) {
     return e == hipSuccess ? ADAPTRA_OK : hip_fail(e);
 }
 
-// The measurement events bracket the kernel that carries the load: the register/LDS
+// The measurement events bracket the kernel that carries the load: the on-chip
 // kernel when it is in use, else the general kernel.
 template <bool BEST>
 int launch_resolve(KArgs a, const Workspace &ws, int w_bound, hipStream_t st) {
@@ -1237,7 +1237,7 @@ int launch_resolve(KArgs a, const Workspace &ws, int w_bound, hipStream_t st) {
         }
         const int general_from = a.cls_hi;               // classes above it go to the general kernel
         if ((rc = record_event(g_ev_before, st))) return rc;
-        if ((rc = hot ? launch_fast<BEST>(a, w_bound, st) : launch_cand_lanes<BEST>(a, w_bound, st))) return rc;
+        if ((rc = hot ? launch_scen_lanes<BEST>(a, w_bound, st) : launch_cand_lanes<BEST>(a, w_bound, st))) return rc;
         if ((rc = record_event(g_ev_after, st))) return rc;
         a.cls_hi = general_from;
         return launch_general<BEST>(a, ws, false, st);   // too deep for the ring, or beyond w_bound

@@ -109,7 +109,7 @@ RAGGED = [
     (17, 8, 64, 17, 1, dict()),                 # a single scenario
     (18, 8, 200, 64, 64, dict(w_extra=40)),     # ring classes 5-6
     (19, 4, 32768, 6, 3, dict(d_max=2)),        # the largest M: general kernel (K = 3)
-    (20, 4, 32768, 5, 64, dict(d_max=2, c_hi=300, t_hi=30)),   # the largest M: register/LDS kernel
+    (20, 4, 32768, 5, 64, dict(d_max=2, c_hi=300, t_hi=30)),   # the largest M: on-chip kernels
     (21, 64, 300, 70, 3, dict(d_max=1)),        # the largest S
     (22, 8, 16, 1, 1, dict()),                  # one pair
     (23, 16, 40, 1000, 192, dict(d_max=3, hist_bins=5, hist_shift=11)),   # three full scenario tiles
