@@ -70,6 +70,19 @@ def traffic_from_profile(S: int, config: int):
     return None
 
 
+def issued_from_profile(S: int, config: int):
+    """Issued int32 VALU lane-ops/s of the resolve kernel from the committed rocprofv3 counter
+    summary (SQ_INSTS_VALU x 64 / kernel time), in T lane-ops/s; None without a summary."""
+    path = os.path.join(ROOT, "profiles", f"resolve_scen_lanes_S{S}_config{config}.txt")
+    try:
+        for line in open(path):
+            if "derived: issued int32 VALU lane-ops/s" in line:
+                return float(line.split("=")[1].split("T")[0])
+    except (OSError, ValueError):
+        pass
+    return None
+
+
 def cpu_baseline(wl, target_seconds: float = 16.0) -> dict:
     """The oracle as it stands, on the host cores, on a seeded sample of this workload's pairs:
     all threads for about `target_seconds`, then one thread on a sixteenth of that sample."""
@@ -353,6 +366,7 @@ def main():
                      "achieved": achieved / 1e12, "peak": INT32_VALU_PEAK / 1e12, "unit": "Tint32op/s",
                      "frac": achieved / INT32_VALU_PEAK, "traffic": traffic_from_profile(S, args.config),
                      "peak_measured": measured_peak / 1e12, "frac_of_measured": achieved / measured_peak,
+                     "issued_from_profile": issued_from_profile(S, args.config),
                      "kernel_ms": kernel_avg_ms, "resolved_ops_per_launch": ops_eval,
                      "algorithmic_ops_per_resolved_op": 3},
     }
