@@ -76,6 +76,7 @@ struct KArgs {
     int *scratch;
     int cls_lo, cls_hi, ring_slots, general_all;
     int pair_div;                          // > 0: candidate c is evaluated under scenario c / pair_div only
+    int direct_out;                        // hot kernel, eval: it writes the final outputs itself (see there)
     long long n_chunks;
     int chunk;                             // candidates per wavefront of the hot kernel (1..kChunk)
     int n_ktiles;
@@ -248,6 +249,14 @@ __global__ __launch_bounds__(kBlock) void k_eval_epilogue(KArgs a) {
     const long long c0 = ((long long)blockIdx.x % ctiles) * 64;
     const long long k0 = ((long long)blockIdx.x / ctiles) * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    if (a.direct_out) {
+        // The scenario-lanes kernel has written the outputs of every candidate of ring class
+        // <= cls_hi (and the sentinels of the deadlocked ones) itself: only tiles that hold a
+        // candidate left to the general kernel remain, and those are redone as a whole.
+        const long long c = c0 + tx;
+        const bool left = c < a.C && !(a.cand_flag[c] & ADAPTRA_FLAG_DEADLOCK) && a.cand_class[c] > a.cls_hi;
+        if (!__syncthreads_or(left)) return;
+    }
     if (threadIdx.x < a.S) tau[threadIdx.x] = a.t_f[threadIdx.x] + a.t_b[threadIdx.x];   // unless per scenario
     for (int i = ty; i < 64; i += kWavesPerBlock) {          // row = candidate, lanes = scenarios
         const long long c = c0 + i, k = k0 + tx;
@@ -679,6 +688,13 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? (VT ? 3 : ADAPTRA_WAVES32) : (S >
         const long long c_left = kargs()->C - c0;
         const int chunk = kargs()->chunk;
         const int c_end = (int)(c_left < chunk ? c_left : chunk);
+        // Direct output (evaluation, chunks of exactly 16 candidates, a single launch): the
+        // makespans of the chunk are kept per lane and written at its end, 16 consecutive
+        // candidates = 64 contiguous bytes per scenario and output plane, so that the separate
+        // streaming pass over all pairs is not needed and the writes hide under the VALU work.
+        int mk_chunk[kChunk];
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j) mk_chunk[j] = INT32_MAX;    // dead candidates keep the sentinel
         for (int ci = 0; ci < c_end; ++ci) {
             const long long c = c0 + ci;
             {
@@ -831,8 +847,41 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? (VT ? 3 : ADAPTRA_WAVES32) : (S >
                 // k_eval_epilogue transposes into out_makespan and adds bubbles and flags
                 kargs()->mk_t[c * K + k] = mk;
             }
+            if constexpr (!BEST) {
+#pragma unroll
+                for (int j = 0; j < kChunk; ++j)
+                    if (j == ci) mk_chunk[j] = mk;           // uniform ci: a select per register
+            }
         }
         if (BEST && kvalid && key != kNoKey) atomicMin(&kargs()->keys[k], key);
+        if constexpr (!BEST) {
+            if (kargs()->direct_out && kvalid) {
+                const long long C = kargs()->C, P = C * K;
+                const long long at = k * C + c0;                 // 16 candidates from here
+                int4 *const mko = (int4 *)(kargs()->out_makespan + at);
+#pragma unroll
+                for (int v = 0; v < kChunk / 4; ++v)
+                    mko[v] = make_int4(mk_chunk[4 * v], mk_chunk[4 * v + 1], mk_chunk[4 * v + 2], mk_chunk[4 * v + 3]);
+                *(uint4 *)(kargs()->out_feasible + at) = *(const uint4 *)(kargs()->cand_flag + c0);
+                if (kargs()->out_bubble) {
+                    const int M = kargs()->M;
+                    for (int s = 0; s < kargs()->S; ++s) {
+                        const int busy = M * (ADAPTRA_TF(s) + ADAPTRA_TB(s));
+                        int4 *const bo = (int4 *)(kargs()->out_bubble + (long long)s * P + at);
+#pragma unroll
+                        for (int v = 0; v < kChunk / 4; ++v) {
+                            int b4[4];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const int mkj = mk_chunk[4 * v + j];
+                                b4[j] = mkj == INT32_MAX ? INT32_MAX : mkj - busy;
+                            }
+                            bo[v] = make_int4(b4[0], b4[1], b4[2], b4[3]);
+                        }
+                    }
+                }
+            }
+        }
     }
     if (lds_hist) {
         __syncthreads();
@@ -1223,9 +1272,15 @@ int record_event(hipEvent_t ev, hipStream_t st) {
 
 // The measurement events bracket the kernel that carries the load: the on-chip
 // kernel when it is in use, else the general kernel.
+// direct (evaluation only, may be null): set to the highest ring class whose candidates got
+// their final outputs straight from the scenario-lanes kernel, or to -1 if the caller's
+// epilogue has to produce all of them.  The kernel does so when one launch covers its
+// candidates, every chunk holds exactly 16 of them and the output addresses allow 16-byte
+// stores; the epilogue is then needed only for tiles with candidates left to the general kernel.
 template <bool BEST>
-int launch_resolve(KArgs a, const Workspace &ws, int w_bound, hipStream_t st) {
+int launch_resolve(KArgs a, const Workspace &ws, int w_bound, hipStream_t st, int *direct = nullptr) {
     int rc;
+    if (direct) *direct = -1;
     const ResolveKernel which = choose_kernel(a.S, a.K, a.tfs != nullptr, a.pair_div != 0);
     if (which != kGeneralOnly) {
         const bool hot = which == kScenarioLanes;
@@ -1236,6 +1291,12 @@ int launch_resolve(KArgs a, const Workspace &ws, int w_bound, hipStream_t st) {
             if (hi < a.cls_hi) a.cls_hi = hi;
         }
         const int general_from = a.cls_hi;               // classes above it go to the general kernel
+        const auto aligned16 = [](const void *p) { return ((uintptr_t)p & 15) == 0; };
+        if (!BEST && direct && hot && w_bound >= 0 && a.chunk == kChunk && a.C % kChunk == 0 && a.Kin == a.K &&
+            aligned16(a.out_makespan) && aligned16(a.out_feasible) && aligned16(a.out_bubble)) {
+            a.direct_out = 1;
+            *direct = general_from;
+        }
         if ((rc = record_event(g_ev_before, st))) return rc;
         if ((rc = hot ? launch_scen_lanes<BEST>(a, w_bound, st) : launch_cand_lanes<BEST>(a, w_bound, st))) return rc;
         if ((rc = record_event(g_ev_after, st))) return rc;
@@ -1311,10 +1372,12 @@ int adaptra_eval(const adaptra_params_t *params, const adaptra_candidates_t *can
     ADAPTRA_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_prepass, dim3(grid_for(a.C, INT32_MAX)), dim3(kBlock), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
-    rc = launch_resolve<false>(a, ws, cands->w_bound, st);
+    int direct = -1;
+    rc = launch_resolve<false>(a, ws, cands->w_bound, st, &direct);
     if (rc) return rc;
     const long long tiles = ((a.C + 63) / 64) * ((a.K + 63) / 64);
     if (tiles > INT32_MAX) return ADAPTRA_EINVAL;
+    if (direct >= 0) { a.direct_out = 1; a.cls_hi = direct; }
     hipLaunchKernelGGL(k_eval_epilogue, dim3((unsigned)tiles), dim3(kBlock), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
     return ADAPTRA_OK;
@@ -1355,11 +1418,14 @@ int adaptra_eval_best(const adaptra_params_t *params, const adaptra_candidates_t
     // the evaluation: the resolve kernels must not see the search's outputs (they would search too)
     KArgs e = a;
     e.hist = nullptr;
-    rc = launch_resolve<false>(e, ws, cands->w_bound, st);
+    int direct = -1;
+    rc = launch_resolve<false>(e, ws, cands->w_bound, st, &direct);
     if (rc) return rc;
     const long long tiles = ((a.C + 63) / 64) * ((a.K + 63) / 64);
     if (tiles > INT32_MAX) return ADAPTRA_EINVAL;
-    hipLaunchKernelGGL(k_eval_epilogue, dim3((unsigned)tiles), dim3(kBlock), 0, st, a);
+    e = a;
+    if (direct >= 0) { e.direct_out = 1; e.cls_hi = direct; }
+    hipLaunchKernelGGL(k_eval_epilogue, dim3((unsigned)tiles), dim3(kBlock), 0, st, e);
     ADAPTRA_LAUNCH_CHECK();
     // the search, over the makespans just computed
     const long long tasks = ((a.K + 63) / 64) * ((a.C + 63) / 64);

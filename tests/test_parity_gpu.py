@@ -27,20 +27,20 @@ def lib():
     binding.adaptra_set_kernel_mode(0)
 
 
-def gpu_eval(binding, wl, mode=0, want_bubble=True):
+def gpu_eval(binding, wl, mode=0, want_bubble=True, w_bound=-1):
     import torch
     binding.adaptra_set_kernel_mode(mode)
-    prob = binding.Problem.from_workload(wl)
+    prob = binding.Problem.from_workload(wl, w_bound=w_bound)
     mk, bub, fl = binding.adaptra_eval(prob, want_bubble=want_bubble)
     torch.cuda.synchronize()
     binding.adaptra_set_kernel_mode(0)
     return mk.cpu().numpy(), None if bub is None else bub.cpu().numpy(), fl.cpu().numpy()
 
 
-def gpu_best(binding, wl, mode=0):
+def gpu_best(binding, wl, mode=0, w_bound=-1):
     import torch
     binding.adaptra_set_kernel_mode(mode)
-    prob = binding.Problem.from_workload(wl)
+    prob = binding.Problem.from_workload(wl, w_bound=w_bound)
     idx, mk, bub, hist = binding.adaptra_best(prob)
     torch.cuda.synchronize()
     binding.adaptra_set_kernel_mode(0)
@@ -156,8 +156,9 @@ def _sampled_parity(lib, oracle, index, n_sample, full_scenarios):
     search over all candidates; (c) adaptra_best must equal a host argmin over the GPU's own
     complete evaluation for every scenario."""
     wl = workloads.config(index)
+    w_bound = int(wl.w.max())                          # as bench.py passes it
     say(f"config {index}: {wl.name}: GPU eval of {wl.n_pairs} pairs")
-    mk, _, fl = gpu_eval(lib, wl, want_bubble=False)
+    mk, _, fl = gpu_eval(lib, wl, want_bubble=False, w_bound=w_bound)
     tau = (wl.t_f + wl.t_b).astype(np.int64)
     # (a) sampled pairs, with bubbles from a second, bubble-enabled pass over a sub-problem
     pc, ps = workloads.sample_pairs(900 + index, wl.n_cand, wl.n_scen, n_sample)
@@ -170,7 +171,7 @@ def _sampled_parity(lib, oracle, index, n_sample, full_scenarios):
                           ref["bubble"][:, live].astype(np.int64))
     # (c) search == argmin over the GPU's evaluation
     say("  GPU best vs host argmin over the GPU evaluation")
-    idx, bmk, bbub, hist = gpu_best(lib, wl)
+    idx, bmk, bbub, hist = gpu_best(lib, wl, w_bound=w_bound)
     masked = np.where(fl == 1, mk.astype(np.int64), np.int64(2) ** 40)
     want_idx = masked.argmin(axis=1).astype(np.int32)
     any_ok = (fl == 1).any(axis=1)
@@ -220,6 +221,40 @@ def test_config3_sampled_parity(lib, oracle):
 
 def test_config4_sampled_parity(lib, oracle):
     _sampled_parity(lib, oracle, 4, 1 << 14, (37,))
+
+
+@pytest.mark.parametrize("promise", ["kept", "broken"])
+def test_direct_output_of_the_hot_kernel(lib, oracle, promise):
+    """With a w_bound hint and chunks of 16 candidates the scenario-lanes kernel writes makespan,
+    flags and bubbles itself; the epilogue only redoes tiles that hold candidates left to the
+    general kernel.  A quarter of configuration 3 (16 384 candidates x 1024 scenarios, bubbles
+    on), once with a true bound and once with a bound some candidates exceed."""
+    wl = workloads.config(3)
+    wl.w = np.ascontiguousarray(wl.w[:, 8192:8192 + 16384])
+    w_max = int(wl.w.max())
+    w_bound = w_max if promise == "kept" else 31
+    if promise == "broken":
+        assert (np.clip(wl.w[0], 0, wl.M - 1) > 31).any()
+    say(f"direct output, promise {promise}: w_bound {w_bound}, largest w {w_max}")
+    mk, bub, fl = gpu_eval(lib, wl, want_bubble=True, w_bound=w_bound)
+    pc, ps = workloads.sample_pairs(78, wl.n_cand, wl.n_scen, 1 << 12)
+    if promise == "broken":                              # make sure candidates beyond the bound are sampled
+        deep = np.flatnonzero(np.clip(wl.w[0], 0, wl.M - 1) > 31)[:512]
+        pc = np.concatenate([pc, deep])
+        ps = np.concatenate([ps, np.arange(len(deep)) % wl.n_scen])
+    ref = oracle.eval_workload(wl, pair_cand=pc, pair_scen=ps)
+    assert np.array_equal(fl[ps, pc], ref["flag"])
+    assert np.array_equal(mk[ps, pc], ref["makespan"])
+    assert np.array_equal(bub[:, ps, pc], ref["bubble"])
+    # everything the oracle did not sample: flags depend on the candidate only, deadlocked pairs
+    # carry sentinels, live bubbles are makespan - M (t_f + t_b)
+    assert np.array_equal(fl, np.broadcast_to(fl[0], fl.shape))
+    dead = (fl[0] & 2) != 0
+    assert np.all(mk[:, dead] == INT32_MAX) and np.all(bub[:, :, dead] == INT32_MAX)
+    tau = (wl.t_f + wl.t_b).astype(np.int64)
+    live = ~dead
+    for s in range(0, wl.S, 5):
+        assert np.array_equal(bub[s][:, live].astype(np.int64), mk[:, live].astype(np.int64) - wl.M * tau[s])
 
 
 def test_bubble_output_at_full_size_config3_subset(lib, oracle):
