@@ -239,20 +239,21 @@ def main():
         del cfs, cbs, sprob
         # how far the paper's own pick (Algorithm 2, one vector per scenario) is from the exhaustive
         # argmin over this workload's candidates: each vector evaluated under its own scenario
-        _, w_ad, _ = binding.adaptra_seed(prob, want_init=False)
-        aprob = binding.Problem(M, prob.tensors[0], prob.tensors[1], w_ad, prob.tensors[3], prob.tensors[4],
-                                prob.tensors[5])
-        amk, _, afl = binding.adaptra_eval(aprob, want_bubble=False)
-        torch.cuda.synchronize()
-        own = torch.arange(K, device=dev)
-        a_mk, a_fl = amk[own, own], afl[own, own]
-        ok = (a_fl == 1) & (bmk != 2 ** 31 - 1)
-        live = ((a_fl & 2) == 0) & (bmk != 2 ** 31 - 1)
-        seed_info["algorithm2_vs_exhaustive"] = {
-            "within_memory_cap": int((a_fl == 1).sum()), "scenarios": int(K),
-            "makespan_ratio_mean_where_within_cap": float((a_mk[ok].double() / bmk[ok].double()).mean()) if ok.any() else None,
-            "makespan_ratio_mean_ignoring_cap": float((a_mk[live].double() / bmk[live].double()).mean()) if live.any() else None}
-        del aprob, amk, afl
+        if not args.no_sens:
+            _, w_ad, _ = binding.adaptra_seed(prob, want_init=False)
+            aprob = binding.Problem(M, prob.tensors[0], prob.tensors[1], w_ad, prob.tensors[3], prob.tensors[4],
+                                    prob.tensors[5])
+            amk, _, afl = binding.adaptra_eval(aprob, want_bubble=False)
+            torch.cuda.synchronize()
+            own = torch.arange(K, device=dev)
+            a_mk, a_fl = amk[own, own], afl[own, own]
+            ok = (a_fl == 1) & (bmk != 2 ** 31 - 1)
+            live = ((a_fl & 2) == 0) & (bmk != 2 ** 31 - 1)
+            seed_info["algorithm2_vs_exhaustive"] = {
+                "within_memory_cap": int((a_fl == 1).sum()), "scenarios": int(K),
+                "makespan_ratio_mean_where_within_cap": float((a_mk[ok].double() / bmk[ok].double()).mean()) if ok.any() else None,
+                "makespan_ratio_mean_ignoring_cap": float((a_mk[live].double() / bmk[live].double()).mean()) if live.any() else None}
+            del aprob, amk, afl
 
     # ZeroBubble (F / B / W) policy evaluation, first version: timed on configuration 1's
     # candidates and scenarios (S=8, N=32, 2^20 pairs, 3 S N = 768 ops per pair), t_w = t_b / 2
