@@ -23,8 +23,8 @@
 //
 // Where the state lives.  The queues (up to N entries each) are in global scratch, laid out
 // [index][thread] so that a wavefront's access is one 256-byte line.  Everything a decision
-// needs is on chip, in LDS laid out [array][stage][lane] (conflict-free for any per-lane
-// stage index): per stage the busy-until time, the cached next-action time, the three
+// needs is on chip, in LDS laid out [stage][array][lane] (conflict-free for any per-lane
+// stage index; a stage's fields at fixed offsets from its base): per stage the busy-until time, the cached next-action time, the three
 // cursors, the warm-up quota x, and the HEAD of each of the three queues (the ready time of
 // the cursor's micro-batch, or "not posted yet").  A post that lands on the head goes straight
 // to LDS and never to memory; a step touches global memory only to append behind a head and
@@ -60,16 +60,17 @@ __device__ __forceinline__ int imax2(int a, int b) { return a > b ? a : b; }
 
 // The lane's view of its state.
 struct Lane {
-    int *lds;                     // this lane's column: element (array, stage) at lds[(array * S + stage) * 64]
+    int *lds;                     // this lane's column: element (stage, array) at lds[(stage * kZbArrays + array) * 64]:
+                                  // a stage's fields sit at fixed offsets from the stage's base address
     const int *dur_table;         // LDS copy of t_f, t_b, t_w: [3][S]
     int *queue;                   // this thread's column of the global queues
     long long nt;
     int S, N;
-    __device__ int &busy(int i) const { return lds[(0 * S + i) * 64]; }
-    __device__ int &act(int i) const { return lds[(1 * S + i) * 64]; }
-    __device__ int &count(int i, int ty) const { return lds[((2 + ty) * S + i) * 64]; }
-    __device__ int &head(int i, int ty) const { return lds[((5 + ty) * S + i) * 64]; }
-    __device__ int &quota(int i) const { return lds[(8 * S + i) * 64]; }
+    __device__ int &busy(int i) const { return lds[(i * kZbArrays + 0) * 64]; }
+    __device__ int &act(int i) const { return lds[(i * kZbArrays + 1) * 64]; }
+    __device__ int &count(int i, int ty) const { return lds[(i * kZbArrays + 2 + ty) * 64]; }
+    __device__ int &head(int i, int ty) const { return lds[(i * kZbArrays + 5 + ty) * 64]; }
+    __device__ int &quota(int i) const { return lds[(i * kZbArrays + 8) * 64]; }
     __device__ int &ready(int i, int ty, int m) const { return queue[(((long long)i * 3 + ty) * N + m) * nt]; }
     __device__ int cursor(int i, int ty) const { return count(i, ty); }
     __device__ void advance(int i, int ty) const { count(i, ty) += 1; }
