@@ -21,15 +21,23 @@
 // the ready times of one (stage, type) form a queue: posted in micro-batch order, consumed in
 // micro-batch order.
 //
-// Where the state lives.  The queues (up to N entries each) are in global scratch, laid out
-// [index][thread] so that a wavefront's access is one 256-byte line.  Everything a decision
-// needs is on chip, in LDS laid out [stage][array][lane] (conflict-free for any per-lane
-// stage index; a stage's fields at fixed offsets from its base): per stage the busy-until time, the cached next-action time, the three
-// cursors, the warm-up quota x, and the HEAD of each of the three queues (the ready time of
-// the cursor's micro-batch, or "not posted yet").  A post that lands on the head goes straight
-// to LDS and never to memory; a step touches global memory only to append behind a head and
-// to fetch the next head after a consume -- about three accesses instead of the forty of a
-// version that kept all state in memory.  One wavefront per block, 9 S KiB / 4 of LDS each.
+// Where the state lives.  Only two kinds of ready time ever have to be remembered: a forward's
+// (posted by the stage before) and a backward's (posted by the stage after).  A weight op is
+// available as soon as its backward has STARTED -- it becomes ready when that backward finishes,
+// and its own stage is busy until then anyway -- so "a W is available" is just nW < nB; the same
+// holds for the last stage's backwards (ready when its own forward finishes: nB < nF) and for
+// stage 0's forwards (ready at time 0).  The two real queues per stage (up to N entries each)
+// are in global scratch, laid out [index][thread] so that a wavefront's access is one 256-byte
+// line.  Everything a decision needs is on chip, in LDS: the cached next-action times as one
+// array [stage][lane] (the earliest-action scan reads two stages per instruction at static
+// offsets), and per stage a block of eight fields [stage][field][lane] at fixed offsets from the
+// stage's base (conflict-free for any per-lane stage index): busy-until, the cursors nF, nB and
+// nW (nW shares a word with the warm-up quota x), the HEAD of each queue (the ready time of the
+// cursor's micro-batch, or "nothing posted"), and the delays of the two links the stage sends
+// over.  A post that lands on an empty queue goes straight to the head in LDS and never to
+// memory, and only then can it change the receiver's next action; a step touches global memory
+// only to append behind a head and to fetch the next head after a consume.  One wavefront per
+// block, (8 S + 8 ceil(S/8)) x 256 bytes of LDS each.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -40,7 +48,10 @@ namespace {
 
 constexpr int kInf = INT32_MAX;
 constexpr int kZbBlock = 64;          // one wavefront per block: LDS, not threads, bounds the occupancy
-constexpr int kZbArrays = 9;          // busy, act, nF, nB, nW, headF, headB, headW, x
+constexpr int kZbFields = 8;          // per-stage block of LDS fields, each 64 lanes wide
+enum : int { fBusy = 0, fNF = 1, fNB = 2, fNWX = 3, fHeadF = 4, fHeadB = 5, fCF = 6, fCB = 7 };
+constexpr int kStage = kZbFields * 64;   // ints from one stage's block to the next
+constexpr int kNone = 3;              // "no op left" in a plan (types: 0 = F, 1 = B, 2 = W)
 
 struct ZbArgs {
     int S, N;
@@ -48,141 +59,142 @@ struct ZbArgs {
     long long C, K;
     const int *w, *cf, *cb;
     long long plan_scenario;      // -1: every pair generates under its own scenario
-    int phase;                    // 0: generate (+ outputs unless a plan is wanted), 1: record plans, 2: replay plans
     int *out_makespan, *out_bubble;
-    int *scratch;                 // queues [S][3][N][threads]
-    int *plans;                   // [C][S][3N], ops as type * N + m
-    long long threads;
+    int *scratch;                 // queues [S][2][N][threads]
+    uint8_t *plans;               // [C][S][3N], op types in the order a stage ran them
+    unsigned threads;
 };
 
 __device__ __forceinline__ int imin(int a, int b) { return a < b ? a : b; }
 __device__ __forceinline__ int imax2(int a, int b) { return a > b ? a : b; }
 
-// The lane's view of its state.
-struct Lane {
-    int *lds;                     // this lane's column: element (stage, array) at lds[(stage * kZbArrays + array) * 64]:
-                                  // a stage's fields sit at fixed offsets from the stage's base address
-    const int *dur_table;         // LDS copy of t_f, t_b, t_w: [3][S]
-    int *queue;                   // this thread's column of the global queues
-    long long nt;
-    int S, N;
-    __device__ int &busy(int i) const { return lds[(i * kZbArrays + 0) * 64]; }
-    __device__ int &act(int i) const { return lds[(i * kZbArrays + 1) * 64]; }
-    __device__ int &count(int i, int ty) const { return lds[(i * kZbArrays + 2 + ty) * 64]; }
-    __device__ int &head(int i, int ty) const { return lds[(i * kZbArrays + 5 + ty) * 64]; }
-    __device__ int &quota(int i) const { return lds[(i * kZbArrays + 8) * 64]; }
-    __device__ int &ready(int i, int ty, int m) const { return queue[(((long long)i * 3 + ty) * N + m) * nt]; }
-    __device__ int cursor(int i, int ty) const { return count(i, ty); }
-    __device__ void advance(int i, int ty) const { count(i, ty) += 1; }
-    __device__ int x(int i) const { return quota(i); }
-    __device__ int done(int i) const { return count(i, 0) + count(i, 1) + count(i, 2); }
+// Next action of a stage from its own fields (Algorithm 3): the time it can act, or kInf if
+// nothing it may run has been posted yet.  nWx = nW | x << 16; when a plan is replayed
+// (PHASE 2) the upper half holds the type of the plan's next op instead of the quota.
+template <int PHASE>
+__device__ __forceinline__ int next_action(int busy, int nF, int nB, int nWx, int headF, int headB) {
+    const int headW = (nWx & 0xffff) < nB ? 0 : kInf;            // ready since its backward finished
+    const int hi = (int)((unsigned)nWx >> 16);
+    int first;
+    if (PHASE == 2) first = hi == 0 ? headF : (hi == 1 ? headB : (hi == 2 ? headW : kInf));
+    else first = nF < hi ? headF : imin(headB, imin(headF, headW));   // warm-up: forwards only
+    return first == kInf ? kInf : imax2(busy, first);
+}
 
-    // Ready times of (i, ty) posted so far: a forward of stage i is posted when the forward of
-    // stage i-1 starts (stage 0: all at time 0), a backward when the backward of stage i+1
-    // starts (last stage: when its own forward starts), a weight op when the stage's own
-    // backward starts.
-    __device__ int posted(int i, int ty) const {
-        if (ty == 0) return i == 0 ? N : cursor(i - 1, 0);
-        if (ty == 1) return i == S - 1 ? cursor(i, 0) : cursor(i + 1, 1);
-        return cursor(i, 1);
-    }
-    // Appends the ready time r of micro-batch m to the queue of (i, ty).
-    __device__ void post(int i, int ty, int m, int r) const {
-        if (m == cursor(i, ty)) head(i, ty) = r;
-        else ready(i, ty, m) = r;
-    }
-    // Next action of stage i from what has been posted so far (Algorithm 3): the time it can
-    // act, or kInf if nothing it may run has been posted yet.  With a plan the next op is the
-    // plan's, whatever its type.
-    __device__ void refresh(int i, const int *plan) const {
-        const int b = busy(i);
-        if (plan) {
-            const int d = done(i);
-            if (d >= 3 * N) { act(i) = kInf; return; }
-            const int r = head(i, plan[d] / N);
-            act(i) = r == kInf ? kInf : imax2(b, r);
-            return;
-        }
-        const int rf = head(i, 0);
-        if (cursor(i, 0) < x(i)) {                              // warm-up: forwards only
-            act(i) = rf == kInf ? kInf : imax2(b, rf);
-            return;
-        }
-        const int first = imin(head(i, 1), imin(rf, head(i, 2)));
-        act(i) = first == kInf ? kInf : imax2(b, first);
-    }
-};
-
+// PHASE 0: generate with the policy and write the outputs; 1: generate under the plan scenario
+// and record each stage's op types; 2: replay the recorded plans under every scenario.
+template <int PHASE>
 __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
     extern __shared__ int zb_lds[];
     const long long tid = (long long)blockIdx.x * kZbBlock + threadIdx.x;
-    const int S = a.S, N = a.N;
-    const long long n_items = a.phase == 1 ? a.C : a.C * a.K;
-    int *const dur_table = zb_lds + kZbArrays * S * 64;
-    for (int i = threadIdx.x; i < 3 * S; i += kZbBlock)
-        dur_table[i] = i < S ? a.t_f[i] : (i < 2 * S ? a.t_b[i - S] : a.t_w[i - 2 * S]);
+    const int S = a.S, N = a.N, Spad = (S + 7) & ~7;
+    const long long n_items = PHASE == 1 ? a.C : a.C * a.K;
+    int *const act = zb_lds + threadIdx.x;                        // [Spad][64]
+    int *const fld = zb_lds + Spad * 64 + threadIdx.x;            // [S][kZbFields][64]
+    int *const dur = zb_lds + Spad * 64 + S * kStage;             // [S][4]: t_f, t_b, t_w, 0
+    for (int i = threadIdx.x; i < 4 * S; i += kZbBlock) {
+        const int s = i >> 2, ty = i & 3;
+        dur[i] = ty == 0 ? a.t_f[s] : (ty == 1 ? a.t_b[s] : (ty == 2 ? a.t_w[s] : 0));
+    }
     __syncthreads();
-    const Lane L{zb_lds + threadIdx.x, dur_table, a.scratch + tid, a.threads, S, N};
-    for (long long item = tid; item < n_items; item += a.threads) {
-        const long long c = a.phase == 1 ? item : item % a.C;
-        const long long k = a.phase == 1 ? a.plan_scenario : item / a.C;
-        const int *plan_base = a.phase == 2 ? a.plans + c * (long long)S * 3 * N : nullptr;
-        int *record = a.phase == 1 ? a.plans + c * (long long)S * 3 * N : nullptr;
+    int *const queue = a.scratch + tid;
+    const unsigned nt = a.threads;
+    for (long long item = tid; item < n_items; item += nt) {
+        const long long c = PHASE == 1 ? item : item % a.C;
+        const long long k = PHASE == 1 ? a.plan_scenario : item / a.C;
+        uint8_t *const plan = a.plans + c * (long long)S * 3 * N;     // stage i's ops at plan + i * 3N
         // set-up: nothing posted except the forwards of stage 0 (available at time 0)
+        for (int i = S; i < Spad; ++i) act[i * 64] = kInf;
         for (int i = 0; i < S; ++i) {
             int wi = a.w[(long long)i * a.C + c];
             wi = wi < 0 ? 0 : (wi > N - 1 ? N - 1 : wi);
-            L.busy(i) = 0;
-            L.count(i, 0) = 0; L.count(i, 1) = 0; L.count(i, 2) = 0;
-            L.quota(i) = wi + 1;                                // x_i = w_i + 1 warm-up forwards
-            L.head(i, 0) = i == 0 ? 0 : kInf;
-            L.head(i, 1) = kInf;
-            L.head(i, 2) = kInf;
+            const int hi = PHASE == 2 ? plan[(long long)i * 3 * N] : wi + 1;   // x_i = w_i + 1 warm-up forwards
+            int *st = fld + i * kStage;
+            st[fBusy * 64] = 0;
+            st[fNF * 64] = 0;
+            st[fNB * 64] = 0;
+            st[fNWX * 64] = hi << 16;
+            st[fHeadF * 64] = i == 0 ? 0 : kInf;
+            st[fHeadB * 64] = kInf;
+            st[fCF * 64] = i < S - 1 ? a.cf[(long long)i * a.K + k] : 0;
+            st[fCB * 64] = i > 0 ? a.cb[(long long)(i - 1) * a.K + k] : 0;
+            act[i * 64] = next_action<PHASE>(0, 0, 0, hi << 16, i == 0 ? 0 : kInf, kInf);
         }
-        for (int i = 0; i < S; ++i) L.refresh(i, plan_base ? plan_base + (long long)i * 3 * N : nullptr);
 
         const int total = 3 * S * N;
         int makespan = 0;
         for (int step = 0; step < total; ++step) {
-            int i = 0, t = L.act(0);
-            for (int j = 1; j < S; ++j) {
-                const int tj = L.act(j);
-                if (tj < t) { t = tj; i = j; }
+            // the stage whose next action is earliest, ties to the lower stage
+            int i = 0, t = kInf;
+            for (int b = 0; b < Spad; b += 8) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int tj = act[(b + j) * 64];
+                    if (tj < t) { t = tj; i = b + j; }
+                }
             }
             if (t == kInf) { makespan = kInf; break; }          // cannot happen for valid input
-            const int *plan_i = plan_base ? plan_base + (long long)i * 3 * N : nullptr;
-            const int done_i = L.done(i);
+            int *const st = fld + i * kStage;
+            int nF = st[fNF * 64], nB = st[fNB * 64], nWx = st[fNWX * 64];
+            int headF = st[fHeadF * 64], headB = st[fHeadB * 64];
+            const int hi = (int)((unsigned)nWx >> 16), nW = nWx & 0xffff;
             int ty;
-            if (plan_i) ty = plan_i[done_i] / N;
-            else if (L.cursor(i, 0) < L.x(i)) ty = 0;
-            else ty = L.head(i, 1) <= t ? 1 : (L.head(i, 0) <= t ? 0 : 2);   // priority B > F > W among those ready at t
-            const int m = L.cursor(i, ty);
-            const int dur = L.dur_table[ty * S + i];
-            const int fin = t + dur;
-            L.busy(i) = fin;
+            if (PHASE == 2) ty = hi;
+            else ty = nF < hi ? 0 : (headB <= t ? 1 : (headF <= t ? 0 : 2));   // priority B > F > W among those ready at t
+            const int m = ty == 0 ? nF : (ty == 1 ? nB : nW);
+            const int done = nF + nB + nW;
+            const int fin = t + dur[i * 4 + ty];
             makespan = imax2(makespan, fin);
-            if (record) record[(long long)i * 3 * N + done_i] = ty * N + m;
-            // consume: the queue's next entry becomes the head (stage 0's forwards are all ready at 0)
-            L.advance(i, ty);
-            if (m + 1 < L.posted(i, ty)) L.head(i, ty) = (ty == 0 && i == 0) ? 0 : L.ready(i, ty, m + 1);
-            else L.head(i, ty) = kInf;
-            int lo = i, hi = i;
-            if (ty == 0) {
-                if (i < S - 1) { L.post(i + 1, 0, m, fin + a.cf[(long long)i * a.K + k]); hi = i + 1; }
-                else L.post(i, 1, m, fin);
-            } else if (ty == 1) {
-                L.post(i, 2, m, fin);
-                if (i > 0) { L.post(i - 1, 1, m, fin + a.cb[(long long)(i - 1) * a.K + k]); lo = i - 1; }
+            if (PHASE == 1) plan[(long long)i * 3 * N + done] = (uint8_t)ty;
+            nF += ty == 0;
+            nB += ty == 1;
+            nWx += ty == 2;
+            if (PHASE == 2) {
+                const int next_ty = done + 1 < 3 * N ? plan[(long long)i * 3 * N + done + 1] : kNone;
+                nWx = (nWx & 0xffff) | next_ty << 16;
             }
-            for (int j = lo; j <= hi; ++j) L.refresh(j, plan_base ? plan_base + (long long)j * 3 * N : nullptr);
+            const bool last = i == S - 1;
+            if (ty < 2) {
+                // consume: the queue's next entry becomes the head.  Entries posted so far = ops of
+                // that type the producing stage has started; stage 0's forwards and the last
+                // stage's backwards come from no other stage and are ready whenever it is idle.
+                const bool own = ty == 0 ? i == 0 : last;
+                const int *producer = own ? st + fNF * 64 : (ty == 0 ? st - kStage + fNF * 64 : st + kStage + fNB * 64);
+                const int posted = own ? (ty == 0 ? N : nF) : *producer;
+                int next = kInf;
+                if (m + 1 < posted) next = own ? 0 : queue[(unsigned long long)(unsigned)((i * 2 + ty) * N + m + 1) * nt];
+                if (ty == 0) headF = next; else headB = next;
+            }
+            if (last && ty == 0) headB = 0;                     // its own forward makes a backward available
+            st[fBusy * 64] = fin;
+            st[fNF * 64] = nF;
+            st[fNB * 64] = nB;
+            st[fNWX * 64] = nWx;
+            st[fHeadF * 64] = headF;
+            st[fHeadB * 64] = headB;
+            act[i * 64] = next_action<PHASE>(fin, nF, nB, nWx, headF, headB);
+            // post the ready time this op creates: F(i,m) -> F(i+1,m), B(i,m) -> B(i-1,m)
+            const int j = ty == 0 ? i + 1 : i - 1;
+            if (ty < 2 && j >= 0 && j < S) {
+                const int r = fin + st[(ty == 0 ? fCF : fCB) * 64];
+                int *const sj = ty == 0 ? st + kStage : st - kStage;
+                int hFj = sj[fHeadF * 64], hBj = sj[fHeadB * 64];
+                if ((ty == 0 ? hFj : hBj) == kInf) {            // empty queue: r is its head, the receiver may act earlier
+                    if (ty == 0) hFj = r; else hBj = r;
+                    sj[(fHeadF + ty) * 64] = r;
+                    act[j * 64] = next_action<PHASE>(sj[fBusy * 64], sj[fNF * 64], sj[fNB * 64], sj[fNWX * 64], hFj, hBj);
+                } else {
+                    queue[(unsigned long long)(unsigned)((j * 2 + ty) * N + m) * nt] = r;
+                }
+            }
         }
-        if (a.phase != 1) {
+        if (PHASE != 1) {
             const long long P = a.C * a.K;
             a.out_makespan[item] = makespan;
             if (a.out_bubble)
                 for (int i = 0; i < S; ++i)
                     a.out_bubble[(long long)i * P + item] =
-                        makespan == kInf ? kInf : makespan - N * (dur_table[i] + dur_table[S + i] + dur_table[2 * S + i]);
+                        makespan == kInf ? kInf : makespan - N * (dur[i * 4] + dur[i * 4 + 1] + dur[i * 4 + 2]);
         }
     }
 }
@@ -190,8 +202,8 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct ZbPlan {
-    long long threads;
-    size_t off_scratch, off_plans, total;
+    unsigned threads;
+    size_t lds, off_scratch, off_plans, total;
 };
 
 bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
@@ -199,21 +211,35 @@ bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
     if (C < 1 || C > INT32_MAX || K < 1 || K > INT32_MAX) return false;
     // Enough threads to fill the chip at the occupancy the LDS state allows (at most 160 KiB
     // per CU, 32 wavefronts per CU, 256 CUs), within about 2 GiB of queue memory.
-    const long long per_thread = 3ll * S * N * 4;
-    const long long lds_per_wave = (long long)kZbArrays * S * 64 * 4 + 3ll * S * 4;
-    long long waves_per_cu = (160ll << 10) / lds_per_wave;
+    const long long per_thread = 2ll * S * N * 4;
+    const int Spad = (S + 7) & ~7;
+    p->lds = ((size_t)Spad * 64 + (size_t)S * kStage + 4 * (size_t)S) * 4;
+    long long waves_per_cu = (160ll << 10) / (long long)p->lds;
     if (waves_per_cu > 32) waves_per_cu = 32;
     if (waves_per_cu < 1) return false;
     long long nt = 256 * waves_per_cu * kZbBlock;
     const long long cap = (2048ll << 20) / per_thread / kZbBlock * kZbBlock;
     if (nt > cap) nt = cap;
     if (nt < 16 * kZbBlock) nt = 16 * kZbBlock;
-    p->threads = nt;
+    p->threads = (unsigned)nt;
     size_t o = 0;
     p->off_scratch = o; o += align256((size_t)nt * per_thread);
-    p->off_plans = o;   o += align256((size_t)C * S * 3 * N * 4);
+    p->off_plans = o;   o += align256((size_t)C * S * 3 * N);
     p->total = o;
     return true;
+}
+
+template <int PHASE>
+int launch_zb(ZbArgs a, long long items, unsigned full, size_t lds, hipStream_t st) {
+    if (lds > 48 * 1024) {                                   // above the default dynamic-LDS limit
+        hipError_t e = hipFuncSetAttribute((const void *)k_zb<PHASE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return adaptra_detail::hip_fail(e);
+    }
+    const long long n = items < (long long)full ? items : (long long)full;
+    a.threads = (unsigned)((n + kZbBlock - 1) / kZbBlock * kZbBlock);   // a multiple of the block, at most `full`
+    hipLaunchKernelGGL(k_zb<PHASE>, dim3(a.threads / kZbBlock), dim3(kZbBlock), lds, st, a);
+    ADAPTRA_CHECK_LAUNCH();
+    return ADAPTRA_OK;
 }
 
 }  // namespace
@@ -246,31 +272,12 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
     a.plan_scenario = plan_scenario;
     a.out_makespan = out_makespan; a.out_bubble = out_bubble;
     a.scratch = (int *)((char *)workspace + p.off_scratch);
-    a.plans = (int *)((char *)workspace + p.off_plans);
-    a.threads = p.threads;
+    a.plans = (uint8_t *)workspace + p.off_plans;
     const long long P = a.C * a.K;
-    const size_t lds = (size_t)kZbArrays * a.S * 64 * 4 + (size_t)3 * a.S * 4;
-    if (lds > 48 * 1024) {                                   // above the default dynamic-LDS limit
-        hipError_t e = hipFuncSetAttribute((const void *)k_zb, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return adaptra_detail::hip_fail(e);
-    }
-    const long long full = p.threads;
-    auto launch = [&](long long items) -> int {              // threads: a multiple of the block, at most `full`
-        const long long n = items < full ? items : full;
-        a.threads = (n + kZbBlock - 1) / kZbBlock * kZbBlock;
-        hipLaunchKernelGGL(k_zb, dim3((unsigned)(a.threads / kZbBlock)), dim3(kZbBlock), lds, st, a);
-        ADAPTRA_CHECK_LAUNCH();
-        return ADAPTRA_OK;
-    };
-    if (plan_scenario < 0) {
-        a.phase = 0;
-        return launch(P);
-    }
-    a.phase = 1;                                             // one plan per candidate, under the plan scenario
-    int rc = launch(a.C);
+    if (plan_scenario < 0) return launch_zb<0>(a, P, p.threads, p.lds, st);
+    int rc = launch_zb<1>(a, a.C, p.threads, p.lds, st);      // one plan per candidate, under the plan scenario
     if (rc) return rc;
-    a.phase = 2;                                             // every pair replays its candidate's plan
-    return launch(P);
+    return launch_zb<2>(a, P, p.threads, p.lds, st);         // every pair replays its candidate's plan
 }
 
 }  // extern "C"
