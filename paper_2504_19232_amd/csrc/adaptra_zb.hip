@@ -30,14 +30,17 @@
 // are in global scratch, laid out [index][thread] so that a wavefront's access is one 256-byte
 // line.  Everything a decision needs is on chip, in LDS: the cached next-action times as one
 // array [stage][lane] (the earliest-action scan reads two stages per instruction at static
-// offsets), and per stage a block of eight fields [stage][field][lane] at fixed offsets from the
-// stage's base (conflict-free for any per-lane stage index): busy-until, the cursors nF, nB and
-// nW (nW shares a word with the warm-up quota x), the HEAD of each queue (the ready time of the
-// cursor's micro-batch, or "nothing posted"), and the delays of the two links the stage sends
-// over.  A post that lands on an empty queue goes straight to the head in LDS and never to
-// memory, and only then can it change the receiver's next action; a step touches global memory
-// only to append behind a head and to fetch the next head after a consume.  One wavefront per
-// block, (8 S + 8 ceil(S/8)) x 256 bytes of LDS each.
+// offsets), and per stage a block of four fields [stage][field][lane] at fixed offsets from the
+// stage's base (conflict-free for any per-lane stage index): the cursors (nF and nB share a
+// word, nW shares one with the warm-up quota x) and the HEAD of each queue (the ready time of
+// the cursor's micro-batch; an empty queue's slot keeps the stage's busy-until time instead).
+// A post that lands on an empty queue goes straight to the head in LDS and never to memory, and
+// only then can it change the receiver's next action; a step touches global memory only to
+// append behind a head and to fetch the next head after a consume.  One wavefront per block
+// works on 64 candidates of ONE scenario at a time, so the link delays are a small table shared
+// by its lanes.  LDS per wavefront: (4 S + 8 ceil(S/8)) x 256 bytes -- the occupancy limit of
+// this kernel, whose step is a chain of dependent LDS round trips that only more resident
+// wavefronts can hide.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -48,10 +51,16 @@ namespace {
 
 constexpr int kInf = INT32_MAX;
 constexpr int kZbBlock = 64;          // one wavefront per block: LDS, not threads, bounds the occupancy
-constexpr int kZbFields = 8;          // per-stage block of LDS fields, each 64 lanes wide
-enum : int { fBusy = 0, fNF = 1, fNB = 2, fNWX = 3, fHeadF = 4, fHeadB = 5, fCF = 6, fCB = 7 };
+constexpr int kZbFields = 4;          // per-stage block of LDS fields, each 64 lanes wide
+enum : int { fNFB = 0, fNWX = 1, fHeadF = 2, fHeadB = 3 };   // nFB = nF | nB << 16, nWx = nW | x << 16
 constexpr int kStage = kZbFields * 64;   // ints from one stage's block to the next
 constexpr int kNone = 3;              // "no op left" in a plan (types: 0 = F, 1 = B, 2 = W)
+// A head holds the ready time of the queue's first entry (>= 0), or, while the queue is empty,
+// the complement of the stage's busy-until time (< 0): read as unsigned, "empty" sorts after
+// every time, and a post that lands on an empty queue -- the only one that makes the receiver
+// look at its next action again -- finds the receiver's busy-until time in the slot it fills.
+__device__ __forceinline__ unsigned empty_head(int busy) { return ~(unsigned)busy; }
+__device__ __forceinline__ bool is_empty(unsigned head) { return (int)head < 0; }
 
 struct ZbArgs {
     int S, N;
@@ -62,23 +71,25 @@ struct ZbArgs {
     int *out_makespan, *out_bubble;
     int *scratch;                 // queues [S][2][N][threads]
     uint8_t *plans;               // [C][S][3N], op types in the order a stage ran them
-    unsigned threads;
+    unsigned threads;             // of the launch = stride of the queues
+    unsigned long long *next_unit;   // work counter of this launch, zero when it starts
 };
 
-__device__ __forceinline__ int imin(int a, int b) { return a < b ? a : b; }
+__device__ __forceinline__ unsigned umin(unsigned a, unsigned b) { return a < b ? a : b; }
 __device__ __forceinline__ int imax2(int a, int b) { return a > b ? a : b; }
 
 // Next action of a stage from its own fields (Algorithm 3): the time it can act, or kInf if
-// nothing it may run has been posted yet.  nWx = nW | x << 16; when a plan is replayed
-// (PHASE 2) the upper half holds the type of the plan's next op instead of the quota.
+// nothing it may run has been posted yet.  When a plan is replayed (PHASE 2) the upper half of
+// nWx holds the type of the plan's next op instead of the quota.
 template <int PHASE>
-__device__ __forceinline__ int next_action(int busy, int nF, int nB, int nWx, int headF, int headB) {
-    const int headW = (nWx & 0xffff) < nB ? 0 : kInf;            // ready since its backward finished
+__device__ __forceinline__ int next_action(int busy, int nFB, int nWx, unsigned headF, unsigned headB) {
+    const int nF = nFB & 0xffff, nB = (int)((unsigned)nFB >> 16);
+    const unsigned headW = (nWx & 0xffff) < nB ? 0u : ~0u;       // ready since its backward finished
     const int hi = (int)((unsigned)nWx >> 16);
-    int first;
-    if (PHASE == 2) first = hi == 0 ? headF : (hi == 1 ? headB : (hi == 2 ? headW : kInf));
-    else first = nF < hi ? headF : imin(headB, imin(headF, headW));   // warm-up: forwards only
-    return first == kInf ? kInf : imax2(busy, first);
+    unsigned first;
+    if (PHASE == 2) first = hi == 0 ? headF : (hi == 1 ? headB : (hi == 2 ? headW : ~0u));
+    else first = nF < hi ? headF : umin(headB, umin(headF, headW));   // warm-up: forwards only
+    return is_empty(first) ? kInf : imax2(busy, (int)first);
 }
 
 // PHASE 0: generate with the policy and write the outputs; 1: generate under the plan scenario
@@ -86,23 +97,40 @@ __device__ __forceinline__ int next_action(int busy, int nF, int nB, int nWx, in
 template <int PHASE>
 __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
     extern __shared__ int zb_lds[];
-    const long long tid = (long long)blockIdx.x * kZbBlock + threadIdx.x;
     const int S = a.S, N = a.N, Spad = (S + 7) & ~7;
-    const long long n_items = PHASE == 1 ? a.C : a.C * a.K;
     int *const act = zb_lds + threadIdx.x;                        // [Spad][64]
     int *const fld = zb_lds + Spad * 64 + threadIdx.x;            // [S][kZbFields][64]
     int *const dur = zb_lds + Spad * 64 + S * kStage;             // [S][4]: t_f, t_b, t_w, 0
+    int *const delay = dur + 4 * S;                               // [S][2]: forward delay of link i -> i+1, backward delay of link i-1 <- i
     for (int i = threadIdx.x; i < 4 * S; i += kZbBlock) {
         const int s = i >> 2, ty = i & 3;
         dur[i] = ty == 0 ? a.t_f[s] : (ty == 1 ? a.t_b[s] : (ty == 2 ? a.t_w[s] : 0));
     }
-    __syncthreads();
-    int *const queue = a.scratch + tid;
+    int *const queue = a.scratch + ((long long)blockIdx.x * kZbBlock + threadIdx.x);
     const unsigned nt = a.threads;
-    for (long long item = tid; item < n_items; item += nt) {
-        const long long c = PHASE == 1 ? item : item % a.C;
-        const long long k = PHASE == 1 ? a.plan_scenario : item / a.C;
+    // A unit of work = one scenario x 64 consecutive candidates (the last chunk may be short:
+    // its spare lanes repeat the last candidate and write nothing).  Wavefronts draw units from
+    // a counter, so one that becomes resident late (the launch may hold a few more than fit at
+    // once) takes what is left instead of a fixed share.
+    __shared__ long long unit_drawn;
+    const long long chunks = (a.C + kZbBlock - 1) / kZbBlock;
+    const long long n_units = PHASE == 1 ? chunks : chunks * a.K;
+    for (;;) {
+        __syncthreads();                                          // the previous unit is finished in every lane
+        if (threadIdx.x == 0) unit_drawn = (long long)atomicAdd(a.next_unit, 1ull);
+        __syncthreads();
+        const long long unit = unit_drawn;
+        if (unit >= n_units) break;
+        const long long k = PHASE == 1 ? a.plan_scenario : unit / chunks;
+        const long long c_lane = (unit % chunks) * kZbBlock + threadIdx.x;
+        const bool live = c_lane < a.C;
+        const long long c = live ? c_lane : a.C - 1;
         uint8_t *const plan = a.plans + c * (long long)S * 3 * N;     // stage i's ops at plan + i * 3N
+        for (int i = threadIdx.x; i < S; i += kZbBlock) {
+            delay[i * 2] = i < S - 1 ? a.cf[(long long)i * a.K + k] : 0;
+            delay[i * 2 + 1] = i > 0 ? a.cb[(long long)(i - 1) * a.K + k] : 0;
+        }
+        __syncthreads();
         // set-up: nothing posted except the forwards of stage 0 (available at time 0)
         for (int i = S; i < Spad; ++i) act[i * 64] = kInf;
         for (int i = 0; i < S; ++i) {
@@ -110,15 +138,11 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
             wi = wi < 0 ? 0 : (wi > N - 1 ? N - 1 : wi);
             const int hi = PHASE == 2 ? plan[(long long)i * 3 * N] : wi + 1;   // x_i = w_i + 1 warm-up forwards
             int *st = fld + i * kStage;
-            st[fBusy * 64] = 0;
-            st[fNF * 64] = 0;
-            st[fNB * 64] = 0;
+            st[fNFB * 64] = 0;
             st[fNWX * 64] = hi << 16;
-            st[fHeadF * 64] = i == 0 ? 0 : kInf;
-            st[fHeadB * 64] = kInf;
-            st[fCF * 64] = i < S - 1 ? a.cf[(long long)i * a.K + k] : 0;
-            st[fCB * 64] = i > 0 ? a.cb[(long long)(i - 1) * a.K + k] : 0;
-            act[i * 64] = next_action<PHASE>(0, 0, 0, hi << 16, i == 0 ? 0 : kInf, kInf);
+            st[fHeadF * 64] = (int)(i == 0 ? 0u : empty_head(0));
+            st[fHeadB * 64] = (int)empty_head(0);
+            act[i * 64] = next_action<PHASE>(0, 0, hi << 16, i == 0 ? 0u : empty_head(0), empty_head(0));
         }
 
         const int total = 3 * S * N;
@@ -127,69 +151,83 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
             // the stage whose next action is earliest, ties to the lower stage
             int i = 0, t = kInf;
             for (int b = 0; b < Spad; b += 8) {
+                int tb = act[b * 64], jb = 0;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
+                for (int j = 1; j < 8; ++j) {
                     const int tj = act[(b + j) * 64];
-                    if (tj < t) { t = tj; i = b + j; }
+                    if (tj < tb) { tb = tj; jb = j; }
                 }
+                if (tb < t) { t = tb; i = b + jb; }
             }
             if (t == kInf) { makespan = kInf; break; }          // cannot happen for valid input
+            // Everything whose address depends on the stage alone is read now, in one round trip:
+            // the stage's fields, its three durations and two delays, the cursors of the two
+            // producing stages.
             int *const st = fld + i * kStage;
-            int nF = st[fNF * 64], nB = st[fNB * 64], nWx = st[fNWX * 64];
-            int headF = st[fHeadF * 64], headB = st[fHeadB * 64];
+            const bool first = i == 0, last = i == S - 1;
+            int nFB = st[fNFB * 64], nWx = st[fNWX * 64];
+            unsigned headF = (unsigned)st[fHeadF * 64], headB = (unsigned)st[fHeadB * 64];
+            const int4 dur_i = *reinterpret_cast<const int4 *>(dur + i * 4);
+            const int2 delay_i = *reinterpret_cast<const int2 *>(delay + i * 2);
+            const int nFB_prev = *(first ? st + fNFB * 64 : st - kStage + fNFB * 64);
+            const int nFB_next = *(last ? st + fNFB * 64 : st + kStage + fNFB * 64);
+            const int nF = nFB & 0xffff, nB = (int)((unsigned)nFB >> 16);
             const int hi = (int)((unsigned)nWx >> 16), nW = nWx & 0xffff;
             int ty;
             if (PHASE == 2) ty = hi;
-            else ty = nF < hi ? 0 : (headB <= t ? 1 : (headF <= t ? 0 : 2));   // priority B > F > W among those ready at t
+            else ty = nF < hi ? 0 : (headB <= (unsigned)t ? 1 : (headF <= (unsigned)t ? 0 : 2));   // priority B > F > W among those ready at t
+            // the stage this op posts to: F(i,m) -> F(i+1,m), B(i,m) -> B(i-1,m); its fields are
+            // read before this stage's own are written (another stage, or unused)
+            const int j = ty == 0 ? i + 1 : i - 1;
+            const bool posts = ty < 2 && j >= 0 && j < S;
+            int *const sj = posts ? (ty == 0 ? st + kStage : st - kStage) : st;
+            const int nFB_j = sj[fNFB * 64], nWx_j = sj[fNWX * 64];
+            unsigned headF_j = (unsigned)sj[fHeadF * 64], headB_j = (unsigned)sj[fHeadB * 64];
+
             const int m = ty == 0 ? nF : (ty == 1 ? nB : nW);
             const int done = nF + nB + nW;
-            const int fin = t + dur[i * 4 + ty];
+            const int fin = t + (ty == 0 ? dur_i.x : (ty == 1 ? dur_i.y : dur_i.z));
             makespan = imax2(makespan, fin);
-            if (PHASE == 1) plan[(long long)i * 3 * N + done] = (uint8_t)ty;
-            nF += ty == 0;
-            nB += ty == 1;
+            if (PHASE == 1 && live) plan[(long long)i * 3 * N + done] = (uint8_t)ty;
+            nFB += ty == 0 ? 1 : (ty == 1 ? 0x10000 : 0);
             nWx += ty == 2;
             if (PHASE == 2) {
                 const int next_ty = done + 1 < 3 * N ? plan[(long long)i * 3 * N + done + 1] : kNone;
                 nWx = (nWx & 0xffff) | next_ty << 16;
             }
-            const bool last = i == S - 1;
             if (ty < 2) {
                 // consume: the queue's next entry becomes the head.  Entries posted so far = ops of
                 // that type the producing stage has started; stage 0's forwards and the last
                 // stage's backwards come from no other stage and are ready whenever it is idle.
-                const bool own = ty == 0 ? i == 0 : last;
-                const int *producer = own ? st + fNF * 64 : (ty == 0 ? st - kStage + fNF * 64 : st + kStage + fNB * 64);
-                const int posted = own ? (ty == 0 ? N : nF) : *producer;
-                int next = kInf;
-                if (m + 1 < posted) next = own ? 0 : queue[(unsigned long long)(unsigned)((i * 2 + ty) * N + m + 1) * nt];
+                const bool own = ty == 0 ? first : last;
+                const int posted = ty == 0 ? (first ? N : (nFB_prev & 0xffff))
+                                           : (last ? (nFB & 0xffff) : (int)((unsigned)nFB_next >> 16));
+                unsigned next = ~0u;
+                if (m + 1 < posted) next = own ? 0u : (unsigned)queue[(unsigned long long)(unsigned)((i * 2 + ty) * N + m + 1) * nt];
                 if (ty == 0) headF = next; else headB = next;
             }
+            if (is_empty(headF)) headF = empty_head(fin);       // busy until fin from now on
+            if (is_empty(headB)) headB = empty_head(fin);
             if (last && ty == 0) headB = 0;                     // its own forward makes a backward available
-            st[fBusy * 64] = fin;
-            st[fNF * 64] = nF;
-            st[fNB * 64] = nB;
+            st[fNFB * 64] = nFB;
             st[fNWX * 64] = nWx;
-            st[fHeadF * 64] = headF;
-            st[fHeadB * 64] = headB;
-            act[i * 64] = next_action<PHASE>(fin, nF, nB, nWx, headF, headB);
-            // post the ready time this op creates: F(i,m) -> F(i+1,m), B(i,m) -> B(i-1,m)
-            const int j = ty == 0 ? i + 1 : i - 1;
-            if (ty < 2 && j >= 0 && j < S) {
-                const int r = fin + st[(ty == 0 ? fCF : fCB) * 64];
-                int *const sj = ty == 0 ? st + kStage : st - kStage;
-                int hFj = sj[fHeadF * 64], hBj = sj[fHeadB * 64];
-                if ((ty == 0 ? hFj : hBj) == kInf) {            // empty queue: r is its head, the receiver may act earlier
-                    if (ty == 0) hFj = r; else hBj = r;
+            st[fHeadF * 64] = (int)headF;
+            st[fHeadB * 64] = (int)headB;
+            act[i * 64] = next_action<PHASE>(fin, nFB, nWx, headF, headB);
+            if (posts) {
+                const int r = fin + (ty == 0 ? delay_i.x : delay_i.y);
+                const unsigned slot = ty == 0 ? headF_j : headB_j;
+                if (is_empty(slot)) {                           // r becomes the head: the receiver may act earlier
+                    if (ty == 0) headF_j = (unsigned)r; else headB_j = (unsigned)r;
                     sj[(fHeadF + ty) * 64] = r;
-                    act[j * 64] = next_action<PHASE>(sj[fBusy * 64], sj[fNF * 64], sj[fNB * 64], sj[fNWX * 64], hFj, hBj);
+                    act[j * 64] = next_action<PHASE>((int)~slot, nFB_j, nWx_j, headF_j, headB_j);
                 } else {
                     queue[(unsigned long long)(unsigned)((j * 2 + ty) * N + m) * nt] = r;
                 }
             }
         }
-        if (PHASE != 1) {
-            const long long P = a.C * a.K;
+        if (PHASE != 1 && live) {
+            const long long P = a.C * a.K, item = k * a.C + c;
             a.out_makespan[item] = makespan;
             if (a.out_bubble)
                 for (int i = 0; i < S; ++i)
@@ -199,11 +237,15 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
     }
 }
 
+__global__ void k_zb_reset(unsigned long long *counters) {
+    if (threadIdx.x < 2) counters[threadIdx.x] = 0;
+}
+
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct ZbPlan {
     unsigned threads;
-    size_t lds, off_scratch, off_plans, total;
+    size_t lds, off_counters, off_scratch, off_plans, total;
 };
 
 bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
@@ -213,7 +255,7 @@ bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
     // per CU, 32 wavefronts per CU, 256 CUs), within about 2 GiB of queue memory.
     const long long per_thread = 2ll * S * N * 4;
     const int Spad = (S + 7) & ~7;
-    p->lds = ((size_t)Spad * 64 + (size_t)S * kStage + 4 * (size_t)S) * 4;
+    p->lds = ((size_t)Spad * 64 + (size_t)S * kStage + 6 * (size_t)S) * 4;
     long long waves_per_cu = (160ll << 10) / (long long)p->lds;
     if (waves_per_cu > 32) waves_per_cu = 32;
     if (waves_per_cu < 1) return false;
@@ -223,6 +265,7 @@ bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
     if (nt < 16 * kZbBlock) nt = 16 * kZbBlock;
     p->threads = (unsigned)nt;
     size_t o = 0;
+    p->off_counters = o; o += 256;
     p->off_scratch = o; o += align256((size_t)nt * per_thread);
     p->off_plans = o;   o += align256((size_t)C * S * 3 * N);
     p->total = o;
@@ -230,13 +273,13 @@ bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
 }
 
 template <int PHASE>
-int launch_zb(ZbArgs a, long long items, unsigned full, size_t lds, hipStream_t st) {
+int launch_zb(ZbArgs a, long long scenarios, unsigned full, size_t lds, hipStream_t st) {
     if (lds > 48 * 1024) {                                   // above the default dynamic-LDS limit
         hipError_t e = hipFuncSetAttribute((const void *)k_zb<PHASE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return adaptra_detail::hip_fail(e);
     }
-    const long long n = items < (long long)full ? items : (long long)full;
-    a.threads = (unsigned)((n + kZbBlock - 1) / kZbBlock * kZbBlock);   // a multiple of the block, at most `full`
+    const long long units = (a.C + kZbBlock - 1) / kZbBlock * scenarios;   // one wavefront each, at most `full` threads at a time
+    a.threads = (unsigned)(units < (long long)(full / kZbBlock) ? units : (long long)(full / kZbBlock)) * kZbBlock;
     hipLaunchKernelGGL(k_zb<PHASE>, dim3(a.threads / kZbBlock), dim3(kZbBlock), lds, st, a);
     ADAPTRA_CHECK_LAUNCH();
     return ADAPTRA_OK;
@@ -273,11 +316,15 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
     a.out_makespan = out_makespan; a.out_bubble = out_bubble;
     a.scratch = (int *)((char *)workspace + p.off_scratch);
     a.plans = (uint8_t *)workspace + p.off_plans;
-    const long long P = a.C * a.K;
-    if (plan_scenario < 0) return launch_zb<0>(a, P, p.threads, p.lds, st);
-    int rc = launch_zb<1>(a, a.C, p.threads, p.lds, st);      // one plan per candidate, under the plan scenario
+    unsigned long long *counters = (unsigned long long *)((char *)workspace + p.off_counters);
+    hipLaunchKernelGGL(k_zb_reset, dim3(1), dim3(64), 0, st, counters);
+    ADAPTRA_CHECK_LAUNCH();
+    a.next_unit = counters;
+    if (plan_scenario < 0) return launch_zb<0>(a, a.K, p.threads, p.lds, st);
+    int rc = launch_zb<1>(a, 1, p.threads, p.lds, st);        // one plan per candidate, under the plan scenario
     if (rc) return rc;
-    return launch_zb<2>(a, P, p.threads, p.lds, st);         // every pair replays its candidate's plan
+    a.next_unit = counters + 1;
+    return launch_zb<2>(a, a.K, p.threads, p.lds, st);       // every pair replays its candidate's plan
 }
 
 }  // extern "C"
