@@ -70,7 +70,8 @@ struct ZbArgs {
     long long plan_scenario;      // -1: every pair generates under its own scenario
     int *out_makespan, *out_bubble;
     int *scratch;                 // queues [S][2][N][threads]
-    uint8_t *plans;               // [C][S][3N], op types in the order a stage ran them
+    uint8_t *plans;               // [C][S][3N], op types in the order a stage ran them (written by PHASE 1)
+    const uint32_t *packed;       // [C][S][packed_words(N)], the same at 2 bits per op, kNone behind the end (read by PHASE 2)
     unsigned threads;             // of the launch = stride of the queues
     unsigned long long *next_unit;   // work counter of this launch, zero when it starts
 };
@@ -78,14 +79,19 @@ struct ZbArgs {
 __device__ __forceinline__ unsigned umin(unsigned a, unsigned b) { return a < b ? a : b; }
 __device__ __forceinline__ int imax2(int a, int b) { return a > b ? a : b; }
 
+// Words per stage of a packed plan: 16 ops each, and one more so that a window starting at any
+// op up to the end can be read as two consecutive words.
+__host__ __device__ inline int packed_words(int N) { return 3 * N / 16 + 2; }
+constexpr int kWindow = 8;            // ops of a plan held on chip per stage (2 bits each, the upper half of nWx)
+
 // Next action of a stage from its own fields (Algorithm 3): the time it can act, or kInf if
 // nothing it may run has been posted yet.  When a plan is replayed (PHASE 2) the upper half of
-// nWx holds the type of the plan's next op instead of the quota.
+// nWx holds, instead of the quota, the types of the plan's next kWindow ops, the next one lowest.
 template <int PHASE>
 __device__ __forceinline__ int next_action(int busy, int nFB, int nWx, unsigned headF, unsigned headB) {
     const int nF = nFB & 0xffff, nB = (int)((unsigned)nFB >> 16);
     const unsigned headW = (nWx & 0xffff) < nB ? 0u : ~0u;       // ready since its backward finished
-    const int hi = (int)((unsigned)nWx >> 16);
+    const int hi = PHASE == 2 ? (nWx >> 16) & 3 : (int)((unsigned)nWx >> 16);
     unsigned first;
     if (PHASE == 2) first = hi == 0 ? headF : (hi == 1 ? headB : (hi == 2 ? headW : ~0u));
     else first = nF < hi ? headF : umin(headB, umin(headF, headW));   // warm-up: forwards only
@@ -126,6 +132,7 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
         const bool live = c_lane < a.C;
         const long long c = live ? c_lane : a.C - 1;
         uint8_t *const plan = a.plans + c * (long long)S * 3 * N;     // stage i's ops at plan + i * 3N
+        const uint32_t *const packed_row = a.packed + c * (long long)S * packed_words(N);
         for (int i = threadIdx.x; i < S; i += kZbBlock) {
             delay[i * 2] = i < S - 1 ? a.cf[(long long)i * a.K + k] : 0;
             delay[i * 2 + 1] = i > 0 ? a.cb[(long long)(i - 1) * a.K + k] : 0;
@@ -136,7 +143,7 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
         for (int i = 0; i < S; ++i) {
             int wi = a.w[(long long)i * a.C + c];
             wi = wi < 0 ? 0 : (wi > N - 1 ? N - 1 : wi);
-            const int hi = PHASE == 2 ? plan[(long long)i * 3 * N] : wi + 1;   // x_i = w_i + 1 warm-up forwards
+            const int hi = PHASE == 2 ? (int)(packed_row[(long long)i * packed_words(N)] & 0xffff) : wi + 1;   // x_i = w_i + 1 warm-up forwards
             int *st = fld + i * kStage;
             st[fNFB * 64] = 0;
             st[fNWX * 64] = hi << 16;
@@ -148,6 +155,20 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
         const int total = 3 * S * N;
         int makespan = 0;
         for (int step = 0; step < total; ++step) {
+            if (PHASE == 2 && step % (kWindow - 1) == 0 && step > 0) {
+                // A stage runs at most kWindow - 1 ops in as many steps, so its window never runs
+                // out of a next op: re-reading every stage's window here, for all lanes at once,
+                // keeps the plan's memory latency out of the steps in between.  The next op of a
+                // stage does not change by this.
+                for (int i = 0; i < S; ++i) {
+                    int *const st = fld + i * kStage;
+                    const int nFB = st[fNFB * 64], nWx = st[fNWX * 64];
+                    const int done = (nFB & 0xffff) + (int)((unsigned)nFB >> 16) + (nWx & 0xffff);
+                    const uint32_t *const at = packed_row + (long long)i * packed_words(N) + (done >> 4);
+                    const unsigned long long two = at[0] | (unsigned long long)at[1] << 32;
+                    st[fNWX * 64] = (nWx & 0xffff) | (int)((unsigned)(two >> ((done & 15) * 2)) << 16);
+                }
+            }
             // the stage whose next action is earliest, ties to the lower stage
             int i = 0, t = kInf;
             for (int b = 0; b < Spad; b += 8) {
@@ -174,7 +195,7 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
             const int nF = nFB & 0xffff, nB = (int)((unsigned)nFB >> 16);
             const int hi = (int)((unsigned)nWx >> 16), nW = nWx & 0xffff;
             int ty;
-            if (PHASE == 2) ty = hi;
+            if (PHASE == 2) ty = hi & 3;
             else ty = nF < hi ? 0 : (headB <= (unsigned)t ? 1 : (headF <= (unsigned)t ? 0 : 2));   // priority B > F > W among those ready at t
             // the stage this op posts to: F(i,m) -> F(i+1,m), B(i,m) -> B(i-1,m); its fields are
             // read before this stage's own are written (another stage, or unused)
@@ -191,10 +212,7 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
             if (PHASE == 1 && live) plan[(long long)i * 3 * N + done] = (uint8_t)ty;
             nFB += ty == 0 ? 1 : (ty == 1 ? 0x10000 : 0);
             nWx += ty == 2;
-            if (PHASE == 2) {
-                const int next_ty = done + 1 < 3 * N ? plan[(long long)i * 3 * N + done + 1] : kNone;
-                nWx = (nWx & 0xffff) | next_ty << 16;
-            }
+            if (PHASE == 2) nWx = (nWx & 0xffff) | (int)(((unsigned)nWx >> 2) & 0xffff0000u);   // the window moves on by one op
             if (ty < 2) {
                 // consume: the queue's next entry becomes the head.  Entries posted so far = ops of
                 // that type the producing stage has started; stage 0's forwards and the last
@@ -237,6 +255,22 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
     }
 }
 
+// Plans from one byte per op to 2 bits per op, 16 ops per word, kNone behind the end of a row.
+__global__ void k_zb_pack(const uint8_t *plans, uint32_t *packed, long long rows, int N) {
+    const int words = packed_words(N);
+    const long long n = rows * words, stride = (long long)gridDim.x * blockDim.x;
+    for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += stride) {
+        const long long row = idx / words;
+        const int first = (int)(idx % words) * 16;
+        uint32_t v = 0;
+        for (int j = 0; j < 16; ++j) {
+            const int op = first + j;
+            v |= (uint32_t)(op < 3 * N ? plans[row * 3 * N + op] : kNone) << (2 * j);
+        }
+        packed[idx] = v;
+    }
+}
+
 __global__ void k_zb_reset(unsigned long long *counters) {
     if (threadIdx.x < 2) counters[threadIdx.x] = 0;
 }
@@ -245,7 +279,7 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct ZbPlan {
     unsigned threads;
-    size_t lds, off_counters, off_scratch, off_plans, total;
+    size_t lds, off_counters, off_scratch, off_plans, off_packed, total;
 };
 
 bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
@@ -268,6 +302,7 @@ bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
     p->off_counters = o; o += 256;
     p->off_scratch = o; o += align256((size_t)nt * per_thread);
     p->off_plans = o;   o += align256((size_t)C * S * 3 * N);
+    p->off_packed = o;  o += align256((size_t)C * S * packed_words(N) * 4);
     p->total = o;
     return true;
 }
@@ -316,6 +351,8 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
     a.out_makespan = out_makespan; a.out_bubble = out_bubble;
     a.scratch = (int *)((char *)workspace + p.off_scratch);
     a.plans = (uint8_t *)workspace + p.off_plans;
+    uint32_t *packed = (uint32_t *)((char *)workspace + p.off_packed);
+    a.packed = packed;
     unsigned long long *counters = (unsigned long long *)((char *)workspace + p.off_counters);
     hipLaunchKernelGGL(k_zb_reset, dim3(1), dim3(64), 0, st, counters);
     ADAPTRA_CHECK_LAUNCH();
@@ -323,6 +360,10 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
     if (plan_scenario < 0) return launch_zb<0>(a, a.K, p.threads, p.lds, st);
     int rc = launch_zb<1>(a, 1, p.threads, p.lds, st);        // one plan per candidate, under the plan scenario
     if (rc) return rc;
+    const long long rows = a.C * a.S, words = rows * packed_words(a.N);
+    hipLaunchKernelGGL(k_zb_pack, dim3((unsigned)adaptra_detail::blocks_for(words, 1 << 16)), dim3(adaptra_detail::kThreadsPerBlock), 0, st,
+                       a.plans, packed, rows, a.N);
+    ADAPTRA_CHECK_LAUNCH();
     a.next_unit = counters + 1;
     return launch_zb<2>(a, a.K, p.threads, p.lds, st);       // every pair replays its candidate's plan
 }
