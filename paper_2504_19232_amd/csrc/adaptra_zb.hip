@@ -71,7 +71,8 @@ struct ZbArgs {
     int *out_makespan, *out_bubble;
     int *scratch;                 // queues [S][2][N][threads]
     uint8_t *plans;               // [C][S][3N], op types in the order a stage ran them (written by PHASE 1)
-    const uint32_t *packed;       // [C][S][packed_words(N)], the same at 2 bits per op, kNone behind the end (read by PHASE 2)
+    const uint32_t *packed;       // [ceil(C/64)][S][packed_words(N)][64 candidates], the same at 2 bits per op, kNone
+                                  // behind the end (read by PHASE 2: the lanes of a wavefront read neighbouring words)
     unsigned threads;             // of the launch = stride of the queues
     unsigned long long *next_unit;   // work counter of this launch, zero when it starts
 };
@@ -132,7 +133,8 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
         const bool live = c_lane < a.C;
         const long long c = live ? c_lane : a.C - 1;
         uint8_t *const plan = a.plans + c * (long long)S * 3 * N;     // stage i's ops at plan + i * 3N
-        const uint32_t *const packed_row = a.packed + c * (long long)S * packed_words(N);
+        // word q of stage i of this lane's plan at packed_lane[(i * packed_words(N) + q) * 64]
+        const uint32_t *const packed_lane = a.packed + (c / kZbBlock) * (long long)S * packed_words(N) * kZbBlock + c % kZbBlock;
         for (int i = threadIdx.x; i < S; i += kZbBlock) {
             delay[i * 2] = i < S - 1 ? a.cf[(long long)i * a.K + k] : 0;
             delay[i * 2 + 1] = i > 0 ? a.cb[(long long)(i - 1) * a.K + k] : 0;
@@ -143,7 +145,7 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
         for (int i = 0; i < S; ++i) {
             int wi = a.w[(long long)i * a.C + c];
             wi = wi < 0 ? 0 : (wi > N - 1 ? N - 1 : wi);
-            const int hi = PHASE == 2 ? (int)(packed_row[(long long)i * packed_words(N)] & 0xffff) : wi + 1;   // x_i = w_i + 1 warm-up forwards
+            const int hi = PHASE == 2 ? (int)(packed_lane[(long long)i * packed_words(N) * kZbBlock] & 0xffff) : wi + 1;   // x_i = w_i + 1 warm-up forwards
             int *st = fld + i * kStage;
             st[fNFB * 64] = 0;
             st[fNWX * 64] = hi << 16;
@@ -164,8 +166,8 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
                     int *const st = fld + i * kStage;
                     const int nFB = st[fNFB * 64], nWx = st[fNWX * 64];
                     const int done = (nFB & 0xffff) + (int)((unsigned)nFB >> 16) + (nWx & 0xffff);
-                    const uint32_t *const at = packed_row + (long long)i * packed_words(N) + (done >> 4);
-                    const unsigned long long two = at[0] | (unsigned long long)at[1] << 32;
+                    const uint32_t *const at = packed_lane + ((long long)i * packed_words(N) + (done >> 4)) * kZbBlock;
+                    const unsigned long long two = at[0] | (unsigned long long)at[kZbBlock] << 32;
                     st[fNWX * 64] = (nWx & 0xffff) | (int)((unsigned)(two >> ((done & 15) * 2)) << 16);
                 }
             }
@@ -255,17 +257,21 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
     }
 }
 
-// Plans from one byte per op to 2 bits per op, 16 ops per word, kNone behind the end of a row.
-__global__ void k_zb_pack(const uint8_t *plans, uint32_t *packed, long long rows, int N) {
+// Plans from one byte per op, [C][S][3N], to 2 bits per op, 16 ops per word, kNone behind the
+// end of a stage's ops, laid out [chunk of 64 candidates][S][word][candidate].
+__global__ void k_zb_pack(const uint8_t *plans, uint32_t *packed, long long C, int S, int N) {
     const int words = packed_words(N);
-    const long long n = rows * words, stride = (long long)gridDim.x * blockDim.x;
+    const long long chunks = (C + kZbBlock - 1) / kZbBlock;
+    const long long n = chunks * S * words * kZbBlock, stride = (long long)gridDim.x * blockDim.x;
     for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += stride) {
-        const long long row = idx / words;
-        const int first = (int)(idx % words) * 16;
+        const int lane = (int)(idx % kZbBlock);
+        const int q = (int)(idx / kZbBlock % words);
+        const int i = (int)(idx / kZbBlock / words % S);
+        const long long c = idx / kZbBlock / words / S * kZbBlock + lane;
         uint32_t v = 0;
         for (int j = 0; j < 16; ++j) {
-            const int op = first + j;
-            v |= (uint32_t)(op < 3 * N ? plans[row * 3 * N + op] : kNone) << (2 * j);
+            const int op = q * 16 + j;
+            v |= (uint32_t)(c < C && op < 3 * N ? plans[(c * S + i) * 3 * N + op] : kNone) << (2 * j);
         }
         packed[idx] = v;
     }
@@ -302,7 +308,7 @@ bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
     p->off_counters = o; o += 256;
     p->off_scratch = o; o += align256((size_t)nt * per_thread);
     p->off_plans = o;   o += align256((size_t)C * S * 3 * N);
-    p->off_packed = o;  o += align256((size_t)C * S * packed_words(N) * 4);
+    p->off_packed = o;  o += align256((size_t)((C + kZbBlock - 1) / kZbBlock) * kZbBlock * S * packed_words(N) * 4);
     p->total = o;
     return true;
 }
@@ -360,9 +366,9 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
     if (plan_scenario < 0) return launch_zb<0>(a, a.K, p.threads, p.lds, st);
     int rc = launch_zb<1>(a, 1, p.threads, p.lds, st);        // one plan per candidate, under the plan scenario
     if (rc) return rc;
-    const long long rows = a.C * a.S, words = rows * packed_words(a.N);
+    const long long words = (a.C + kZbBlock - 1) / kZbBlock * kZbBlock * a.S * packed_words(a.N);
     hipLaunchKernelGGL(k_zb_pack, dim3((unsigned)adaptra_detail::blocks_for(words, 1 << 16)), dim3(adaptra_detail::kThreadsPerBlock), 0, st,
-                       a.plans, packed, rows, a.N);
+                       a.plans, packed, a.C, a.S, a.N);
     ADAPTRA_CHECK_LAUNCH();
     a.next_unit = counters + 1;
     return launch_zb<2>(a, a.K, p.threads, p.lds, st);       // every pair replays its candidate's plan
