@@ -51,9 +51,6 @@ namespace {
 
 constexpr int kInf = INT32_MAX;
 constexpr int kZbBlock = 64;          // one wavefront per block: LDS, not threads, bounds the occupancy
-constexpr int kZbFields = 4;          // per-stage block of LDS fields, each 64 lanes wide
-enum : int { fNFB = 0, fNWX = 1, fHeadF = 2, fHeadB = 3 };   // nFB = nF | nB << 16, nWx = nW | x << 16
-constexpr int kStage = kZbFields * 64;   // ints from one stage's block to the next
 constexpr int kNone = 3;              // "no op left" in a plan (types: 0 = F, 1 = B, 2 = W)
 // A head holds the ready time of the queue's first entry (>= 0), or, while the queue is empty,
 // the complement of the stage's busy-until time (< 0): read as unsigned, "empty" sorts after
@@ -61,6 +58,47 @@ constexpr int kNone = 3;              // "no op left" in a plan (types: 0 = F, 1
 // look at its next action again -- finds the receiver's busy-until time in the slot it fills.
 __device__ __forceinline__ unsigned empty_head(int busy) { return ~(unsigned)busy; }
 __device__ __forceinline__ bool is_empty(unsigned head) { return (int)head < 0; }
+
+// The cursors of a stage (ops of each type started so far) and one more number `hi`: the
+// warm-up quota x, or, when a plan is replayed, the types of the plan's next ops (2 bits each,
+// the next one lowest).  Wide form, any N: two words, nF | nB << 16 and nW | hi << 16.  Narrow
+// form, N <= 255 and never for a replay: one word, nF | nB << 8 | nW << 16 | hi << 24 -- one
+// LDS field less per stage, i.e. more resident wavefronts.  The heads follow the cursors in a
+// stage's block of fields.
+template <bool NARROW>
+struct Cursors {
+    static constexpr int kFields = NARROW ? 3 : 4;       // fields of a stage's block, each 64 lanes wide
+    static constexpr int kStage = kFields * 64;          // ints from one stage's block to the next
+    static constexpr int kHeadF = (NARROW ? 1 : 2) * 64, kHeadB = kHeadF + 64;   // offsets in the block
+    int a, b;
+    __device__ __forceinline__ static Cursors start(int hi) {
+        Cursors c;
+        c.a = NARROW ? hi << 24 : 0;
+        c.b = NARROW ? 0 : hi << 16;
+        return c;
+    }
+    __device__ __forceinline__ static Cursors load(const int *st) {
+        Cursors c;
+        c.a = st[0];
+        c.b = NARROW ? 0 : st[64];
+        return c;
+    }
+    __device__ __forceinline__ void store(int *st) const {
+        st[0] = a;
+        if (!NARROW) st[64] = b;
+    }
+    __device__ __forceinline__ int nF() const { return NARROW ? a & 0xff : a & 0xffff; }
+    __device__ __forceinline__ int nB() const { return NARROW ? (a >> 8) & 0xff : (int)((unsigned)a >> 16); }
+    __device__ __forceinline__ int nW() const { return NARROW ? (a >> 16) & 0xff : b & 0xffff; }
+    __device__ __forceinline__ int hi() const { return NARROW ? (int)((unsigned)a >> 24) : (int)((unsigned)b >> 16); }
+    __device__ __forceinline__ void started(int ty) {
+        if (NARROW) a += ty == 0 ? 1 : (ty == 1 ? 0x100 : 0x10000);
+        else { a += ty == 0 ? 1 : (ty == 1 ? 0x10000 : 0); b += ty == 2; }
+    }
+    // replay only (wide form): the window of coming ops
+    __device__ __forceinline__ void set_window(unsigned types) { b = (b & 0xffff) | (int)(types << 16); }
+    __device__ __forceinline__ void advance_window() { b = (b & 0xffff) | (int)(((unsigned)b >> 2) & 0xffff0000u); }
+};
 
 struct ZbArgs {
     int S, N;
@@ -83,30 +121,34 @@ __device__ __forceinline__ int imax2(int a, int b) { return a > b ? a : b; }
 // Words per stage of a packed plan: 16 ops each, and one more so that a window starting at any
 // op up to the end can be read as two consecutive words.
 __host__ __device__ inline int packed_words(int N) { return 3 * N / 16 + 2; }
-constexpr int kWindow = 8;            // ops of a plan held on chip per stage (2 bits each, the upper half of nWx)
+constexpr int kWindow = 8;            // ops of a plan held on chip per stage (16 bits of `hi`)
 
 // Next action of a stage from its own fields (Algorithm 3): the time it can act, or kInf if
-// nothing it may run has been posted yet.  When a plan is replayed (PHASE 2) the upper half of
-// nWx holds, instead of the quota, the types of the plan's next kWindow ops, the next one lowest.
-template <int PHASE>
-__device__ __forceinline__ int next_action(int busy, int nFB, int nWx, unsigned headF, unsigned headB) {
-    const int nF = nFB & 0xffff, nB = (int)((unsigned)nFB >> 16);
-    const unsigned headW = (nWx & 0xffff) < nB ? 0u : ~0u;       // ready since its backward finished
-    const int hi = PHASE == 2 ? (nWx >> 16) & 3 : (int)((unsigned)nWx >> 16);
+// nothing it may run has been posted yet.
+template <int PHASE, bool NARROW>
+__device__ __forceinline__ int next_action(int busy, const Cursors<NARROW> &c, unsigned headF, unsigned headB) {
+    const unsigned headW = c.nW() < c.nB() ? 0u : ~0u;           // ready since its backward finished
     unsigned first;
-    if (PHASE == 2) first = hi == 0 ? headF : (hi == 1 ? headB : (hi == 2 ? headW : ~0u));
-    else first = nF < hi ? headF : umin(headB, umin(headF, headW));   // warm-up: forwards only
+    if (PHASE == 2) {
+        const int ty = c.hi() & 3;
+        first = ty == 0 ? headF : (ty == 1 ? headB : (ty == 2 ? headW : ~0u));
+    } else {
+        first = c.nF() < c.hi() ? headF : umin(headB, umin(headF, headW));   // warm-up: forwards only
+    }
     return is_empty(first) ? kInf : imax2(busy, (int)first);
 }
 
 // PHASE 0: generate with the policy and write the outputs; 1: generate under the plan scenario
 // and record each stage's op types; 2: replay the recorded plans under every scenario.
-template <int PHASE>
+template <int PHASE, bool NARROW>
 __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
+    static_assert(!(PHASE == 2 && NARROW), "a replay keeps its window of coming ops in the wide form");
+    typedef Cursors<NARROW> Cur;
+    constexpr int kStage = Cur::kStage;
     extern __shared__ int zb_lds[];
     const int S = a.S, N = a.N, Spad = (S + 7) & ~7;
     int *const act = zb_lds + threadIdx.x;                        // [Spad][64]
-    int *const fld = zb_lds + Spad * 64 + threadIdx.x;            // [S][kZbFields][64]
+    int *const fld = zb_lds + Spad * 64 + threadIdx.x;            // [S][Cur::kFields][64]
     int *const dur = zb_lds + Spad * 64 + S * kStage;             // [S][4]: t_f, t_b, t_w, 0
     int *const delay = dur + 4 * S;                               // [S][2]: forward delay of link i -> i+1, backward delay of link i-1 <- i
     for (int i = threadIdx.x; i < 4 * S; i += kZbBlock) {
@@ -145,13 +187,14 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
         for (int i = 0; i < S; ++i) {
             int wi = a.w[(long long)i * a.C + c];
             wi = wi < 0 ? 0 : (wi > N - 1 ? N - 1 : wi);
-            const int hi = PHASE == 2 ? (int)(packed_lane[(long long)i * packed_words(N) * kZbBlock] & 0xffff) : wi + 1;   // x_i = w_i + 1 warm-up forwards
+            // x_i = w_i + 1 warm-up forwards; a replay starts with the first ops of its plan
+            const Cur cur = Cur::start(PHASE == 2 ? (int)(packed_lane[(long long)i * packed_words(N) * kZbBlock] & 0xffff) : wi + 1);
+            const unsigned headF = i == 0 ? 0u : empty_head(0), headB = empty_head(0);
             int *st = fld + i * kStage;
-            st[fNFB * 64] = 0;
-            st[fNWX * 64] = hi << 16;
-            st[fHeadF * 64] = (int)(i == 0 ? 0u : empty_head(0));
-            st[fHeadB * 64] = (int)empty_head(0);
-            act[i * 64] = next_action<PHASE>(0, 0, hi << 16, i == 0 ? 0u : empty_head(0), empty_head(0));
+            cur.store(st);
+            st[Cur::kHeadF] = (int)headF;
+            st[Cur::kHeadB] = (int)headB;
+            act[i * 64] = next_action<PHASE>(0, cur, headF, headB);
         }
 
         const int total = 3 * S * N;
@@ -164,11 +207,12 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
                 // stage does not change by this.
                 for (int i = 0; i < S; ++i) {
                     int *const st = fld + i * kStage;
-                    const int nFB = st[fNFB * 64], nWx = st[fNWX * 64];
-                    const int done = (nFB & 0xffff) + (int)((unsigned)nFB >> 16) + (nWx & 0xffff);
+                    Cur cur = Cur::load(st);
+                    const int done = cur.nF() + cur.nB() + cur.nW();
                     const uint32_t *const at = packed_lane + ((long long)i * packed_words(N) + (done >> 4)) * kZbBlock;
                     const unsigned long long two = at[0] | (unsigned long long)at[kZbBlock] << 32;
-                    st[fNWX * 64] = (nWx & 0xffff) | (int)((unsigned)(two >> ((done & 15) * 2)) << 16);
+                    cur.set_window((unsigned)(two >> ((done & 15) * 2)));
+                    cur.store(st);
                 }
             }
             // the stage whose next action is earliest, ties to the lower stage
@@ -188,59 +232,57 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
             // producing stages.
             int *const st = fld + i * kStage;
             const bool first = i == 0, last = i == S - 1;
-            int nFB = st[fNFB * 64], nWx = st[fNWX * 64];
-            unsigned headF = (unsigned)st[fHeadF * 64], headB = (unsigned)st[fHeadB * 64];
+            Cur cur = Cur::load(st);
+            unsigned headF = (unsigned)st[Cur::kHeadF], headB = (unsigned)st[Cur::kHeadB];
             const int4 dur_i = *reinterpret_cast<const int4 *>(dur + i * 4);
             const int2 delay_i = *reinterpret_cast<const int2 *>(delay + i * 2);
-            const int nFB_prev = *(first ? st + fNFB * 64 : st - kStage + fNFB * 64);
-            const int nFB_next = *(last ? st + fNFB * 64 : st + kStage + fNFB * 64);
-            const int nF = nFB & 0xffff, nB = (int)((unsigned)nFB >> 16);
-            const int hi = (int)((unsigned)nWx >> 16), nW = nWx & 0xffff;
+            Cur prev, next;                                     // only their first word is needed
+            prev.a = *(first ? st : st - kStage);
+            next.a = *(last ? st : st + kStage);
+            prev.b = next.b = 0;
+            const int nF = cur.nF(), nB = cur.nB(), nW = cur.nW();
             int ty;
-            if (PHASE == 2) ty = hi & 3;
-            else ty = nF < hi ? 0 : (headB <= (unsigned)t ? 1 : (headF <= (unsigned)t ? 0 : 2));   // priority B > F > W among those ready at t
+            if (PHASE == 2) ty = cur.hi() & 3;
+            else ty = nF < cur.hi() ? 0 : (headB <= (unsigned)t ? 1 : (headF <= (unsigned)t ? 0 : 2));   // priority B > F > W among those ready at t
             // the stage this op posts to: F(i,m) -> F(i+1,m), B(i,m) -> B(i-1,m); its fields are
             // read before this stage's own are written (another stage, or unused)
             const int j = ty == 0 ? i + 1 : i - 1;
             const bool posts = ty < 2 && j >= 0 && j < S;
             int *const sj = posts ? (ty == 0 ? st + kStage : st - kStage) : st;
-            const int nFB_j = sj[fNFB * 64], nWx_j = sj[fNWX * 64];
-            unsigned headF_j = (unsigned)sj[fHeadF * 64], headB_j = (unsigned)sj[fHeadB * 64];
+            const Cur cur_j = Cur::load(sj);
+            unsigned headF_j = (unsigned)sj[Cur::kHeadF], headB_j = (unsigned)sj[Cur::kHeadB];
 
             const int m = ty == 0 ? nF : (ty == 1 ? nB : nW);
             const int done = nF + nB + nW;
             const int fin = t + (ty == 0 ? dur_i.x : (ty == 1 ? dur_i.y : dur_i.z));
             makespan = imax2(makespan, fin);
             if (PHASE == 1 && live) plan[(long long)i * 3 * N + done] = (uint8_t)ty;
-            nFB += ty == 0 ? 1 : (ty == 1 ? 0x10000 : 0);
-            nWx += ty == 2;
-            if (PHASE == 2) nWx = (nWx & 0xffff) | (int)(((unsigned)nWx >> 2) & 0xffff0000u);   // the window moves on by one op
+            cur.started(ty);
+            if (PHASE == 2) cur.advance_window();
             if (ty < 2) {
                 // consume: the queue's next entry becomes the head.  Entries posted so far = ops of
                 // that type the producing stage has started; stage 0's forwards and the last
                 // stage's backwards come from no other stage and are ready whenever it is idle.
                 const bool own = ty == 0 ? first : last;
-                const int posted = ty == 0 ? (first ? N : (nFB_prev & 0xffff))
-                                           : (last ? (nFB & 0xffff) : (int)((unsigned)nFB_next >> 16));
-                unsigned next = ~0u;
-                if (m + 1 < posted) next = own ? 0u : (unsigned)queue[(unsigned long long)(unsigned)((i * 2 + ty) * N + m + 1) * nt];
-                if (ty == 0) headF = next; else headB = next;
+                const int posted = ty == 0 ? (first ? N : prev.nF()) : (last ? cur.nF() : next.nB());
+                unsigned head = ~0u;
+                if (m + 1 < posted) head = own ? 0u : (unsigned)queue[(unsigned long long)(unsigned)((i * 2 + ty) * N + m + 1) * nt];
+                if (ty == 0) headF = head; else headB = head;
             }
             if (is_empty(headF)) headF = empty_head(fin);       // busy until fin from now on
             if (is_empty(headB)) headB = empty_head(fin);
             if (last && ty == 0) headB = 0;                     // its own forward makes a backward available
-            st[fNFB * 64] = nFB;
-            st[fNWX * 64] = nWx;
-            st[fHeadF * 64] = (int)headF;
-            st[fHeadB * 64] = (int)headB;
-            act[i * 64] = next_action<PHASE>(fin, nFB, nWx, headF, headB);
+            cur.store(st);
+            st[Cur::kHeadF] = (int)headF;
+            st[Cur::kHeadB] = (int)headB;
+            act[i * 64] = next_action<PHASE>(fin, cur, headF, headB);
             if (posts) {
                 const int r = fin + (ty == 0 ? delay_i.x : delay_i.y);
                 const unsigned slot = ty == 0 ? headF_j : headB_j;
                 if (is_empty(slot)) {                           // r becomes the head: the receiver may act earlier
                     if (ty == 0) headF_j = (unsigned)r; else headB_j = (unsigned)r;
-                    sj[(fHeadF + ty) * 64] = r;
-                    act[j * 64] = next_action<PHASE>((int)~slot, nFB_j, nWx_j, headF_j, headB_j);
+                    sj[ty == 0 ? Cur::kHeadF : Cur::kHeadB] = r;
+                    act[j * 64] = next_action<PHASE>((int)~slot, cur_j, headF_j, headB_j);
                 } else {
                     queue[(unsigned long long)(unsigned)((j * 2 + ty) * N + m) * nt] = r;
                 }
@@ -284,44 +326,53 @@ __global__ void k_zb_reset(unsigned long long *counters) {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct ZbPlan {
-    unsigned threads;
-    size_t lds, off_counters, off_scratch, off_plans, off_packed, total;
+    bool narrow;                  // generation (PHASE 0, 1) in the one-word form of the cursors
+    unsigned threads, threads_replay;
+    size_t lds, lds_replay, off_counters, off_scratch, off_plans, off_packed, total;
 };
 
-bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
-    if (S < 1 || S > ADAPTRA_MAX_STAGES || N < 1 || N > ADAPTRA_MAX_MICROBATCHES) return false;
-    if (C < 1 || C > INT32_MAX || K < 1 || K > INT32_MAX) return false;
-    // Enough threads to fill the chip at the occupancy the LDS state allows (at most 160 KiB
-    // per CU, 32 wavefronts per CU, 256 CUs), within about 2 GiB of queue memory.
-    const long long per_thread = 2ll * S * N * 4;
-    const int Spad = (S + 7) & ~7;
-    p->lds = ((size_t)Spad * 64 + (size_t)S * kStage + 6 * (size_t)S) * 4;
-    long long waves_per_cu = (160ll << 10) / (long long)p->lds;
+// Enough threads to fill the chip at the occupancy the LDS state allows (at most 160 KiB per CU,
+// 32 wavefronts per CU, 256 CUs), within about 2 GiB of queue memory.
+unsigned threads_for(size_t lds, long long per_thread) {
+    long long waves_per_cu = (160ll << 10) / (long long)lds;
     if (waves_per_cu > 32) waves_per_cu = 32;
-    if (waves_per_cu < 1) return false;
     long long nt = 256 * waves_per_cu * kZbBlock;
     const long long cap = (2048ll << 20) / per_thread / kZbBlock * kZbBlock;
     if (nt > cap) nt = cap;
     if (nt < 16 * kZbBlock) nt = 16 * kZbBlock;
-    p->threads = (unsigned)nt;
+    return (unsigned)nt;
+}
+
+bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
+    if (S < 1 || S > ADAPTRA_MAX_STAGES || N < 1 || N > ADAPTRA_MAX_MICROBATCHES) return false;
+    if (C < 1 || C > INT32_MAX || K < 1 || K > INT32_MAX) return false;
+    const long long per_thread = 2ll * S * N * 4;
+    const int Spad = (S + 7) & ~7;
+    auto lds_bytes = [&](int stage_ints) { return ((size_t)Spad * 64 + (size_t)S * stage_ints + 6 * (size_t)S + 2) * 4; };
+    p->narrow = N <= 255;
+    p->lds = lds_bytes(p->narrow ? Cursors<true>::kStage : Cursors<false>::kStage);
+    p->lds_replay = lds_bytes(Cursors<false>::kStage);
+    if (p->lds_replay > (160u << 10)) return false;
+    p->threads = threads_for(p->lds, per_thread);
+    p->threads_replay = threads_for(p->lds_replay, per_thread);
     size_t o = 0;
     p->off_counters = o; o += 256;
-    p->off_scratch = o; o += align256((size_t)nt * per_thread);
+    p->off_scratch = o; o += align256((size_t)p->threads * per_thread);
     p->off_plans = o;   o += align256((size_t)C * S * 3 * N);
     p->off_packed = o;  o += align256((size_t)((C + kZbBlock - 1) / kZbBlock) * kZbBlock * S * packed_words(N) * 4);
     p->total = o;
     return true;
 }
 
-template <int PHASE>
+template <int PHASE, bool NARROW>
 int launch_zb(ZbArgs a, long long scenarios, unsigned full, size_t lds, hipStream_t st) {
     if (lds > 48 * 1024) {                                   // above the default dynamic-LDS limit
-        hipError_t e = hipFuncSetAttribute((const void *)k_zb<PHASE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute((const void *)k_zb<PHASE, NARROW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return adaptra_detail::hip_fail(e);
     }
     const long long units = (a.C + kZbBlock - 1) / kZbBlock * scenarios;   // one wavefront each, at most `full` threads at a time
     a.threads = (unsigned)(units < (long long)(full / kZbBlock) ? units : (long long)(full / kZbBlock)) * kZbBlock;
-    hipLaunchKernelGGL(k_zb<PHASE>, dim3(a.threads / kZbBlock), dim3(kZbBlock), lds, st, a);
+    hipLaunchKernelGGL((k_zb<PHASE, NARROW>), dim3(a.threads / kZbBlock), dim3(kZbBlock), lds, st, a);
     ADAPTRA_CHECK_LAUNCH();
     return ADAPTRA_OK;
 }
@@ -363,15 +414,17 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
     hipLaunchKernelGGL(k_zb_reset, dim3(1), dim3(64), 0, st, counters);
     ADAPTRA_CHECK_LAUNCH();
     a.next_unit = counters;
-    if (plan_scenario < 0) return launch_zb<0>(a, a.K, p.threads, p.lds, st);
-    int rc = launch_zb<1>(a, 1, p.threads, p.lds, st);        // one plan per candidate, under the plan scenario
+    if (plan_scenario < 0)
+        return p.narrow ? launch_zb<0, true>(a, a.K, p.threads, p.lds, st) : launch_zb<0, false>(a, a.K, p.threads, p.lds, st);
+    // one plan per candidate, under the plan scenario
+    int rc = p.narrow ? launch_zb<1, true>(a, 1, p.threads, p.lds, st) : launch_zb<1, false>(a, 1, p.threads, p.lds, st);
     if (rc) return rc;
     const long long words = (a.C + kZbBlock - 1) / kZbBlock * kZbBlock * a.S * packed_words(a.N);
     hipLaunchKernelGGL(k_zb_pack, dim3((unsigned)adaptra_detail::blocks_for(words, 1 << 16)), dim3(adaptra_detail::kThreadsPerBlock), 0, st,
                        a.plans, packed, a.C, a.S, a.N);
     ADAPTRA_CHECK_LAUNCH();
     a.next_unit = counters + 1;
-    return launch_zb<2>(a, a.K, p.threads, p.lds, st);       // every pair replays its candidate's plan
+    return launch_zb<2, false>(a, a.K, p.threads_replay, p.lds_replay, st);   // every pair replays its candidate's plan
 }
 
 }  // extern "C"

@@ -455,7 +455,10 @@ def test_zb_paper_example_on_gpu(lib):
 ZB_CASES = [(1, 1, 1, 3, 2), (2, 2, 3, 9, 5), (3, 4, 8, 40, 21), (4, 8, 16, 70, 33), (5, 5, 7, 300, 4),
             (6, 16, 12, 20, 10), (7, 3, 40, 10, 64),
             (8, 32, 10, 6, 70),           # per-wavefront state above the default LDS limit
-            (9, 64, 6, 150, 130)]         # the largest S; more pairs than resident threads
+            (9, 64, 6, 150, 130),         # the largest S; more pairs than resident threads
+            (10, 2, 255, 70, 3),          # the most micro-batches the one-word form of the cursors takes
+            (11, 3, 256, 30, 4),          # the fewest that need the two-word form
+            (12, 2, 300, 20, 6)]
 
 
 @pytest.mark.parametrize("seed_,S,N,C,K", ZB_CASES, ids=[f"S{c[1]}_N{c[2]}_C{c[3]}_K{c[4]}" for c in ZB_CASES])
