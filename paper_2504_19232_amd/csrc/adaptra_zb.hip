@@ -109,8 +109,8 @@ struct ZbArgs {
     int *out_makespan, *out_bubble;
     int *scratch;                 // queues [S][2][N][threads]
     uint8_t *plans;               // [C][S][3N], op types in the order a stage ran them (written by PHASE 1)
-    const uint32_t *packed;       // [ceil(C/64)][S][packed_words(N)][64 candidates], the same at 2 bits per op, kNone
-                                  // behind the end (read by PHASE 2: the lanes of a wavefront read neighbouring words)
+    const uint32_t *packed;       // [ceil(C/64)][S][packed_words(N)][64 candidates], the same at 2 bits per op (see
+                                  // packed_words), read by PHASE 2: the lanes of a wavefront read neighbouring words
     unsigned threads;             // of the launch = stride of the queues
     unsigned long long *next_unit;   // work counter of this launch, zero when it starts
 };
@@ -118,9 +118,10 @@ struct ZbArgs {
 __device__ __forceinline__ unsigned umin(unsigned a, unsigned b) { return a < b ? a : b; }
 __device__ __forceinline__ int imax2(int a, int b) { return a > b ? a : b; }
 
-// Words per stage of a packed plan: 16 ops each, and one more so that a window starting at any
-// op up to the end can be read as two consecutive words.
-__host__ __device__ inline int packed_words(int N) { return 3 * N / 16 + 2; }
+// A packed plan holds 16 ops per word, 2 bits each, and consecutive words overlap by half: word
+// q starts at op 8 q.  A window of kWindow = 8 ops that starts at any op therefore lies inside
+// ONE word, (op / 8), at bit 2 (op % 8).  Words per stage, including the window at the very end:
+__host__ __device__ inline int packed_words(int N) { return 3 * N / 8 + 1; }
 constexpr int kWindow = 8;            // ops of a plan held on chip per stage (16 bits of `hi`)
 
 // Next action of a stage from its own fields (Algorithm 3): the time it can act, or kInf if
@@ -209,9 +210,8 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
                     int *const st = fld + i * kStage;
                     Cur cur = Cur::load(st);
                     const int done = cur.nF() + cur.nB() + cur.nW();
-                    const uint32_t *const at = packed_lane + ((long long)i * packed_words(N) + (done >> 4)) * kZbBlock;
-                    const unsigned long long two = at[0] | (unsigned long long)at[kZbBlock] << 32;
-                    cur.set_window((unsigned)(two >> ((done & 15) * 2)));
+                    const uint32_t word = packed_lane[((long long)i * packed_words(N) + (done >> 3)) * kZbBlock];
+                    cur.set_window(word >> ((done & 7) * 2));
                     cur.store(st);
                 }
             }
@@ -299,8 +299,8 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
     }
 }
 
-// Plans from one byte per op, [C][S][3N], to 2 bits per op, 16 ops per word, kNone behind the
-// end of a stage's ops, laid out [chunk of 64 candidates][S][word][candidate].
+// Plans from one byte per op, [C][S][3N], to 2 bits per op, 16 ops per word from op 8 q on, kNone
+// behind the end of a stage's ops, laid out [chunk of 64 candidates][S][word][candidate].
 __global__ void k_zb_pack(const uint8_t *plans, uint32_t *packed, long long C, int S, int N) {
     const int words = packed_words(N);
     const long long chunks = (C + kZbBlock - 1) / kZbBlock;
@@ -312,7 +312,7 @@ __global__ void k_zb_pack(const uint8_t *plans, uint32_t *packed, long long C, i
         const long long c = idx / kZbBlock / words / S * kZbBlock + lane;
         uint32_t v = 0;
         for (int j = 0; j < 16; ++j) {
-            const int op = q * 16 + j;
+            const int op = q * 8 + j;
             v |= (uint32_t)(c < C && op < 3 * N ? plans[(c * S + i) * 3 * N + op] : kNone) << (2 * j);
         }
         packed[idx] = v;

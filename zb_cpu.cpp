@@ -9,6 +9,7 @@
 #define __global__
 #define __forceinline__ inline
 #define __launch_bounds__(x)
+#define __host__
 #define __shared__ static
 #define atomicAdd(p, v) __atomic_fetch_add(p, v, __ATOMIC_SEQ_CST)
 static pthread_barrier_t bar;
@@ -18,16 +19,13 @@ static pthread_barrier_t bar;
 struct Idx { unsigned x; };
 struct int4 { int x, y, z, w; };
 struct int2 { int x, y; };
-static Idx blockIdx, gridDim;
+static Idx blockIdx, gridDim, blockDim;
 static thread_local Idx threadIdx;
 static int *zb_lds;
 
 
 constexpr int kInf = INT32_MAX;
 constexpr int kZbBlock = 64;          // one wavefront per block: LDS, not threads, bounds the occupancy
-constexpr int kZbFields = 4;          // per-stage block of LDS fields, each 64 lanes wide
-enum : int { fNFB = 0, fNWX = 1, fHeadF = 2, fHeadB = 3 };   // nFB = nF | nB << 16, nWx = nW | x << 16
-constexpr int kStage = kZbFields * 64;   // ints from one stage's block to the next
 constexpr int kNone = 3;              // "no op left" in a plan (types: 0 = F, 1 = B, 2 = W)
 // A head holds the ready time of the queue's first entry (>= 0), or, while the queue is empty,
 // the complement of the stage's busy-until time (< 0): read as unsigned, "empty" sorts after
@@ -35,6 +33,47 @@ constexpr int kNone = 3;              // "no op left" in a plan (types: 0 = F, 1
 // look at its next action again -- finds the receiver's busy-until time in the slot it fills.
 __device__ __forceinline__ unsigned empty_head(int busy) { return ~(unsigned)busy; }
 __device__ __forceinline__ bool is_empty(unsigned head) { return (int)head < 0; }
+
+// The cursors of a stage (ops of each type started so far) and one more number `hi`: the
+// warm-up quota x, or, when a plan is replayed, the types of the plan's next ops (2 bits each,
+// the next one lowest).  Wide form, any N: two words, nF | nB << 16 and nW | hi << 16.  Narrow
+// form, N <= 255 and never for a replay: one word, nF | nB << 8 | nW << 16 | hi << 24 -- one
+// LDS field less per stage, i.e. more resident wavefronts.  The heads follow the cursors in a
+// stage's block of fields.
+template <bool NARROW>
+struct Cursors {
+    static constexpr int kFields = NARROW ? 3 : 4;       // fields of a stage's block, each 64 lanes wide
+    static constexpr int kStage = kFields * 64;          // ints from one stage's block to the next
+    static constexpr int kHeadF = (NARROW ? 1 : 2) * 64, kHeadB = kHeadF + 64;   // offsets in the block
+    int a, b;
+    __device__ __forceinline__ static Cursors start(int hi) {
+        Cursors c;
+        c.a = NARROW ? hi << 24 : 0;
+        c.b = NARROW ? 0 : hi << 16;
+        return c;
+    }
+    __device__ __forceinline__ static Cursors load(const int *st) {
+        Cursors c;
+        c.a = st[0];
+        c.b = NARROW ? 0 : st[64];
+        return c;
+    }
+    __device__ __forceinline__ void store(int *st) const {
+        st[0] = a;
+        if (!NARROW) st[64] = b;
+    }
+    __device__ __forceinline__ int nF() const { return NARROW ? a & 0xff : a & 0xffff; }
+    __device__ __forceinline__ int nB() const { return NARROW ? (a >> 8) & 0xff : (int)((unsigned)a >> 16); }
+    __device__ __forceinline__ int nW() const { return NARROW ? (a >> 16) & 0xff : b & 0xffff; }
+    __device__ __forceinline__ int hi() const { return NARROW ? (int)((unsigned)a >> 24) : (int)((unsigned)b >> 16); }
+    __device__ __forceinline__ void started(int ty) {
+        if (NARROW) a += ty == 0 ? 1 : (ty == 1 ? 0x100 : 0x10000);
+        else { a += ty == 0 ? 1 : (ty == 1 ? 0x10000 : 0); b += ty == 2; }
+    }
+    // replay only (wide form): the window of coming ops
+    __device__ __forceinline__ void set_window(unsigned types) { b = (b & 0xffff) | (int)(types << 16); }
+    __device__ __forceinline__ void advance_window() { b = (b & 0xffff) | (int)(((unsigned)b >> 2) & 0xffff0000u); }
+};
 
 struct ZbArgs {
     int S, N;
@@ -44,7 +83,9 @@ struct ZbArgs {
     long long plan_scenario;      // -1: every pair generates under its own scenario
     int *out_makespan, *out_bubble;
     int *scratch;                 // queues [S][2][N][threads]
-    uint8_t *plans;               // [C][S][3N], op types in the order a stage ran them
+    uint8_t *plans;               // [C][S][3N], op types in the order a stage ran them (written by PHASE 1)
+    const uint32_t *packed;       // [ceil(C/64)][S][packed_words(N)][64 candidates], the same at 2 bits per op (see
+                                  // packed_words), read by PHASE 2: the lanes of a wavefront read neighbouring words
     unsigned threads;             // of the launch = stride of the queues
     unsigned long long *next_unit;   // work counter of this launch, zero when it starts
 };
@@ -52,27 +93,37 @@ struct ZbArgs {
 __device__ __forceinline__ unsigned umin(unsigned a, unsigned b) { return a < b ? a : b; }
 __device__ __forceinline__ int imax2(int a, int b) { return a > b ? a : b; }
 
+// A packed plan holds 16 ops per word, 2 bits each, and consecutive words overlap by half: word
+// q starts at op 8 q.  A window of kWindow = 8 ops that starts at any op therefore lies inside
+// ONE word, (op / 8), at bit 2 (op % 8).  Words per stage, including the window at the very end:
+__host__ __device__ inline int packed_words(int N) { return 3 * N / 8 + 1; }
+constexpr int kWindow = 8;            // ops of a plan held on chip per stage (16 bits of `hi`)
+
 // Next action of a stage from its own fields (Algorithm 3): the time it can act, or kInf if
-// nothing it may run has been posted yet.  When a plan is replayed (PHASE 2) the upper half of
-// nWx holds the type of the plan's next op instead of the quota.
-template <int PHASE>
-__device__ __forceinline__ int next_action(int busy, int nFB, int nWx, unsigned headF, unsigned headB) {
-    const int nF = nFB & 0xffff, nB = (int)((unsigned)nFB >> 16);
-    const unsigned headW = (nWx & 0xffff) < nB ? 0u : ~0u;       // ready since its backward finished
-    const int hi = (int)((unsigned)nWx >> 16);
+// nothing it may run has been posted yet.
+template <int PHASE, bool NARROW>
+__device__ __forceinline__ int next_action(int busy, const Cursors<NARROW> &c, unsigned headF, unsigned headB) {
+    const unsigned headW = c.nW() < c.nB() ? 0u : ~0u;           // ready since its backward finished
     unsigned first;
-    if (PHASE == 2) first = hi == 0 ? headF : (hi == 1 ? headB : (hi == 2 ? headW : ~0u));
-    else first = nF < hi ? headF : umin(headB, umin(headF, headW));   // warm-up: forwards only
+    if (PHASE == 2) {
+        const int ty = c.hi() & 3;
+        first = ty == 0 ? headF : (ty == 1 ? headB : (ty == 2 ? headW : ~0u));
+    } else {
+        first = c.nF() < c.hi() ? headF : umin(headB, umin(headF, headW));   // warm-up: forwards only
+    }
     return is_empty(first) ? kInf : imax2(busy, (int)first);
 }
 
 // PHASE 0: generate with the policy and write the outputs; 1: generate under the plan scenario
 // and record each stage's op types; 2: replay the recorded plans under every scenario.
-template <int PHASE>
+template <int PHASE, bool NARROW>
 __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
+    static_assert(!(PHASE == 2 && NARROW), "a replay keeps its window of coming ops in the wide form");
+    typedef Cursors<NARROW> Cur;
+    constexpr int kStage = Cur::kStage;
     const int S = a.S, N = a.N, Spad = (S + 7) & ~7;
     int *const act = zb_lds + threadIdx.x;                        // [Spad][64]
-    int *const fld = zb_lds + Spad * 64 + threadIdx.x;            // [S][kZbFields][64]
+    int *const fld = zb_lds + Spad * 64 + threadIdx.x;            // [S][Cur::kFields][64]
     int *const dur = zb_lds + Spad * 64 + S * kStage;             // [S][4]: t_f, t_b, t_w, 0
     int *const delay = dur + 4 * S;                               // [S][2]: forward delay of link i -> i+1, backward delay of link i-1 <- i
     for (int i = threadIdx.x; i < 4 * S; i += kZbBlock) {
@@ -99,6 +150,8 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
         const bool live = c_lane < a.C;
         const long long c = live ? c_lane : a.C - 1;
         uint8_t *const plan = a.plans + c * (long long)S * 3 * N;     // stage i's ops at plan + i * 3N
+        // word q of stage i of this lane's plan at packed_lane[(i * packed_words(N) + q) * 64]
+        const uint32_t *const packed_lane = a.packed + (c / kZbBlock) * (long long)S * packed_words(N) * kZbBlock + c % kZbBlock;
         for (int i = threadIdx.x; i < S; i += kZbBlock) {
             delay[i * 2] = i < S - 1 ? a.cf[(long long)i * a.K + k] : 0;
             delay[i * 2 + 1] = i > 0 ? a.cb[(long long)(i - 1) * a.K + k] : 0;
@@ -109,18 +162,33 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
         for (int i = 0; i < S; ++i) {
             int wi = a.w[(long long)i * a.C + c];
             wi = wi < 0 ? 0 : (wi > N - 1 ? N - 1 : wi);
-            const int hi = PHASE == 2 ? plan[(long long)i * 3 * N] : wi + 1;   // x_i = w_i + 1 warm-up forwards
+            // x_i = w_i + 1 warm-up forwards; a replay starts with the first ops of its plan
+            const Cur cur = Cur::start(PHASE == 2 ? (int)(packed_lane[(long long)i * packed_words(N) * kZbBlock] & 0xffff) : wi + 1);
+            const unsigned headF = i == 0 ? 0u : empty_head(0), headB = empty_head(0);
             int *st = fld + i * kStage;
-            st[fNFB * 64] = 0;
-            st[fNWX * 64] = hi << 16;
-            st[fHeadF * 64] = (int)(i == 0 ? 0u : empty_head(0));
-            st[fHeadB * 64] = (int)empty_head(0);
-            act[i * 64] = next_action<PHASE>(0, 0, hi << 16, i == 0 ? 0u : empty_head(0), empty_head(0));
+            cur.store(st);
+            st[Cur::kHeadF] = (int)headF;
+            st[Cur::kHeadB] = (int)headB;
+            act[i * 64] = next_action<PHASE>(0, cur, headF, headB);
         }
 
         const int total = 3 * S * N;
         int makespan = 0;
         for (int step = 0; step < total; ++step) {
+            if (PHASE == 2 && step % (kWindow - 1) == 0 && step > 0) {
+                // A stage runs at most kWindow - 1 ops in as many steps, so its window never runs
+                // out of a next op: re-reading every stage's window here, for all lanes at once,
+                // keeps the plan's memory latency out of the steps in between.  The next op of a
+                // stage does not change by this.
+                for (int i = 0; i < S; ++i) {
+                    int *const st = fld + i * kStage;
+                    Cur cur = Cur::load(st);
+                    const int done = cur.nF() + cur.nB() + cur.nW();
+                    const uint32_t word = packed_lane[((long long)i * packed_words(N) + (done >> 3)) * kZbBlock];
+                    cur.set_window(word >> ((done & 7) * 2));
+                    cur.store(st);
+                }
+            }
             // the stage whose next action is earliest, ties to the lower stage
             int i = 0, t = kInf;
             for (int b = 0; b < Spad; b += 8) {
@@ -138,62 +206,57 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
             // producing stages.
             int *const st = fld + i * kStage;
             const bool first = i == 0, last = i == S - 1;
-            int nFB = st[fNFB * 64], nWx = st[fNWX * 64];
-            unsigned headF = (unsigned)st[fHeadF * 64], headB = (unsigned)st[fHeadB * 64];
+            Cur cur = Cur::load(st);
+            unsigned headF = (unsigned)st[Cur::kHeadF], headB = (unsigned)st[Cur::kHeadB];
             const int4 dur_i = *reinterpret_cast<const int4 *>(dur + i * 4);
             const int2 delay_i = *reinterpret_cast<const int2 *>(delay + i * 2);
-            const int nFB_prev = *(first ? st + fNFB * 64 : st - kStage + fNFB * 64);
-            const int nFB_next = *(last ? st + fNFB * 64 : st + kStage + fNFB * 64);
-            const int nF = nFB & 0xffff, nB = (int)((unsigned)nFB >> 16);
-            const int hi = (int)((unsigned)nWx >> 16), nW = nWx & 0xffff;
+            Cur prev, next;                                     // only their first word is needed
+            prev.a = *(first ? st : st - kStage);
+            next.a = *(last ? st : st + kStage);
+            prev.b = next.b = 0;
+            const int nF = cur.nF(), nB = cur.nB(), nW = cur.nW();
             int ty;
-            if (PHASE == 2) ty = hi;
-            else ty = nF < hi ? 0 : (headB <= (unsigned)t ? 1 : (headF <= (unsigned)t ? 0 : 2));   // priority B > F > W among those ready at t
+            if (PHASE == 2) ty = cur.hi() & 3;
+            else ty = nF < cur.hi() ? 0 : (headB <= (unsigned)t ? 1 : (headF <= (unsigned)t ? 0 : 2));   // priority B > F > W among those ready at t
             // the stage this op posts to: F(i,m) -> F(i+1,m), B(i,m) -> B(i-1,m); its fields are
             // read before this stage's own are written (another stage, or unused)
             const int j = ty == 0 ? i + 1 : i - 1;
             const bool posts = ty < 2 && j >= 0 && j < S;
             int *const sj = posts ? (ty == 0 ? st + kStage : st - kStage) : st;
-            const int nFB_j = sj[fNFB * 64], nWx_j = sj[fNWX * 64];
-            unsigned headF_j = (unsigned)sj[fHeadF * 64], headB_j = (unsigned)sj[fHeadB * 64];
+            const Cur cur_j = Cur::load(sj);
+            unsigned headF_j = (unsigned)sj[Cur::kHeadF], headB_j = (unsigned)sj[Cur::kHeadB];
 
             const int m = ty == 0 ? nF : (ty == 1 ? nB : nW);
             const int done = nF + nB + nW;
             const int fin = t + (ty == 0 ? dur_i.x : (ty == 1 ? dur_i.y : dur_i.z));
             makespan = imax2(makespan, fin);
             if (PHASE == 1 && live) plan[(long long)i * 3 * N + done] = (uint8_t)ty;
-            nFB += ty == 0 ? 1 : (ty == 1 ? 0x10000 : 0);
-            nWx += ty == 2;
-            if (PHASE == 2) {
-                const int next_ty = done + 1 < 3 * N ? plan[(long long)i * 3 * N + done + 1] : kNone;
-                nWx = (nWx & 0xffff) | next_ty << 16;
-            }
+            cur.started(ty);
+            if (PHASE == 2) cur.advance_window();
             if (ty < 2) {
                 // consume: the queue's next entry becomes the head.  Entries posted so far = ops of
                 // that type the producing stage has started; stage 0's forwards and the last
                 // stage's backwards come from no other stage and are ready whenever it is idle.
                 const bool own = ty == 0 ? first : last;
-                const int posted = ty == 0 ? (first ? N : (nFB_prev & 0xffff))
-                                           : (last ? (nFB & 0xffff) : (int)((unsigned)nFB_next >> 16));
-                unsigned next = ~0u;
-                if (m + 1 < posted) next = own ? 0u : (unsigned)queue[(unsigned long long)(unsigned)((i * 2 + ty) * N + m + 1) * nt];
-                if (ty == 0) headF = next; else headB = next;
+                const int posted = ty == 0 ? (first ? N : prev.nF()) : (last ? cur.nF() : next.nB());
+                unsigned head = ~0u;
+                if (m + 1 < posted) head = own ? 0u : (unsigned)queue[(unsigned long long)(unsigned)((i * 2 + ty) * N + m + 1) * nt];
+                if (ty == 0) headF = head; else headB = head;
             }
             if (is_empty(headF)) headF = empty_head(fin);       // busy until fin from now on
             if (is_empty(headB)) headB = empty_head(fin);
             if (last && ty == 0) headB = 0;                     // its own forward makes a backward available
-            st[fNFB * 64] = nFB;
-            st[fNWX * 64] = nWx;
-            st[fHeadF * 64] = (int)headF;
-            st[fHeadB * 64] = (int)headB;
-            act[i * 64] = next_action<PHASE>(fin, nFB, nWx, headF, headB);
+            cur.store(st);
+            st[Cur::kHeadF] = (int)headF;
+            st[Cur::kHeadB] = (int)headB;
+            act[i * 64] = next_action<PHASE>(fin, cur, headF, headB);
             if (posts) {
                 const int r = fin + (ty == 0 ? delay_i.x : delay_i.y);
                 const unsigned slot = ty == 0 ? headF_j : headB_j;
                 if (is_empty(slot)) {                           // r becomes the head: the receiver may act earlier
                     if (ty == 0) headF_j = (unsigned)r; else headB_j = (unsigned)r;
-                    sj[(fHeadF + ty) * 64] = r;
-                    act[j * 64] = next_action<PHASE>((int)~slot, nFB_j, nWx_j, headF_j, headB_j);
+                    sj[ty == 0 ? Cur::kHeadF : Cur::kHeadB] = r;
+                    act[j * 64] = next_action<PHASE>((int)~slot, cur_j, headF_j, headB_j);
                 } else {
                     queue[(unsigned long long)(unsigned)((j * 2 + ty) * N + m) * nt] = r;
                 }
@@ -210,14 +273,34 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
     }
 }
 
+// Plans from one byte per op, [C][S][3N], to 2 bits per op, 16 ops per word from op 8 q on, kNone
+// behind the end of a stage's ops, laid out [chunk of 64 candidates][S][word][candidate].
+__global__ void k_zb_pack(const uint8_t *plans, uint32_t *packed, long long C, int S, int N) {
+    const int words = packed_words(N);
+    const long long chunks = (C + kZbBlock - 1) / kZbBlock;
+    const long long n = chunks * S * words * kZbBlock, stride = (long long)gridDim.x * blockDim.x;
+    for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += stride) {
+        const int lane = (int)(idx % kZbBlock);
+        const int q = (int)(idx / kZbBlock % words);
+        const int i = (int)(idx / kZbBlock / words % S);
+        const long long c = idx / kZbBlock / words / S * kZbBlock + lane;
+        uint32_t v = 0;
+        for (int j = 0; j < 16; ++j) {
+            const int op = q * 8 + j;
+            v |= (uint32_t)(c < C && op < 3 * N ? plans[(c * S + i) * 3 * N + op] : kNone) << (2 * j);
+        }
+        packed[idx] = v;
+    }
+}
+
 
 extern "C" int zb_cpu(int S, int N, long long C, long long K, const int *tf, const int *tb, const int *tw,
                       const int *w, const int *cf, const int *cb, long long plan_scenario,
-                      int *out_mk, int *out_bub, unsigned threads) {
+                      int *out_mk, int *out_bub, unsigned threads, int narrow) {
     ZbArgs a{}; a.S=S; a.N=N; a.t_f=tf; a.t_b=tb; a.t_w=tw; a.C=C; a.K=K; a.w=w; a.cf=cf; a.cb=cb;
     a.plan_scenario=plan_scenario; a.out_makespan=out_mk; a.out_bubble=out_bub;
     const int Spad=(S+7)&~7;
-    size_t lds_ints=(size_t)Spad*64+(size_t)S*kStage+6*(size_t)S;
+    auto lds_ints_for=[&](int stage){ return (size_t)Spad*64+(size_t)S*stage+6*(size_t)S; };
     a.plans=(uint8_t*)malloc((size_t)C*S*3*N);
     pthread_barrier_init(&bar, nullptr, 64);
     auto run=[&](int phase, long long scen){
@@ -228,16 +311,16 @@ extern "C" int zb_cpu(int S, int N, long long C, long long K, const int *tf, con
         gridDim.x=(unsigned)waves;
         unsigned long long ctr=0; a.next_unit=&ctr;
         for (unsigned b=0;b<waves;++b){
-            zb_lds=(int*)malloc(lds_ints*4);
+            zb_lds=(int*)malloc(lds_ints_for((narrow && phase!=2) ? Cursors<true>::kStage : Cursors<false>::kStage)*4);
             blockIdx.x=b;
             std::vector<std::thread> th;
-            for(unsigned t=0;t<64;++t) th.emplace_back([&,t]{ threadIdx.x=t; if(phase==0)k_zb<0>(a); else if(phase==1)k_zb<1>(a); else k_zb<2>(a); });
+            for(unsigned t=0;t<64;++t) th.emplace_back([&,t]{ threadIdx.x=t; if(phase==0){ if(narrow) k_zb<0,true>(a); else k_zb<0,false>(a);} else if(phase==1){ if(narrow) k_zb<1,true>(a); else k_zb<1,false>(a);} else k_zb<2,false>(a); });
             for(auto&x:th) x.join();
             free(zb_lds);
         }
         free(a.scratch);
     };
-    if (plan_scenario<0) run(0,K); else { run(1,1); run(2,K); }
+    if (plan_scenario<0) run(0,K); else { run(1,1); uint32_t *pk=(uint32_t*)malloc((size_t)((C+63)/64)*64*S*packed_words(N)*4); blockIdx.x=0; gridDim.x=1; blockDim.x=1; threadIdx.x=0; k_zb_pack(a.plans,pk,C,S,N); a.packed=pk; run(2,K); free(pk); }
     free(a.plans);
     return 0;
 }
