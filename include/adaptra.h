@@ -223,7 +223,9 @@ int adaptra_sensitivity(const adaptra_params_t *params, const adaptra_candidates
  *   out_w          DEVICE int32 [S][n_scen]: the point each scenario ended on
  *   out_makespan   DEVICE int32 [n_scen]: its makespan; INT32_MAX if no feasible point was seen
  *   out_rounds     HOST int32: rounds run (may be NULL)
- *   out_evaluated  HOST int64: pairs evaluated in total, rounds * n_scen * (moves + 1) (may be NULL)
+ *   out_evaluated  HOST int64: pairs evaluated in total: moves + 1 per round for every scenario that moved in
+ *                  the round before (all of them in the first round); a scenario at rest is not evaluated
+ *                  again, its result could not change (with S = 1 or M = 1 all are, every round) (may be NULL)
  * params->mem_cap and per-scenario stage times are honoured; the histogram fields are ignored.
  * n_scen * (moves + 1) <= 2^31 - 1.  SYNCHRONOUS: each round waits for the stream (the host
  * needs to know whether anything moved). */

@@ -10,6 +10,11 @@
 //   k_search_init      every scenario's point = w_start clamped, makespan = INT32_MAX
 //   k_search_pool      pool[s][k * (moves + 1) + j] = point of scenario k after move j, clamped
 //   k_search_advance   a scenario adopts its best pool entry iff strictly better
+//
+// A scenario that did not move in a round is at rest for good: its pool, hence its best entry,
+// would be the same in every later round.  Its pool entries are then written as a vector that
+// Lemma 1 rules out (w_0 < w_1), which the evaluation flags in its pre-pass and never resolves,
+// so the rounds get cheaper as the scenarios settle.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -28,6 +33,8 @@ struct SearchArgs {
     const int *w_start;
     int *cur_w, *cur_mk;          // [S][K], [K]: the outputs double as the state
     int *counters;                // [0] scenarios that moved in this round, [1] largest w[0] any point has had
+    int *active;                  // [K] 1 while the scenario is still moving
+    int skip_resting;             // resting scenarios can be marked (needs a stage 1 and M > 1)
     int *pool;                    // [S][C]
     const int *best_idx, *best_mk;
 };
@@ -39,6 +46,7 @@ __global__ void k_search_init(SearchArgs a) {
     if (k >= a.K) return;
     for (int s = 0; s < a.S; ++s) a.cur_w[(long long)s * a.K + k] = clamp_w(a.w_start[s], a.M);
     a.cur_mk[k] = INT32_MAX;
+    a.active[k] = 1;
 }
 
 // Move j of the neighbourhood: j = 0 keeps the point; otherwise (j - 1) / 2 numbers the stage
@@ -60,6 +68,10 @@ __global__ void k_search_pool(SearchArgs a) {
     const long long k = c / per_point;
     const int j = (int)(c % per_point);
     if (c == 0) a.counters[0] = 0;        // nobody has moved yet in this round
+    if (a.skip_resting && !a.active[k]) {               // at rest: an entry that is never resolved
+        for (int s = 0; s < a.S; ++s) a.pool[(long long)s * a.C + c] = s == 1 ? 1 : 0;
+        return;
+    }
     int lo, hi, sign;
     decode_move(a.nb, a.S, j, &lo, &hi, &sign);
     for (int s = 0; s < a.S; ++s) {
@@ -77,6 +89,8 @@ __global__ void k_search_advance(SearchArgs a) {
         a.cur_mk[k] = a.best_mk[k];
         atomicAdd(&a.counters[0], 1);
         atomicMax(&a.counters[1], a.cur_w[k]);           // w is non-increasing over the stages of a feasible point
+    } else {
+        a.active[k] = 0;
     }
 }
 
@@ -85,7 +99,7 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 struct SearchPlan {
     int n_moves;
     long long c_max;
-    size_t off_counters, off_pool, off_best_idx, off_best_mk, off_best_ws, best_ws_bytes, total;
+    size_t off_counters, off_active, off_pool, off_best_idx, off_best_mk, off_best_ws, best_ws_bytes, total;
 };
 
 bool plan_search(const adaptra_params_t *p, long long K, int nb, SearchPlan *pl) {
@@ -98,6 +112,7 @@ bool plan_search(const adaptra_params_t *p, long long K, int nb, SearchPlan *pl)
     if (pl->best_ws_bytes == 0) return false;
     size_t o = 0;
     pl->off_counters = o; o += 256;
+    pl->off_active = o;   o += align256((size_t)K * 4);
     pl->off_pool = o;     o += align256((size_t)p->S * (size_t)pl->c_max * 4);
     pl->off_best_idx = o; o += align256((size_t)K * 4);
     pl->off_best_mk = o;  o += align256((size_t)K * 4);
@@ -131,6 +146,8 @@ int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *sc
     a.w_start = w_start;
     a.cur_w = out_w; a.cur_mk = out_makespan;
     a.counters = (int *)(base + pl.off_counters);
+    a.active = (int *)(base + pl.off_active);
+    a.skip_resting = a.S > 1 && a.M > 1;
     a.pool = (int *)(base + pl.off_pool);
     a.C = pl.c_max;
     int *best_idx = (int *)(base + pl.off_best_idx), *best_mk = (int *)(base + pl.off_best_mk);
@@ -161,7 +178,7 @@ int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *sc
         if ((e = hipStreamSynchronize(st)) != hipSuccess) return hip_fail(e);     // w_top is on this stack
     }
     int rounds = 0;
-    long long evaluated = 0;
+    long long evaluated = 0, still_moving = a.K;
     for (;;) {
         ++rounds;
         // step 1: every scenario's point and its neighbours
@@ -173,7 +190,7 @@ int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *sc
         int rc = adaptra_detail::best(&bp, &pool, scens, pl.n_moves + 1, best_idx, best_mk, nullptr, nullptr,
                                       base + pl.off_best_ws, pl.best_ws_bytes, stream);
         if (rc) return rc;
-        evaluated += a.C;
+        evaluated += (a.skip_resting ? still_moving : a.K) * (pl.n_moves + 1);
         // step 3: move
         hipLaunchKernelGGL(k_search_advance, dim3(kblocks), dim3(kThreadsPerBlock), 0, st, a);
         ADAPTRA_CHECK_LAUNCH();
@@ -182,6 +199,7 @@ int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *sc
         if (e != hipSuccess) return hip_fail(e);
         if ((e = hipStreamSynchronize(st)) != hipSuccess) return hip_fail(e);
         w_top = back[1];
+        still_moving = back[0];
         if (back[0] == 0 || rounds >= max_iters) break;
     }
     if (out_rounds) *out_rounds = rounds;
