@@ -860,4 +860,5 @@ def test_readme_example_runs(lib):
     w, makespan, rounds, pairs = binding.adaptra_search(prob, w_init, neighbourhood=1)
     torch.cuda.synchronize()
     assert mk.shape == (wl.n_scen, wl.n_cand) and w.shape == (wl.S, wl.n_scen) and rounds >= 1
-    assert pairs == rounds * wl.n_scen * (wl.S * (wl.S + 1) + 1)
+    per_scenario = wl.S * (wl.S + 1) + 1                    # the point and its range moves
+    assert wl.n_scen * per_scenario <= pairs <= rounds * wl.n_scen * per_scenario
