@@ -974,16 +974,22 @@ __global__ __launch_bounds__(kBlock) void k_seed(SeedArgs a) {
         return a.tfs ? (long long)a.tfs[(long long)i * a.K + k] + a.tbs[(long long)i * a.K + k]
                      : (long long)a.t_f[i] + a.t_b[i];
     };
-    if (a.w_adapted) {
-        int x = 1;
-        a.w_adapted[(long long)(S - 1) * a.K + k] = 0;
-        const int clip = a.M - 2 * S;
-        for (int i = S - 2; i >= 0; --i) {
-            const long long num = tau(i) + a.cf[(long long)i * a.K + k] + a.cb[(long long)i * a.K + k];
-            const long long den = tau(i + 1);
+    // One pass over the links, last to first, serves both outputs: the delays are read once.
+    int x = 1;
+    if (a.w_adapted) a.w_adapted[(long long)(S - 1) * a.K + k] = 0;
+    const int clip = a.M - 2 * S;
+    long long tau_next = S > 1 ? tau(S - 1) : 0;
+    for (int i = S - 2; i >= 0; --i) {
+        const long long tau_i = tau(i);
+        const long long num = tau_i + a.cf[(long long)i * a.K + k] + a.cb[(long long)i * a.K + k];
+        const long long den = tau_next;
+        if (a.w_adapted) {
             long long d = clip;
             if (den != 0) {
-                long long ratio = (num + den - 1) / den;
+                // ceil(num / den); both are sums of non-negative int32 values, and whenever they fit
+                // 32 bits (always, under adaptra_check_inputs' bound) a 32-bit division does
+                const long long up = num + den - 1;
+                long long ratio = ((unsigned long long)(up | den) >> 32) == 0 ? (long long)((unsigned)up / (unsigned)den) : up / den;
                 if (ratio < 2) ratio = 2;
                 if (ratio < d) d = ratio;
             }
@@ -992,13 +998,11 @@ __global__ __launch_bounds__(kBlock) void k_seed(SeedArgs a) {
             x = nx > a.M ? a.M : (int)nx;
             a.w_adapted[(long long)i * a.K + k] = x - 1;
         }
-    }
-    if (a.not_absorbed) {
-        for (int i = 0; i + 1 < S; ++i) {
-            const long long lhs = tau(i) + a.cf[(long long)i * a.K + k] + a.cb[(long long)i * a.K + k];
-            const long long rhs = ((long long)a.w_cur[i] - a.w_cur[i + 1]) * tau(i + 1);
-            a.not_absorbed[(long long)i * a.K + k] = lhs <= rhs ? 0 : 1;
+        if (a.not_absorbed) {
+            const long long rhs = ((long long)a.w_cur[i] - a.w_cur[i + 1]) * den;
+            a.not_absorbed[(long long)i * a.K + k] = num <= rhs ? 0 : 1;
         }
+        tau_next = tau_i;
     }
 }
 
