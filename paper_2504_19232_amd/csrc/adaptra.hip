@@ -207,14 +207,26 @@ __global__ __launch_bounds__(kBlock) void k_prepass(KArgs a) {
     if (c < a.C) {
     const int S = a.S, M = a.M;
     bool dead = false, mem = false;
-    int prev = clampw(a.w[c], M);
-    const int w0 = prev;
-    if (a.mem_cap && prev + 1 > a.mem_cap[0]) mem = true;
-    for (int s = 1; s < S; ++s) {
-        int ws = clampw(a.w[(long long)s * a.C + c], M);
-        if (prev < ws) dead = true;
-        if (a.mem_cap && ws + 1 > a.mem_cap[s]) mem = true;
-        prev = ws;
+    int prev = INT32_MAX, w0 = 0;
+    // One pass over the stages, four at a time: the Lemma 1 and memory tests, and w as bytes for
+    // the ring kernels (wq_stride is a multiple of 4; bytes past S are the hot kernel's padding
+    // stages, w = 0; with more than 32 stages there are no ring kernels and wq_stride is 0).
+    // The bytes of a candidate no ring kernel takes are never read.
+    unsigned *const q = (unsigned *)(a.cand_wq + c * a.wq_stride);
+    const int s_end = a.wq_stride > S ? a.wq_stride : S;
+    for (int s4 = 0; s4 < s_end; s4 += 4) {
+        unsigned packed = 0;
+        for (int j = 0; j < 4; ++j) {
+            const int s = s4 + j;
+            if (s >= S) break;
+            const int ws = clampw(a.w[(long long)s * a.C + c], M);
+            if (s == 0) w0 = ws;
+            if (prev < ws) dead = true;
+            if (a.mem_cap && ws + 1 > a.mem_cap[s]) mem = true;
+            prev = ws;
+            packed |= (unsigned)(ws & 0xff) << (8 * j);
+        }
+        if (s4 < a.wq_stride) q[s4 / 4] = packed;
     }
     int flag = (dead ? ADAPTRA_FLAG_DEADLOCK : 0) | (mem ? ADAPTRA_FLAG_MEMCAP : 0);
     if (flag == 0) flag = ADAPTRA_FLAG_FEASIBLE;
@@ -224,12 +236,6 @@ __global__ __launch_bounds__(kBlock) void k_prepass(KArgs a) {
     else cls = (w0 + 8) / 8 - 1;            // ring of 8 * (cls + 1) >= w0 + 1 slots
     a.cand_flag[c] = (unsigned char)flag;
     a.cand_class[c] = (unsigned char)cls;
-    if (cls < kNumRingClasses) {
-        unsigned char *q = a.cand_wq + c * a.wq_stride;
-        for (int s = 0; s < S; ++s) q[s] = (unsigned char)clampw(a.w[(long long)s * a.C + c], M);
-        for (int s = S; s < a.wq_stride; ++s) q[s] = 0;      // the hot kernel's padding stages
-
-    }
     if (!dead) atomicAdd(&class_count[cls == kClassDeep ? kNumRingClasses : cls], 1);
     }
     __syncthreads();       // how many candidates need which ring depth: lets the kernels that
