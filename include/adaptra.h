@@ -266,7 +266,9 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
  *      warm-ups deeper than the LDS ring of 128 slots)
  *   1  general kernel only (any S, M, warm-up depth)
  *   2  scenario-lanes kernel wherever its limits allow, regardless of lane efficiency
- *   3  candidate-lanes kernel wherever its limits allow
+ *   3  candidate-lanes kernel wherever its limits allow, in its plain form
+ *   4  the same, in its read-ahead form where that exists (the search with fixed stage times;
+ *      automatic mode takes it for launches of fewer than two wavefronts per SIMD)
  * Returns the previous mode, or -1 for an unknown mode (nothing changes). */
 int adaptra_set_kernel_mode(int mode);
 

@@ -76,6 +76,7 @@ struct KArgs {
     int *scratch;
     int cls_lo, cls_hi, ring_slots, general_all;
     int pair_div;                          // > 0: candidate c is evaluated under scenario c / pair_div only
+    long long live_hint;                   // host side only: candidates expected to run (0: unknown), sizes the launch form
     int direct_out;                        // hot kernel, eval: it writes the final outputs itself (see there)
     long long n_chunks;
     int chunk;                             // candidates per wavefront of the hot kernel (1..kChunk)
@@ -484,8 +485,17 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
 // count lands in a slot no live micro-batch uses: slots of live micro-batches differ from it
 // by less than D.  Ring reads follow the previous stage's write in program order, so a link
 // with equal w needs no special case.  S is padded as in the hot kernel.
-template <int S, bool BEST, bool VT>
-__global__ __launch_bounds__(kBlock, S >= 32 ? 4 : 6) void k_resolve_cand_lanes(KArgs) {
+// AHEAD (search only, fixed stage times): the ring values are read three stages before their
+// use, for launches too small to hide the LDS latency behind other wavefronts (a single decision
+// over some ten thousand candidates, the late rounds of a guided search).  The read of stage s
+// then precedes the write of stage s-1, which targets the same slot exactly when the two stages
+// share w (w is non-increasing, so no earlier stage of the round can have written it): in that
+// case the value just computed is taken instead.  Two more instructions per stage and round,
+// and registers for the values in flight (hence fewer resident wavefronts, which such launches
+// do not have anyway).
+template <int S, bool BEST, bool VT, bool AHEAD>
+__global__ __launch_bounds__(kBlock, AHEAD ? 2 : (S >= 32 ? 4 : 6)) void k_resolve_cand_lanes(KArgs) {
+    static_assert(!AHEAD || (BEST && !VT), "the read-ahead form exists for the search with fixed stage times");
     // The arguments are read through kargs() where they are needed (see there): kept in SGPRs
     // across the round loop they would crowd out the loop's own scalars.
     extern __shared__ int lds[];
@@ -534,6 +544,48 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? 4 : 6) void k_resolve_cand_lanes(
         w0max = uni(w0max);
         int b = w0max == 0 ? 0 : D - w0max;              // (-w0max) mod D: the ring slot of micro-batch r
         for (int r = -w0max; r < M; ++r) {
+            if constexpr (AHEAD) {                       // forward sweep, ring reads three stages ahead
+                constexpr int kAhead = S - 1 < 3 ? S - 1 : 3;
+                int *slot_of[S];
+                int ahead[S];
+                auto ring_slot = [&](int s) {
+                    unsigned slot = ((wpk[s / 4] >> (8 * (s % 4))) & 0xffu) + (unsigned)b;
+                    slot = slot < slot - (unsigned)D ? slot : slot - (unsigned)D;      // mod D (w < D, b < D)
+                    return ring + slot * 64;
+                };
+#pragma unroll
+                for (int s = 1; s <= kAhead; ++s) {
+                    slot_of[s] = ring_slot(s);
+                    ahead[s] = *slot_of[s];
+                }
+                int fin_before = 0;
+#pragma unroll
+                for (int h = 0; h < S; h += kTimesBlock) {
+                    const ConstInt *tf = (const ConstInt *)kargs()->tpad + h;
+#pragma unroll
+                    for (int j = 0; j < kTimesBlock && h + j < S; ++j) {
+                        const int s = h + j;
+                        if (s >= 1 && s + kAhead < S) {
+                            slot_of[s + kAhead] = ring_slot(s + kAhead);
+                            ahead[s + kAhead] = *slot_of[s + kAhead];
+                        }
+                        const int ws = (int)((wpk[s / 4] >> (8 * (s % 4))) & 0xffu);
+                        const bool valid = (unsigned)(ws + r) < (unsigned)M;
+                        int fin;
+                        if (s == 0) {
+                            slot_of[0] = ring_slot(0);
+                            fin = last[0] + tf[j];
+                        } else {
+                            const int ws_before = (int)((wpk[(s - 1) / 4] >> (8 * ((s - 1) % 4))) & 0xffu);
+                            const int arrived = ws == ws_before ? fin_before : ahead[s];
+                            fin = imax(last[s], arrived + cf[s - 1]) + tf[j];
+                        }
+                        last[s] = valid ? fin : last[s];
+                        if (s < S - 1) *slot_of[s] = fin;
+                        fin_before = fin;
+                    }
+                }
+            } else {
 #pragma unroll
             for (int h = 0; h < S; h += kTimesBlock) {   // forward sweep
                 const ConstInt *tf = (const ConstInt *)kargs()->tpad + h;      // scalar loads             // load this block's times here, not before the loops
@@ -554,6 +606,7 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? 4 : 6) void k_resolve_cand_lanes(
                     last[s] = valid ? fin : last[s];
                     if (s < S - 1) *p = fin;
                 }
+            }
             }
             if (r >= 0) {                                // backward sweep
                 int carry = 0;
@@ -1100,7 +1153,8 @@ ResolveKernel choose_kernel(int S, long long K, bool stage_times, bool paired) {
     switch (g_kernel_mode) {
         case 1: return kGeneralOnly;
         case 2: return scen_ok ? kScenarioLanes : kGeneralOnly;
-        case 3: return cand_ok ? kCandidateLanes : kGeneralOnly;
+        case 3:
+        case 4: return cand_ok ? kCandidateLanes : kGeneralOnly;
         default: break;
     }
     if (scen_ok && (K >= 32 || (!cand_ok && K >= 6))) return kScenarioLanes;
@@ -1224,7 +1278,7 @@ int launch_scen_lanes(const KArgs &a, int w_bound, hipStream_t st) {
     }
 }
 
-template <int S, bool BEST, bool VT>
+template <int S, bool BEST, bool VT, bool AHEAD>
 int launch_cand_lanes_one(KArgs a, int w_bound, hipStream_t st) {
     const long long ntiles = (a.pair_div ? 1 : a.K) * ((a.C + 63) / 64);
     long long blocks = (ntiles + kWavesPerBlock - 1) / kWavesPerBlock;
@@ -1237,11 +1291,11 @@ int launch_cand_lanes_one(KArgs a, int w_bound, hipStream_t st) {
         a.ring_slots = 8 * (a.cls_hi + 1);
         const size_t lds = (size_t)kWavesPerBlock * a.ring_slots * 256;
         if (lds > 48 * 1024) {
-            hipError_t e = hipFuncSetAttribute((const void *)k_resolve_cand_lanes<S, BEST, VT>,
+            hipError_t e = hipFuncSetAttribute((const void *)k_resolve_cand_lanes<S, BEST, VT, AHEAD>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return hip_fail(e);
         }
-        hipLaunchKernelGGL((k_resolve_cand_lanes<S, BEST, VT>), dim3((unsigned)blocks), dim3(kBlock), lds, st, a);
+        hipLaunchKernelGGL((k_resolve_cand_lanes<S, BEST, VT, AHEAD>), dim3((unsigned)blocks), dim3(kBlock), lds, st, a);
         ADAPTRA_LAUNCH_CHECK();
     }
     return ADAPTRA_OK;
@@ -1249,12 +1303,19 @@ int launch_cand_lanes_one(KArgs a, int w_bound, hipStream_t st) {
 
 template <bool BEST>
 int launch_cand_lanes(const KArgs &a, int w_bound, hipStream_t st) {
+    // The read-ahead form for launches of fewer wavefronts than two per SIMD (of candidates that
+    // can run, where the caller knows: a.live_hint), or when the tests ask for it.
+    const long long tiles = a.live_hint ? (a.live_hint + 63) / 64 : (a.pair_div ? 1 : a.K) * ((a.C + 63) / 64);
+    const bool ahead = BEST && !a.tfs && (g_kernel_mode == 4 || (g_kernel_mode != 3 && tiles < 2 * 1024));
 #define ADAPTRA_CASE(S_)                                                                         \
     case S_:                                                                                     \
         if constexpr (S_ < 16) {                                                                 \
-            if (a.tfs) return launch_cand_lanes_one<S_, BEST, true>(a, w_bound, st);             \
+            if (a.tfs) return launch_cand_lanes_one<S_, BEST, true, false>(a, w_bound, st);      \
         }                                                                                        \
-        return launch_cand_lanes_one<S_, BEST, false>(a, w_bound, st);
+        if constexpr (BEST) {                                                                    \
+            if (ahead) return launch_cand_lanes_one<S_, BEST, false, true>(a, w_bound, st);      \
+        }                                                                                        \
+        return launch_cand_lanes_one<S_, BEST, false, false>(a, w_bound, st);
     switch (hot_kernel_stages(a.S)) {
         ADAPTRA_CASE(2) ADAPTRA_CASE(4) ADAPTRA_CASE(8) ADAPTRA_CASE(16) ADAPTRA_CASE(32)
         default: return ADAPTRA_EINVAL;
@@ -1494,7 +1555,7 @@ int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *can
                  int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
                  uint64_t *out_hist,
                  void *workspace, size_t workspace_bytes, void *stream) {
-    return adaptra_detail::best(params, cands, scens, 0, out_best_idx, out_best_makespan, out_best_bubble,
+    return adaptra_detail::best(params, cands, scens, 0, 0, out_best_idx, out_best_makespan, out_best_bubble,
                                 out_hist, workspace, workspace_bytes, stream);
 }
 
@@ -1504,7 +1565,7 @@ int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *can
 // c / pair_div and is evaluated under that scenario only, by the general kernel (its lanes
 // carry candidates, so each may have a scenario of its own).
 int adaptra_detail::best(const adaptra_params_t *params, const adaptra_candidates_t *cands,
-                         const adaptra_scenarios_t *scens, int pair_div,
+                         const adaptra_scenarios_t *scens, int pair_div, long long live_hint,
                          int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
                          uint64_t *out_hist,
                          void *workspace, size_t workspace_bytes, void *stream) {
@@ -1527,6 +1588,7 @@ int adaptra_detail::best(const adaptra_params_t *params, const adaptra_candidate
     a.hist_in_lds = (size_t)a.S * a.hist_bins * 4 <= (size_t)kMaxLdsHistBytes;
     if (pair_div < 0 || (pair_div > 0 && (cands->n + pair_div - 1) / pair_div > scens->n)) return ADAPTRA_EINVAL;
     a.pair_div = pair_div;
+    a.live_hint = live_hint > 0 ? live_hint : 0;
     hipLaunchKernelGGL(k_zero_status, dim3(1), dim3(64), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_prepass, dim3(grid_for(a.C, INT32_MAX)), dim3(kBlock), 0, st, a);
@@ -1565,7 +1627,7 @@ int adaptra_seed(const adaptra_params_t *params, const adaptra_scenarios_t *scen
 }
 
 int adaptra_set_kernel_mode(int mode) {
-    if (mode < 0 || mode > 3) return -1;
+    if (mode < 0 || mode > 4) return -1;
     const int prev = g_kernel_mode;
     g_kernel_mode = mode;
     return prev;

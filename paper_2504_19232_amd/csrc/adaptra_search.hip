@@ -187,10 +187,11 @@ int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *sc
         // step 2: each pool entry under its own scenario, and the best entry per scenario
         const int w_bound = w_top + 1 > a.M - 1 ? a.M - 1 : w_top + 1;
         const adaptra_candidates_t pool{a.C, a.pool, w_bound};
-        int rc = adaptra_detail::best(&bp, &pool, scens, pl.n_moves + 1, best_idx, best_mk, nullptr, nullptr,
+        const long long live = (a.skip_resting ? still_moving : a.K) * (pl.n_moves + 1);
+        int rc = adaptra_detail::best(&bp, &pool, scens, pl.n_moves + 1, live, best_idx, best_mk, nullptr, nullptr,
                                       base + pl.off_best_ws, pl.best_ws_bytes, stream);
         if (rc) return rc;
-        evaluated += (a.skip_resting ? still_moving : a.K) * (pl.n_moves + 1);
+        evaluated += live;
         // step 3: move
         hipLaunchKernelGGL(k_search_advance, dim3(kblocks), dim3(kThreadsPerBlock), 0, st, a);
         ADAPTRA_CHECK_LAUNCH();

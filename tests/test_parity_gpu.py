@@ -48,7 +48,7 @@ def gpu_best(binding, wl, mode=0, w_bound=-1):
             None if hist is None else hist.cpu().numpy().astype(np.uint64))
 
 
-def check_full(binding, oracle, wl, modes=(0, 1, 2, 3)):
+def check_full(binding, oracle, wl, modes=(0, 1, 2, 3, 4)):
     ref = oracle.eval_workload(wl)
     rbest = oracle.best_from_eval(ref["makespan"], ref["flag"], ref["bubble"])
     rhist = (oracle.hist_from_eval(ref["bubble"], ref["flag"], wl.hist_bins, wl.hist_shift)
@@ -565,7 +565,7 @@ def test_per_scenario_stage_times_parity(lib, oracle, seed, S, M, C, K, kw):
     ref = oracle.eval_scenario_times(S, M, tfs, tbs, wl.mem_cap, wl.w, wl.c_fwd, wl.c_bwd)
     rbest = oracle.best_from_eval(ref["makespan"], ref["flag"], ref["bubble"])
     rhist = oracle.hist_from_eval(ref["bubble"], ref["flag"], wl.hist_bins, wl.hist_shift) if wl.hist_bins else None
-    for mode in (0, 1, 2, 3):
+    for mode in (0, 1, 2, 3, 4):
         say(f"  eval mode {mode}")
         mk, bub, fl = _with_stage_times(lib, wl, tfs, tbs, mode, lambda p: lib.adaptra_eval(p))
         assert np.array_equal(fl, ref["flag"])
@@ -633,7 +633,7 @@ def test_sensitivity_parity(lib, oracle, seed, S, M, C, K, delta, vt, kw):
     ref = oracle.sensitivity(S, M, wl.t_f, wl.t_b, wl.mem_cap, wl.w, wl.c_fwd, wl.c_bwd, delta,
                              t_f_scen=tfs, t_b_scen=tbs)
     assert ref["sens"].shape == (C, S - 1, K)
-    for mode in (0, 1, 2, 3):
+    for mode in (0, 1, 2, 3, 4):
         say(f"  mode {mode}")
         mk, fl, sens = _with_stage_times(lib, wl, tfs, tbs, mode, lambda p: lib.adaptra_sensitivity(p, delta))
         assert np.array_equal(fl, ref["flag"])
@@ -706,7 +706,7 @@ def test_guided_search_parity(lib, oracle, seed, S, M, K, nb, iters, vt, kw):
     say(f"search {wl.name} neighbourhood {nb}")
     ref = osearch.search(S, M, wl.t_f, wl.t_b, cap, start, wl.c_fwd, wl.c_bwd, neighbourhood=nb,
                          max_iters=iters, t_f_scen=tfs, t_b_scen=tbs)
-    for mode in (0, 1):                                     # candidate-lanes kernel, general kernel
+    for mode in (0, 1, 3, 4):                               # automatic, general kernel, candidate lanes plain / read-ahead
         lib.adaptra_set_kernel_mode(mode)
         prob = lib.Problem.from_workload(wl, t_f_scen=tfs, t_b_scen=tbs)
         w, mk, rounds, evaluated = lib.adaptra_search(prob, torch.from_numpy(start).cuda(), nb, iters)
@@ -836,7 +836,7 @@ def test_many_small_random_problems(lib, oracle):
             ref = oracle.eval_workload(wl)
         rbest = oracle.best_from_eval(ref["makespan"], ref["flag"], ref["bubble"])
         rhist = oracle.hist_from_eval(ref["bubble"], ref["flag"], wl.hist_bins, wl.hist_shift) if wl.hist_bins else None
-        for mode in (0, 1, 2, 3):
+        for mode in (0, 1, 2, 3, 4):
             tag = f"trial {trial} {wl.name} stage-times {vt} mode {mode}"
             mk, bub, fl = _with_stage_times(lib, wl, tfs, tbs, mode, lambda p: lib.adaptra_eval(p))
             assert np.array_equal(fl, ref["flag"]), tag
