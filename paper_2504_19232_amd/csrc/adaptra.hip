@@ -1092,7 +1092,6 @@ thread_local int g_last_hip_error = 0;
 int g_kernel_mode = 0;
 hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;
 
-inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // The hot kernel exists for 2, 4, 8, 16 and 32 stages; a pipeline with another stage count
 // up to 32 runs in the next larger one, padded with stages that take no time (see the
@@ -1125,14 +1124,14 @@ bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws, bool 
     ws->wq_stride = (hot_kernel_stages(S) + 3) & ~3;
     ws->general_threads = general_thread_count(S, M);
     size_t o = 0;
-    ws->off_flag = o;    o += align256((size_t)C);
-    ws->off_class = o;   o += align256((size_t)C);
-    ws->off_wq = o;      o += align256((size_t)C * ws->wq_stride);
-    ws->off_keys = o;    o += align256((size_t)K * 8);
+    ws->off_flag = o;    o += adaptra_detail::align256((size_t)C);
+    ws->off_class = o;   o += adaptra_detail::align256((size_t)C);
+    ws->off_wq = o;      o += adaptra_detail::align256((size_t)C * ws->wq_stride);
+    ws->off_keys = o;    o += adaptra_detail::align256((size_t)K * 8);
     ws->off_status = o;  o += 256;
     ws->off_tpad = o;    o += 512;
-    ws->off_scratch = o; o += align256((size_t)ws->general_threads * (2 * S + M) * 4);
-    ws->off_mkt = o;     o += with_mkt ? align256((size_t)C * (size_t)K * 4) : 0;   // last: the search needs none
+    ws->off_scratch = o; o += adaptra_detail::align256((size_t)ws->general_threads * (2 * S + M) * 4);
+    ws->off_mkt = o;     o += with_mkt ? adaptra_detail::align256((size_t)C * (size_t)K * 4) : 0;   // last: the search needs none
     ws->total = o;
     return true;
 }

@@ -4,6 +4,7 @@
 #define ADAPTRA_INTERNAL_H
 
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include "adaptra.h"
@@ -22,6 +23,9 @@ int hip_fail(hipError_t e);
 int best(const adaptra_params_t *params, const adaptra_candidates_t *cands, const adaptra_scenarios_t *scens,
          int pair_div, long long live_hint, int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
          uint64_t *out_hist, void *workspace, size_t workspace_bytes, void *stream);
+
+// Workspace sections start on 256-byte boundaries.
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 inline int blocks_for(long long n, long long cap) {
     long long g = (n + kThreadsPerBlock - 1) / kThreadsPerBlock;

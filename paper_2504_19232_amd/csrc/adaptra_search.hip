@@ -94,7 +94,6 @@ __global__ void k_search_advance(SearchArgs a) {
     }
 }
 
-inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct SearchPlan {
     int n_moves;
@@ -112,11 +111,11 @@ bool plan_search(const adaptra_params_t *p, long long K, int nb, SearchPlan *pl)
     if (pl->best_ws_bytes == 0) return false;
     size_t o = 0;
     pl->off_counters = o; o += 256;
-    pl->off_active = o;   o += align256((size_t)K * 4);
-    pl->off_pool = o;     o += align256((size_t)p->S * (size_t)pl->c_max * 4);
-    pl->off_best_idx = o; o += align256((size_t)K * 4);
-    pl->off_best_mk = o;  o += align256((size_t)K * 4);
-    pl->off_best_ws = o;  o += align256(pl->best_ws_bytes);
+    pl->off_active = o;   o += adaptra_detail::align256((size_t)K * 4);
+    pl->off_pool = o;     o += adaptra_detail::align256((size_t)p->S * (size_t)pl->c_max * 4);
+    pl->off_best_idx = o; o += adaptra_detail::align256((size_t)K * 4);
+    pl->off_best_mk = o;  o += adaptra_detail::align256((size_t)K * 4);
+    pl->off_best_ws = o;  o += adaptra_detail::align256(pl->best_ws_bytes);
     pl->total = o;
     return true;
 }

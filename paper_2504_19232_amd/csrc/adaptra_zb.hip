@@ -323,7 +323,6 @@ __global__ void k_zb_reset(unsigned long long *counters) {
     if (threadIdx.x < 2) counters[threadIdx.x] = 0;
 }
 
-inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct ZbPlan {
     bool narrow;                  // generation (PHASE 0, 1) in the one-word form of the cursors
@@ -357,9 +356,9 @@ bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
     p->threads_replay = threads_for(p->lds_replay, per_thread);
     size_t o = 0;
     p->off_counters = o; o += 256;
-    p->off_scratch = o; o += align256((size_t)p->threads * per_thread);
-    p->off_plans = o;   o += align256((size_t)C * S * 3 * N);
-    p->off_packed = o;  o += align256((size_t)((C + kZbBlock - 1) / kZbBlock) * kZbBlock * S * packed_words(N) * 4);
+    p->off_scratch = o; o += adaptra_detail::align256((size_t)p->threads * per_thread);
+    p->off_plans = o;   o += adaptra_detail::align256((size_t)C * S * 3 * N);
+    p->off_packed = o;  o += adaptra_detail::align256((size_t)((C + kZbBlock - 1) / kZbBlock) * kZbBlock * S * packed_words(N) * 4);
     p->total = o;
     return true;
 }
