@@ -815,6 +815,54 @@ def test_eval_and_best_replay_from_a_hip_graph(lib, oracle):
                               oracle.hist_from_eval(ref["bubble"], ref["flag"], wl.hist_bins, wl.hist_shift))
 
 
+def test_zb_replays_from_a_hip_graph(lib, oracle):
+    """adaptra_zb_eval draws its work units from a counter in the workspace, reset by a kernel of
+    the same call: captured into a HIP graph (policy and fixed plans), every replay starts from
+    that reset.  Replayed with the delays changed in place and eager calls in between."""
+    import torch
+    b = lib
+    rng = np.random.default_rng(130)
+    S, N, C, K = 8, 16, 150, 33
+    t_f, t_b, t_w = rng.integers(1, 60, S), rng.integers(1, 90, S), rng.integers(0, 50, S)
+    w = np.sort(rng.integers(0, N, (S, C)), axis=0)[::-1]
+    cf = rng.integers(0, 400, (S - 1, K)).astype(np.int32)
+    cb = rng.integers(0, 400, (S - 1, K)).astype(np.int32)
+    prob, t_w_d = _zb_problem(b, S, N, t_f, t_b, t_w, w, cf, cb)
+    x = np.clip(w, 0, N - 1) + 1
+    n = int(b.load().adaptra_zb_workspace_bytes(__import__("ctypes").byref(prob.params), prob.C, prob.K))
+    ws = torch.empty(n, dtype=torch.uint8, device=prob.device)
+    b.adaptra_zb_eval(prob, t_w_d, -1, workspace=ws)          # eager warm-up
+    b.adaptra_zb_eval(prob, t_w_d, 2, workspace=ws)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            mk, bub = b.adaptra_zb_eval(prob, t_w_d, -1, workspace=ws)
+            mkp, _ = b.adaptra_zb_eval(prob, t_w_d, 2, want_bubble=False, workspace=ws)
+    torch.cuda.synchronize()
+    c_fwd_dev = prob.tensors[3]
+    for replay in range(3):
+        say(f"  replay {replay}")
+        if replay:
+            cf[:] = (cf.astype(np.int64) * (replay + 2) % 997).astype(np.int32)
+            c_fwd_dev.copy_(torch.from_numpy(cf))
+            b.adaptra_zb_eval(prob, t_w_d, 0)                 # eager work of the same library in between
+        mk.fill_(-7)
+        mkp.fill_(-7)
+        graph.replay()
+        torch.cuda.synchronize()
+        ref = oracle.zb_batch(S, N, t_f, t_b, t_w, x, cf, cb)
+        assert np.array_equal(mk.cpu().numpy(), ref["makespan"])
+        assert np.array_equal(bub.cpu().numpy(), ref["idle"])
+        got = mkp.cpu().numpy()
+        for c in range(0, C, 13):
+            gen = oracle.zb_simulate(S, N, t_f, t_b, t_w, cf[:, 2], cb[:, 2], x=x[:, c])
+            for k in (0, 2, K - 1):
+                rep = oracle.zb_simulate(S, N, t_f, t_b, t_w, cf[:, k], cb[:, k], order=gen["order"])
+                assert got[k, c] == rep["makespan"], (replay, c, k)
+
+
 def test_many_small_random_problems(lib, oracle):
     """A sweep of small random shapes (every stage count from 1 to 20, M from 1, ragged C and
     K, with and without caps, histograms and per-scenario stage times) in every kernel mode."""
