@@ -815,6 +815,51 @@ def test_eval_and_best_replay_from_a_hip_graph(lib, oracle):
                               oracle.hist_from_eval(ref["bubble"], ref["flag"], wl.hist_bins, wl.hist_shift))
 
 
+def test_other_entry_points_replay_from_a_hip_graph(lib):
+    """adaptra_eval_best, adaptra_seed and adaptra_sensitivity captured into one HIP graph: every
+    replay, after the inputs changed in place, equals what the same calls return eagerly (the
+    eager paths are checked against the oracle by the tests above)."""
+    import torch
+    wl = workloads.random_workload(140, 8, 20, 200, 70, hist_bins=8, hist_shift=10)
+    prob = lib.Problem.from_workload(wl, w_bound=int(np.clip(wl.w, 0, wl.M - 1).max()))
+    w_cur = torch.from_numpy(np.arange(wl.S - 1, -1, -1, dtype=np.int32)).cuda()
+
+    def enqueue():
+        return (lib.adaptra_eval_best(prob), lib.adaptra_seed(prob, x_max=6, w_current=w_cur, want_not_absorbed=True),
+                lib.adaptra_sensitivity(prob, 3))
+
+    def flat(out):
+        return [t.cpu().numpy().copy() for group in out for t in group if t is not None]
+
+    enqueue()                                   # eager warm-up (sets the kernels' LDS attributes)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            captured = enqueue()
+    torch.cuda.synchronize()
+    c_bwd_dev = prob.tensors[4]
+    for replay in range(3):
+        say(f"  replay {replay}")
+        if replay:
+            wl.c_bwd[:] = (wl.c_bwd.astype(np.int64) * (replay + 3) % 2999).astype(np.int32)
+            c_bwd_dev.copy_(torch.from_numpy(wl.c_bwd))
+        eager = enqueue()
+        torch.cuda.synchronize()
+        want = flat(eager)
+        for group in captured:
+            for t in group:
+                if t is not None:
+                    t.fill_(0)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = flat(captured)
+        assert len(got) == len(want)
+        for i, (g, w) in enumerate(zip(got, want)):
+            assert np.array_equal(g, w), (replay, i)
+
+
 def test_zb_replays_from_a_hip_graph(lib, oracle):
     """adaptra_zb_eval draws its work units from a counter in the workspace, reset by a kernel of
     the same call: captured into a HIP graph (policy and fixed plans), every replay starts from
