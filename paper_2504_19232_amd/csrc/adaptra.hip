@@ -210,12 +210,11 @@ __global__ __launch_bounds__(kBlock) void k_prepass(KArgs a) {
     bool dead = false, mem = false;
     int prev = INT32_MAX, w0 = 0;
     // One pass over the stages, four at a time: the Lemma 1 and memory tests, and w as bytes for
-    // the ring kernels (wq_stride is a multiple of 4; bytes past S are the hot kernel's padding
-    // stages, w = 0; with more than 32 stages there are no ring kernels and wq_stride is 0).
-    // The bytes of a candidate no ring kernel takes are never read.
+    // the ring kernels (wq_stride is a multiple of 4; bytes past S are the padding stages of the
+    // kernel size the pipeline runs in, w = 0).  The bytes of a candidate no ring kernel takes
+    // are never read.
     unsigned *const q = (unsigned *)(a.cand_wq + c * a.wq_stride);
-    const int s_end = a.wq_stride > S ? a.wq_stride : S;
-    for (int s4 = 0; s4 < s_end; s4 += 4) {
+    for (int s4 = 0; s4 < a.wq_stride; s4 += 4) {
         unsigned packed = 0;
         for (int j = 0; j < 4; ++j) {
             const int s = s4 + j;
@@ -227,7 +226,7 @@ __global__ __launch_bounds__(kBlock) void k_prepass(KArgs a) {
             prev = ws;
             packed |= (unsigned)(ws & 0xff) << (8 * j);
         }
-        if (s4 < a.wq_stride) q[s4 / 4] = packed;
+        q[s4 / 4] = packed;
     }
     int flag = (dead ? ADAPTRA_FLAG_DEADLOCK : 0) | (mem ? ADAPTRA_FLAG_MEMCAP : 0);
     if (flag == 0) flag = ADAPTRA_FLAG_FEASIBLE;
@@ -494,7 +493,7 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
 // and registers for the values in flight (hence fewer resident wavefronts, which such launches
 // do not have anyway).
 template <int S, bool BEST, bool VT, bool AHEAD>
-__global__ __launch_bounds__(kBlock, AHEAD ? 2 : (S >= 32 ? 4 : 6)) void k_resolve_cand_lanes(KArgs) {
+__global__ __launch_bounds__(kBlock, AHEAD || S >= 64 ? 2 : (S >= 32 ? 4 : 6)) void k_resolve_cand_lanes(KArgs) {
     static_assert(!AHEAD || (BEST && !VT), "the read-ahead form exists for the search with fixed stage times");
     // The arguments are read through kargs() where they are needed (see there): kept in SGPRs
     // across the round loop they would crowd out the loop's own scalars.
@@ -1101,6 +1100,14 @@ int hot_kernel_stages(int S) {
         if (S <= p) return p;
     return 0;
 }
+// The candidate-lanes kernel has one size more: per-lane state in VGPRs (last, c_fwd, c_bwd:
+// 3 S registers) still fits at 64 stages with two wavefronts per SIMD, which the scenario-lanes
+// kernel's per-stage scalars (2 S SGPRs) do not.
+int cand_kernel_stages(int S) {
+    for (int p = 2; p <= 64; p *= 2)
+        if (S <= p) return p;
+    return 0;
+}
 
 struct Workspace {
     size_t off_flag, off_class, off_wq, off_keys, off_status, off_tpad, off_scratch, off_mkt, total;
@@ -1121,7 +1128,7 @@ long long general_thread_count(int S, int M) {
 bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws, bool with_mkt = true) {
     if (S < 1 || S > ADAPTRA_MAX_STAGES || M < 1 || M > ADAPTRA_MAX_MICROBATCHES) return false;
     if (C < 1 || C > INT32_MAX || K < 1 || K > INT32_MAX) return false;
-    ws->wq_stride = (hot_kernel_stages(S) + 3) & ~3;
+    ws->wq_stride = (cand_kernel_stages(S) + 3) & ~3;
     ws->general_threads = general_thread_count(S, M);
     size_t o = 0;
     ws->off_flag = o;    o += adaptra_detail::align256((size_t)C);
@@ -1137,8 +1144,9 @@ bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws, bool 
 }
 
 
-// Which of the two on-chip kernels runs (the general kernel takes what neither can: more than
-// 32 stages, warm-ups deeper than the ring).  The scenario-lanes kernel spends 6 VALU ops per
+// Which of the two on-chip kernels runs (the general kernel takes what neither can: warm-ups
+// deeper than the ring, per-scenario stage times at too many stages); from 33 to 64 stages only
+// the candidate-lanes kernel has a size.  The scenario-lanes kernel spends 6 VALU ops per
 // stage and round on 64 scenarios whether or not all 64 lanes carry one; the candidate-lanes
 // kernel spends 13 on 64 pairs.  Measured on 8 192 candidates of configurations 1-3 they cross
 // at 28-32 scenarios for every stage count.  The candidate-lanes kernel is also the only one
@@ -1146,9 +1154,8 @@ bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws, bool 
 // 16 stages on, and the scenario-lanes kernel then wins from 6 scenarios against the general one.
 enum ResolveKernel { kScenarioLanes, kCandidateLanes, kGeneralOnly };
 ResolveKernel choose_kernel(int S, long long K, bool stage_times, bool paired) {
-    const bool sized = hot_kernel_stages(S) != 0;
-    const bool scen_ok = sized && !paired;
-    const bool cand_ok = sized && !(stage_times && hot_kernel_stages(S) >= 16);
+    const bool scen_ok = hot_kernel_stages(S) != 0 && !paired;
+    const bool cand_ok = cand_kernel_stages(S) != 0 && !(stage_times && cand_kernel_stages(S) >= 16);
     switch (g_kernel_mode) {
         case 1: return kGeneralOnly;
         case 2: return scen_ok ? kScenarioLanes : kGeneralOnly;
@@ -1311,12 +1318,12 @@ int launch_cand_lanes(const KArgs &a, int w_bound, hipStream_t st) {
         if constexpr (S_ < 16) {                                                                 \
             if (a.tfs) return launch_cand_lanes_one<S_, BEST, true, false>(a, w_bound, st);      \
         }                                                                                        \
-        if constexpr (BEST) {                                                                    \
+        if constexpr (BEST && S_ < 64) {      /* at 64 stages its scalars would spill */        \
             if (ahead) return launch_cand_lanes_one<S_, BEST, false, true>(a, w_bound, st);      \
         }                                                                                        \
         return launch_cand_lanes_one<S_, BEST, false, false>(a, w_bound, st);
-    switch (hot_kernel_stages(a.S)) {
-        ADAPTRA_CASE(2) ADAPTRA_CASE(4) ADAPTRA_CASE(8) ADAPTRA_CASE(16) ADAPTRA_CASE(32)
+    switch (cand_kernel_stages(a.S)) {
+        ADAPTRA_CASE(2) ADAPTRA_CASE(4) ADAPTRA_CASE(8) ADAPTRA_CASE(16) ADAPTRA_CASE(32) ADAPTRA_CASE(64)
         default: return ADAPTRA_EINVAL;
     }
 #undef ADAPTRA_CASE
