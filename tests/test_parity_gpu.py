@@ -690,6 +690,7 @@ SEARCH_CASES = [
     (106, 8, 32, 20, 1, 4, False, dict(c_hi=3000)),        # stopped by max_iters
     (107, 16, 40, 12, 0, 50, True, dict(c_hi=2000, cap=False)),
     (108, 5, 20, 1100, 0, 50, False, {}),                  # many scenarios
+    (109, 40, 50, 7, 0, 8, False, dict(cap=False)),        # the candidate-lanes kernel's 64-stage size
 ]
 
 
