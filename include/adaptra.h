@@ -263,8 +263,8 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
  *   0  automatic (default): up to 32 stages, the register/LDS kernel with scenarios on the
  *      lanes from 32 scenarios on, below that -- and from 33 to 64 stages always -- the kernel
  *      with candidates on the lanes (the measured crossover); the general kernel for what fits
- *      neither (per-scenario stage times from 16 stages on with few scenarios or more than 32
- *      stages, warm-ups deeper than the LDS ring of 128 slots)
+ *      neither (per-scenario stage times at more than 32 stages, warm-ups deeper than the LDS
+ *      ring of 128 slots)
  *   1  general kernel only (any S, M, warm-up depth)
  *   2  scenario-lanes kernel wherever its limits allow, regardless of lane efficiency
  *   3  candidate-lanes kernel wherever its limits allow, in its plain form

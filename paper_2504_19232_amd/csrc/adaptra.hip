@@ -493,7 +493,7 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
 // and registers for the values in flight (hence fewer resident wavefronts, which such launches
 // do not have anyway).
 template <int S, bool BEST, bool VT, bool AHEAD>
-__global__ __launch_bounds__(kBlock, AHEAD || S >= 64 ? 2 : (S >= 32 ? 4 : 6)) void k_resolve_cand_lanes(KArgs) {
+__global__ __launch_bounds__(kBlock, AHEAD || S >= 64 || (VT && S >= 16) ? 2 : (S >= 32 ? 4 : 6)) void k_resolve_cand_lanes(KArgs) {
     static_assert(!AHEAD || (BEST && !VT), "the read-ahead form exists for the search with fixed stage times");
     // The arguments are read through kargs() where they are needed (see there): kept in SGPRs
     // across the round loop they would crowd out the loop's own scalars.
@@ -536,6 +536,16 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 64 ? 2 : (S >= 32 ? 4 : 6)) v
             const bool real = s + 1 < kargs()->S;
             cf[s] = real ? kargs()->cf[(long long)s * kargs()->Kin + kin] + (s == link_up ? kargs()->sens_delta : 0) : 0;
             cb[s] = real ? kargs()->cb[(long long)s * kargs()->Kin + kin] : 0;
+        }
+        // Per-scenario stage times (VT): the lane's own t_f and t_b, 2 S more registers.
+        int tfv[VT ? S : 1], tbv[VT ? S : 1];
+        if constexpr (VT) {
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                const bool real = s < kargs()->S;
+                tfv[s] = real ? kargs()->tfs[(long long)s * kargs()->Kin + kin] : 0;
+                tbv[s] = real ? kargs()->tbs[(long long)s * kargs()->Kin + kin] : 0;
+            }
         }
         int w0max = (int)(wpk[0] & 0xffu);
 #pragma unroll
@@ -597,7 +607,7 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 64 ? 2 : (S >= 32 ? 4 : 6)) v
                     slot = slot < slot - (unsigned)D ? slot : slot - (unsigned)D;      // mod D (w < D, b < D)
                     int *const p = ring + slot * 64;
                     int t_f_s;
-                    if constexpr (VT) t_f_s = s < kargs()->S ? kargs()->tfs[(long long)s * kargs()->Kin + kin] : 0;
+                    if constexpr (VT) t_f_s = tfv[s];
                     else t_f_s = tf[j];
                     int fin;
                     if (s == 0) fin = last[0] + t_f_s;
@@ -617,7 +627,7 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 64 ? 2 : (S >= 32 ? 4 : 6)) v
                         const int s = h + j;
                         if (s > S - 1) continue;
                         int t_b_s;
-                        if constexpr (VT) t_b_s = s < kargs()->S ? kargs()->tbs[(long long)s * kargs()->Kin + kin] : 0;
+                        if constexpr (VT) t_b_s = tbv[s];
                         else t_b_s = tb[j];
                         const int arrive = s == S - 1 ? 0 : carry + cb[s < S - 1 ? s : 0];
                         last[s] = imax(last[s], arrive) + t_b_s;
@@ -1150,12 +1160,15 @@ bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws, bool 
 // stage and round on 64 scenarios whether or not all 64 lanes carry one; the candidate-lanes
 // kernel spends 13 on 64 pairs.  Measured on 8 192 candidates of configurations 1-3 they cross
 // at 28-32 scenarios for every stage count.  The candidate-lanes kernel is also the only one
-// for the search's paired form; with per-scenario stage times it runs out of registers from
-// 16 stages on, and the scenario-lanes kernel then wins from 6 scenarios against the general one.
+// for the search's paired form.  With per-scenario stage times it keeps 5 S values per lane in
+// registers (two wavefronts per SIMD from 16 stages on, still ahead of the scenario-lanes kernel
+// below 32 scenarios: 0.42 / 1.64 ms against 1.71 ms at 1 / 31 scenarios, S = 32, 8 192
+// candidates) and has no 64-stage size; where it is missing the scenario-lanes kernel wins
+// from 6 scenarios against the general one.
 enum ResolveKernel { kScenarioLanes, kCandidateLanes, kGeneralOnly };
 ResolveKernel choose_kernel(int S, long long K, bool stage_times, bool paired) {
     const bool scen_ok = hot_kernel_stages(S) != 0 && !paired;
-    const bool cand_ok = cand_kernel_stages(S) != 0 && !(stage_times && cand_kernel_stages(S) >= 16);
+    const bool cand_ok = cand_kernel_stages(S) != 0 && !(stage_times && cand_kernel_stages(S) >= 64);
     switch (g_kernel_mode) {
         case 1: return kGeneralOnly;
         case 2: return scen_ok ? kScenarioLanes : kGeneralOnly;
@@ -1315,7 +1328,7 @@ int launch_cand_lanes(const KArgs &a, int w_bound, hipStream_t st) {
     const bool ahead = BEST && !a.tfs && (g_kernel_mode == 4 || (g_kernel_mode != 3 && tiles < 2 * 1024));
 #define ADAPTRA_CASE(S_)                                                                         \
     case S_:                                                                                     \
-        if constexpr (S_ < 16) {                                                                 \
+        if constexpr (S_ < 64) {      /* 5 S per-lane registers: not at 64 stages */             \
             if (a.tfs) return launch_cand_lanes_one<S_, BEST, true, false>(a, w_bound, st);      \
         }                                                                                        \
         if constexpr (BEST && S_ < 64) {      /* at 64 stages its scalars would spill */        \
