@@ -88,6 +88,24 @@ struct KArgs {
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ int imax(int a, int b) { return a > b ? a : b; }
+// One count into hist[bin] for every lane that calls (the callers' lanes are the scenarios of
+// one candidate, whose bubbles mostly fall into one or two bins: as single atomics those would
+// queue up on one address).  The lanes sharing the first lane's bin are counted with one
+// atomic, then the same for the next bin still open; what is left counts for itself.
+template <class Count>
+__device__ __forceinline__ void hist_count(Count *hist, int bin, int lane) {
+    unsigned long long open = __ballot(true);
+    bool mine = true;
+    for (int group = 0; group < 2 && open; ++group) {
+        const int lead = __ffsll((long long)open) - 1;
+        const int lead_bin = __builtin_amdgcn_readlane(bin, lead);
+        const unsigned long long same = __ballot(mine && bin == lead_bin);
+        if (lane == lead) atomicAdd(&hist[lead_bin], (Count)__popcll(same));
+        open &= ~same;
+        mine = mine && bin != lead_bin;
+    }
+    if (mine) atomicAdd(&hist[bin], (Count)1);
+}
 // Ring offset of a stage, one slot (256 B) further, wrapping to slot 0.  The offset is kept
 // biased by -ring_bytes (mod 2^32) so that the wrap shows up as the carry of the add: two
 // SALU ops instead of add, compare, select.  The bias is folded into the lane's base address.
@@ -346,8 +364,8 @@ __global__ __launch_bounds__(kBlock) void k_best_from_eval(KArgs a) {
                 const int tau_s = a.tfs ? a.tfs[(long long)s * a.K + k] + a.tbs[(long long)s * a.K + k] : a.t_f[s] + a.t_b[s];
                 int b = (mk - a.M * tau_s) >> a.hist_shift;
                 b = b > a.hist_bins - 1 ? a.hist_bins - 1 : b;
-                if (lds_hist) atomicAdd(&hist_lds_scan[s * a.hist_bins + b], 1u);
-                else atomicAdd(&a.hist[s * a.hist_bins + b], 1ull);
+                if (lds_hist) hist_count(hist_lds_scan + s * a.hist_bins, b, lane);
+                else hist_count(a.hist + s * a.hist_bins, b, lane);
             }
         }
     }
@@ -898,15 +916,12 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? (VT ? 3 : ADAPTRA_WAVES32) : (S >
                     if (kargs()->hist) {
                         const int bins = kargs()->hist_bins, shift = kargs()->hist_shift;
                         unsigned long long *const hist = kargs()->hist;
-#pragma unroll
-                        for (int s = 0; s < S; ++s) {
-                            if (s < kargs()->S) {
-                                const int tau_s = ADAPTRA_TF(s) + ADAPTRA_TB(s);
-                                int b = (mk - M * tau_s) >> shift;
-                                b = b > bins - 1 ? bins - 1 : b;
-                                if (lds_hist) atomicAdd(&hist_lds[s * bins + b], 1u);
-                                else atomicAdd(&hist[s * bins + b], 1ull);
-                            }
+                        for (int s = 0; s < kargs()->S; ++s) {
+                            const int tau_s = ADAPTRA_TF(s) + ADAPTRA_TB(s);
+                            int b = (mk - M * tau_s) >> shift;
+                            b = b > bins - 1 ? bins - 1 : b;
+                            if (lds_hist) hist_count(hist_lds + s * bins, b, lane);
+                            else hist_count(hist + s * bins, b, lane);
                         }
                     }
                 }
