@@ -340,6 +340,11 @@ __global__ __launch_bounds__(kBlock) void k_best_init(KArgs a) {
 // (adaptra_eval_best): nothing is resolved twice.  One wavefront = 64 scenarios (lanes) x a
 // run of 64 candidates; only the rows of feasible candidates are read (coalesced along the
 // scenario axis).  Keys and histogram as in the resolve kernels' search.
+// RUNS > 0 (pipelines of up to RUNS stages, with a histogram): a lane -- one scenario -- walks
+// the candidates of its tile and keeps, per stage, the bin of the last bubble and how often it
+// came in a row; only a change of bin costs an atomic.  Neighbouring candidates mostly share
+// their bins, so this replaces S atomics (or wavefront votes) per pair by a compare and an add.
+template <int RUNS>
 __global__ __launch_bounds__(kBlock) void k_best_from_eval(KArgs a) {
     extern __shared__ unsigned hist_lds_scan[];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -354,19 +359,73 @@ __global__ __launch_bounds__(kBlock) void k_best_from_eval(KArgs a) {
     const long long c0 = (task / ktiles) * 64;
     const bool kvalid = k < a.K;
     unsigned long long key = kNoKey;
-    for (long long c = c0; c < c0 + 64 && c < a.C; ++c) {
-        if (uni(a.cand_flag[c]) != ADAPTRA_FLAG_FEASIBLE || !kvalid) continue;
-        const int mk = a.mk_t[c * a.K + k];
-        const unsigned long long cand = ((unsigned long long)(unsigned)mk << 32) | (unsigned)c;
-        key = cand < key ? cand : key;
-        if (a.hist) {
-            for (int s = 0; s < a.S; ++s) {
-                const int tau_s = a.tfs ? a.tfs[(long long)s * a.K + k] + a.tbs[(long long)s * a.K + k] : a.t_f[s] + a.t_b[s];
-                int b = (mk - a.M * tau_s) >> a.hist_shift;
-                b = b > a.hist_bins - 1 ? a.hist_bins - 1 : b;
-                if (lds_hist) hist_count(hist_lds_scan + s * a.hist_bins, b, lane);
-                else hist_count(a.hist + s * a.hist_bins, b, lane);
+    int run_bin[RUNS > 0 ? RUNS : 1], run_len[RUNS > 0 ? RUNS : 1], busy[RUNS > 0 ? RUNS : 1];
+    if constexpr (RUNS > 0) {
+#pragma unroll
+        for (int s = 0; s < RUNS; ++s) {
+            run_bin[s] = 0;
+            run_len[s] = 0;
+            busy[s] = 0;
+            if (s < a.S && kvalid)
+                busy[s] = a.M * (a.tfs ? a.tfs[(long long)s * a.K + k] + a.tbs[(long long)s * a.K + k] : a.t_f[s] + a.t_b[s]);
+        }
+    }
+    auto count_run = [&](int s, int bin, int n) {
+        if (lds_hist) atomicAdd(&hist_lds_scan[s * a.hist_bins + bin], (unsigned)n);
+        else atomicAdd(&a.hist[s * a.hist_bins + bin], (unsigned long long)n);
+    };
+    // The feasible candidates of this tile as a mask (lane j looks at candidate c0 + j), then
+    // four of them at a time so that their loads are in flight together.
+    unsigned long long feasible = __ballot(c0 + lane < a.C && a.cand_flag[c0 + lane < a.C ? c0 + lane : 0] == ADAPTRA_FLAG_FEASIBLE);
+    while (feasible) {
+        long long cs[4];
+        int mks[4], n = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (feasible) {
+                cs[u] = c0 + (__ffsll((long long)feasible) - 1);
+                feasible &= feasible - 1;
+                n = u + 1;
+            } else {
+                cs[u] = cs[0];
             }
+            mks[u] = kvalid ? a.mk_t[cs[u] * a.K + k] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (u >= n || !kvalid) continue;
+            const long long c = cs[u];
+            const int mk = mks[u];
+            const unsigned long long cand = ((unsigned long long)(unsigned)mk << 32) | (unsigned)c;
+            key = cand < key ? cand : key;
+            if (!a.hist) continue;
+            if constexpr (RUNS > 0) {
+#pragma unroll
+                for (int s = 0; s < RUNS; ++s) {
+                    if (s >= a.S) break;
+                    int bin = (mk - busy[s]) >> a.hist_shift;
+                    bin = bin > a.hist_bins - 1 ? a.hist_bins - 1 : bin;
+                    const bool same = bin == run_bin[s];
+                    if (!same && run_len[s]) count_run(s, run_bin[s], run_len[s]);
+                    run_len[s] = same ? run_len[s] + 1 : 1;
+                    run_bin[s] = bin;
+                }
+            } else {
+                for (int s = 0; s < a.S; ++s) {
+                    const int tau_s = a.tfs ? a.tfs[(long long)s * a.K + k] + a.tbs[(long long)s * a.K + k] : a.t_f[s] + a.t_b[s];
+                    int b = (mk - a.M * tau_s) >> a.hist_shift;
+                    b = b > a.hist_bins - 1 ? a.hist_bins - 1 : b;
+                    if (lds_hist) hist_count(hist_lds_scan + s * a.hist_bins, b, lane);
+                    else hist_count(a.hist + s * a.hist_bins, b, lane);
+                }
+            }
+        }
+    }
+    if constexpr (RUNS > 0) {
+        if (a.hist && kvalid) {
+#pragma unroll
+            for (int s = 0; s < RUNS; ++s)
+                if (s < a.S && run_len[s]) count_run(s, run_bin[s], run_len[s]);
         }
     }
     if (key != kNoKey) atomicMin(&a.keys[k], key);
@@ -1535,8 +1594,12 @@ int adaptra_eval_best(const adaptra_params_t *params, const adaptra_candidates_t
     // the search, over the makespans just computed
     const long long tasks = ((a.K + 63) / 64) * ((a.C + 63) / 64);
     const size_t lds = a.hist && a.hist_in_lds ? (size_t)a.S * a.hist_bins * 4 : 0;
-    hipLaunchKernelGGL(k_best_from_eval, dim3((unsigned)((tasks + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(kBlock),
-                       lds, st, a);
+    if (a.hist && a.S <= 16)
+        hipLaunchKernelGGL(k_best_from_eval<16>, dim3((unsigned)((tasks + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(kBlock),
+                           lds, st, a);
+    else
+        hipLaunchKernelGGL(k_best_from_eval<0>, dim3((unsigned)((tasks + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(kBlock),
+                           lds, st, a);
     ADAPTRA_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_best_finalize, dim3(grid_for(a.K, INT32_MAX)), dim3(kBlock), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
