@@ -329,7 +329,7 @@ def main():
         binding.adaptra_best(one, oidx, omk, None, None, want_bubble=False, workspace=ws)
         t_one = timed(lambda: binding.adaptra_best(one, oidx, omk, None, None, want_bubble=False, workspace=ws), n=20)
         online_info = {"candidates": C, "scenarios": 1, "best_ms": t_one * 1e3,
-                       "kernel": "candidate lanes (fewer than 32 scenarios)"}
+                       "kernel": "candidate lanes, read-ahead form (few scenarios)"}
         del one
 
     flags = fl[0].cpu().numpy()                    # the flag depends on the candidate only

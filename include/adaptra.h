@@ -261,15 +261,15 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
 
 /* Kernel selection, process-wide; for tests and measurements.
  *   0  automatic (default): up to 32 stages, the register/LDS kernel with scenarios on the
- *      lanes from 32 scenarios on, below that -- and from 33 to 64 stages always -- the kernel
- *      with candidates on the lanes (the measured crossover); the general kernel for what fits
+ *      lanes from 40 scenarios on (from 28 with at least 32768 candidates), below that -- and
+ *      from 33 to 64 stages always -- the kernel with candidates on the lanes, in its read-ahead
+ *      form (the measured crossover); the general kernel for what fits
  *      neither (per-scenario stage times at more than 32 stages, warm-ups deeper than the LDS
  *      ring of 128 slots)
  *   1  general kernel only (any S, M, warm-up depth)
  *   2  scenario-lanes kernel wherever its limits allow, regardless of lane efficiency
  *   3  candidate-lanes kernel wherever its limits allow, in its plain form
- *   4  the same, in its read-ahead form where that exists (the search with fixed stage times;
- *      automatic mode takes it for launches of fewer than two wavefronts per SIMD)
+ *   4  the same, in its read-ahead form where that exists (up to 32 stages)
  * Returns the previous mode, or -1 for an unknown mode (nothing changes). */
 int adaptra_set_kernel_mode(int mode);
 

@@ -81,7 +81,6 @@ struct KArgs {
     int *scratch;
     int cls_lo, cls_hi, ring_slots, general_all;
     int pair_div;                          // > 0: candidate c is evaluated under scenario c / pair_div only
-    long long live_hint;                   // host side only: candidates expected to run (0: unknown), sizes the launch form
     int direct_out;                        // hot kernel, eval: it writes the final outputs itself (see there)
     long long n_chunks;
     int chunk;                             // candidates per wavefront of the hot kernel (1..kChunk)
@@ -566,17 +565,17 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
 // count lands in a slot no live micro-batch uses: slots of live micro-batches differ from it
 // by less than D.  Ring reads follow the previous stage's write in program order, so a link
 // with equal w needs no special case.  S is padded as in the hot kernel.
-// AHEAD (search only, fixed stage times): the ring values are read three stages before their
-// use, for launches too small to hide the LDS latency behind other wavefronts (a single decision
-// over some ten thousand candidates, the late rounds of a guided search).  The read of stage s
+// AHEAD (every size but 64 stages): the ring values are read three stages before their use, so
+// that the LDS latency is not paid stage by stage (the plain form waits for each read right
+// where it is issued; measured 1.3-1.6 times slower from 16 stages on, whatever the size of the
+// launch).  The read of stage s
 // then precedes the write of stage s-1, which targets the same slot exactly when the two stages
 // share w (w is non-increasing, so no earlier stage of the round can have written it): in that
 // case the value just computed is taken instead.  Two more instructions per stage and round,
-// and registers for the values in flight (hence fewer resident wavefronts, which such launches
-// do not have anyway).
+// and registers for the values in flight.
 template <int S, bool BEST, bool VT, bool AHEAD>
 __global__ __launch_bounds__(kBlock, AHEAD || S >= 64 || (VT && S >= 16) ? 2 : (S >= 32 ? 4 : 6)) void k_resolve_cand_lanes(KArgs) {
-    static_assert(!AHEAD || (BEST && !VT), "the read-ahead form exists for the search with fixed stage times");
+    static_assert(!AHEAD || S < 64, "at 64 stages the read-ahead form's scalars would spill");
     // The arguments are read through kargs() where they are needed (see there): kept in SGPRs
     // across the round loop they would crowd out the loop's own scalars.
     extern __shared__ int lds[];
@@ -662,14 +661,17 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 64 || (VT && S >= 16) ? 2 : (
                         }
                         const int ws = (int)((wpk[s / 4] >> (8 * (s % 4))) & 0xffu);
                         const bool valid = (unsigned)(ws + r) < (unsigned)M;
+                        int t_f_s;
+                        if constexpr (VT) t_f_s = tfv[s];
+                        else t_f_s = tf[j];
                         int fin;
                         if (s == 0) {
                             slot_of[0] = ring_slot(0);
-                            fin = last[0] + tf[j];
+                            fin = last[0] + t_f_s;
                         } else {
                             const int ws_before = (int)((wpk[(s - 1) / 4] >> (8 * ((s - 1) % 4))) & 0xffu);
                             const int arrived = ws == ws_before ? fin_before : ahead[s];
-                            fin = imax(last[s], arrived + cf[s - 1]) + tf[j];
+                            fin = imax(last[s], arrived + cf[s - 1]) + t_f_s;
                         }
                         last[s] = valid ? fin : last[s];
                         if (s < S - 1) *slot_of[s] = fin;
@@ -1244,13 +1246,13 @@ bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws, bool 
 // deeper than the ring, per-scenario stage times at too many stages); from 33 to 64 stages only
 // the candidate-lanes kernel has a size.  The scenario-lanes kernel spends 6 VALU ops per
 // stage and round on 64 scenarios whether or not all 64 lanes carry one; the candidate-lanes
-// kernel spends 13 on 64 pairs.  Measured on 8 192 candidates of configurations 1-3 they cross
-// at 28-32 scenarios for every stage count.  The candidate-lanes kernel is also the only one
-// for the search's paired form.  With per-scenario stage times it keeps 5 S values per lane in
-// registers (two wavefronts per SIMD from 16 stages on, still ahead of the scenario-lanes kernel
-// below 32 scenarios: 0.42 / 1.64 ms against 1.71 ms at 1 / 31 scenarios, S = 32, 8 192
-// candidates) and has no 64-stage size; where it is missing the scenario-lanes kernel wins
-// from 6 scenarios against the general one.
+// kernel spends 15 (13 in its plain form) on 64 pairs.  Measured at 16 and 32 stages they cross
+// at about 28 scenarios on 65 536 candidates and at about 40 on 8 192, where the scenario-lanes
+// kernel works through one candidate per wavefront and its set-up per scenario is not spread
+// over a chunk.  The candidate-lanes kernel is also the only one for the search's paired form.
+// With per-scenario stage times it keeps 5 S values per lane in registers (two wavefronts per
+// SIMD from 16 stages on) and has no 64-stage size; where it is missing the scenario-lanes
+// kernel wins from 6 scenarios against the general one.
 enum ResolveKernel { kScenarioLanes, kCandidateLanes, kGeneralOnly };
 ResolveKernel choose_kernel(int S, long long K, bool stage_times, bool paired) {
     const bool scen_ok = hot_kernel_stages(S) != 0 && !paired;
@@ -1408,16 +1410,13 @@ int launch_cand_lanes_one(KArgs a, int w_bound, hipStream_t st) {
 
 template <bool BEST>
 int launch_cand_lanes(const KArgs &a, int w_bound, hipStream_t st) {
-    // The read-ahead form for launches of fewer wavefronts than two per SIMD (of candidates that
-    // can run, where the caller knows: a.live_hint), or when the tests ask for it.
-    const long long tiles = a.live_hint ? (a.live_hint + 63) / 64 : (a.pair_div ? 1 : a.K) * ((a.C + 63) / 64);
-    const bool ahead = BEST && !a.tfs && (g_kernel_mode == 4 || (g_kernel_mode != 3 && tiles < 2 * 1024));
+    // The read-ahead form wherever it exists (kernel mode 3 asks for the plain one).
+    const bool ahead = g_kernel_mode != 3;
 #define ADAPTRA_CASE(S_)                                                                         \
     case S_:                                                                                     \
         if constexpr (S_ < 64) {      /* 5 S per-lane registers: not at 64 stages */             \
-            if (a.tfs) return launch_cand_lanes_one<S_, BEST, true, false>(a, w_bound, st);      \
-        }                                                                                        \
-        if constexpr (BEST && S_ < 64) {      /* at 64 stages its scalars would spill */        \
+            if (a.tfs) return ahead ? launch_cand_lanes_one<S_, BEST, true, true>(a, w_bound, st)  \
+                                    : launch_cand_lanes_one<S_, BEST, true, false>(a, w_bound, st); \
             if (ahead) return launch_cand_lanes_one<S_, BEST, false, true>(a, w_bound, st);      \
         }                                                                                        \
         return launch_cand_lanes_one<S_, BEST, false, false>(a, w_bound, st);
@@ -1664,7 +1663,7 @@ int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *can
                  int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
                  uint64_t *out_hist,
                  void *workspace, size_t workspace_bytes, void *stream) {
-    return adaptra_detail::best(params, cands, scens, 0, 0, out_best_idx, out_best_makespan, out_best_bubble,
+    return adaptra_detail::best(params, cands, scens, 0, out_best_idx, out_best_makespan, out_best_bubble,
                                 out_hist, workspace, workspace_bytes, stream);
 }
 
@@ -1674,7 +1673,7 @@ int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *can
 // c / pair_div and is evaluated under that scenario only, by the general kernel (its lanes
 // carry candidates, so each may have a scenario of its own).
 int adaptra_detail::best(const adaptra_params_t *params, const adaptra_candidates_t *cands,
-                         const adaptra_scenarios_t *scens, int pair_div, long long live_hint,
+                         const adaptra_scenarios_t *scens, int pair_div,
                          int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
                          uint64_t *out_hist,
                          void *workspace, size_t workspace_bytes, void *stream) {
@@ -1697,7 +1696,6 @@ int adaptra_detail::best(const adaptra_params_t *params, const adaptra_candidate
     a.hist_in_lds = (size_t)a.S * a.hist_bins * 4 <= (size_t)kMaxLdsHistBytes;
     if (pair_div < 0 || (pair_div > 0 && (cands->n + pair_div - 1) / pair_div > scens->n)) return ADAPTRA_EINVAL;
     a.pair_div = pair_div;
-    a.live_hint = live_hint > 0 ? live_hint : 0;
     hipLaunchKernelGGL(k_zero_status, dim3(1), dim3(64), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_prepass, dim3(grid_for(a.C, INT32_MAX)), dim3(kBlock), 0, st, a);

@@ -16,12 +16,10 @@ constexpr int kThreadsPerBlock = 256;
 // Records the hipError_t for adaptra_last_hip_error and returns ADAPTRA_EHIP.
 int hip_fail(hipError_t e);
 
-// adaptra_best with two more arguments: pair_div > 0 evaluates candidate c under scenario
-// c / pair_div only (0: every candidate under every scenario); live_hint > 0 tells how many
-// candidates are expected to run at all (the rest being infeasible on purpose), which lets a
-// small launch take the kernel form made for small launches.
+// adaptra_best with one more argument: pair_div > 0 evaluates candidate c under scenario
+// c / pair_div only (0: every candidate under every scenario).
 int best(const adaptra_params_t *params, const adaptra_candidates_t *cands, const adaptra_scenarios_t *scens,
-         int pair_div, long long live_hint, int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
+         int pair_div, int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
          uint64_t *out_hist, void *workspace, size_t workspace_bytes, void *stream);
 
 // Workspace sections start on 256-byte boundaries.

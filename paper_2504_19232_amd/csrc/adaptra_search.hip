@@ -187,7 +187,7 @@ int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *sc
         const int w_bound = w_top + 1 > a.M - 1 ? a.M - 1 : w_top + 1;
         const adaptra_candidates_t pool{a.C, a.pool, w_bound};
         const long long live = (a.skip_resting ? still_moving : a.K) * (pl.n_moves + 1);
-        int rc = adaptra_detail::best(&bp, &pool, scens, pl.n_moves + 1, live, best_idx, best_mk, nullptr, nullptr,
+        int rc = adaptra_detail::best(&bp, &pool, scens, pl.n_moves + 1, best_idx, best_mk, nullptr, nullptr,
                                       base + pl.off_best_ws, pl.best_ws_bytes, stream);
         if (rc) return rc;
         evaluated += live;
