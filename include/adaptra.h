@@ -269,7 +269,7 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
  *   1  general kernel only (any S, M, warm-up depth)
  *   2  scenario-lanes kernel wherever its limits allow, regardless of lane efficiency
  *   3  candidate-lanes kernel wherever its limits allow, in its plain form
- *   4  the same, in its read-ahead form where that exists (up to 32 stages)
+ *   4  the same, in its read-ahead form (what automatic mode uses)
  * Returns the previous mode, or -1 for an unknown mode (nothing changes). */
 int adaptra_set_kernel_mode(int mode);
 

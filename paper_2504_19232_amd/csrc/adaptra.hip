@@ -565,7 +565,7 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
 // count lands in a slot no live micro-batch uses: slots of live micro-batches differ from it
 // by less than D.  Ring reads follow the previous stage's write in program order, so a link
 // with equal w needs no special case.  S is padded as in the hot kernel.
-// AHEAD (every size but 64 stages): the ring values are read three stages before their use, so
+// AHEAD: the ring values are read three stages before their use, so
 // that the LDS latency is not paid stage by stage (the plain form waits for each read right
 // where it is issued; measured 1.3-1.6 times slower from 16 stages on, whatever the size of the
 // launch).  The read of stage s
@@ -575,7 +575,6 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
 // and registers for the values in flight.
 template <int S, bool BEST, bool VT, bool AHEAD>
 __global__ __launch_bounds__(kBlock, AHEAD || S >= 64 || (VT && S >= 16) ? 2 : (S >= 32 ? 4 : 6)) void k_resolve_cand_lanes(KArgs) {
-    static_assert(!AHEAD || S < 64, "at 64 stages the read-ahead form's scalars would spill");
     // The arguments are read through kargs() where they are needed (see there): kept in SGPRs
     // across the round loop they would crowd out the loop's own scalars.
     extern __shared__ int lds[];
@@ -669,7 +668,13 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 64 || (VT && S >= 16) ? 2 : (
                             slot_of[0] = ring_slot(0);
                             fin = last[0] + t_f_s;
                         } else {
-                            const int ws_before = (int)((wpk[(s - 1) / 4] >> (8 * ((s - 1) % 4))) & 0xffu);
+                            // w does not change over the rounds, and up to 32 stages the compiler keeps
+                            // the S lane masks of this comparison in scalar registers (one instruction
+                            // less per stage and round); at 64 stages they would not fit, so there the
+                            // comparison is made afresh each time.
+                            unsigned w4_before = wpk[(s - 1) / 4];
+                            if constexpr (S >= 64) asm volatile("" : "+v"(w4_before));
+                            const int ws_before = (int)((w4_before >> (8 * ((s - 1) % 4))) & 0xffu);
                             const int arrived = ws == ws_before ? fin_before : ahead[s];
                             fin = imax(last[s], arrived + cf[s - 1]) + t_f_s;
                         }
@@ -1417,9 +1422,9 @@ int launch_cand_lanes(const KArgs &a, int w_bound, hipStream_t st) {
         if constexpr (S_ < 64) {      /* 5 S per-lane registers: not at 64 stages */             \
             if (a.tfs) return ahead ? launch_cand_lanes_one<S_, BEST, true, true>(a, w_bound, st)  \
                                     : launch_cand_lanes_one<S_, BEST, true, false>(a, w_bound, st); \
-            if (ahead) return launch_cand_lanes_one<S_, BEST, false, true>(a, w_bound, st);      \
         }                                                                                        \
-        return launch_cand_lanes_one<S_, BEST, false, false>(a, w_bound, st);
+        return ahead ? launch_cand_lanes_one<S_, BEST, false, true>(a, w_bound, st)              \
+                     : launch_cand_lanes_one<S_, BEST, false, false>(a, w_bound, st);
     switch (cand_kernel_stages(a.S)) {
         ADAPTRA_CASE(2) ADAPTRA_CASE(4) ADAPTRA_CASE(8) ADAPTRA_CASE(16) ADAPTRA_CASE(32) ADAPTRA_CASE(64)
         default: return ADAPTRA_EINVAL;
