@@ -60,3 +60,22 @@ def test_null_arguments_are_rejected_without_touching_the_gpu(binding):
     s = binding.Scenarios(10, 1, 1, None, None)
     rc = lib.adaptra_eval(ctypes.byref(p), ctypes.byref(c), ctypes.byref(s), 1, None, 1, None, 0, None)
     assert rc == binding.EWORKSPACE
+
+
+def test_zb_and_search_reject_bad_arguments_without_touching_the_gpu(binding):
+    lib = binding.load()
+    assert lib.adaptra_zb_eval(None, None, None, None, 0, None, None, None, 0, None) == binding.EINVAL
+    p = binding.Params(4, 8, 1, 1, None, 0, 0)                        # non-null dummies, never dereferenced
+    c = binding.Candidates(10, 1, -1)
+    s = binding.Scenarios(6, 1, 1, None, None)
+    args = (ctypes.byref(p), 1, ctypes.byref(c), ctypes.byref(s))
+    assert lib.adaptra_zb_eval(*args, 6, 1, None, 256, 1 << 30, None) == binding.EINVAL      # plan scenario out of range
+    assert lib.adaptra_zb_eval(*args, -2, 1, None, 256, 1 << 30, None) == binding.EINVAL
+    assert lib.adaptra_zb_eval(*args, -1, 1, None, 256, 64, None) == binding.EWORKSPACE      # too small
+    assert lib.adaptra_zb_eval(*args, -1, 1, None, 257, 1 << 30, None) == binding.EWORKSPACE  # misaligned
+    big = binding.Params(65, 8, 1, 1, None, 0, 0)
+    assert lib.adaptra_zb_workspace_bytes(ctypes.byref(big), 10, 6) == 0                      # more than 64 stages
+    assert lib.adaptra_zb_workspace_bytes(ctypes.byref(p), 10, 6) > 0
+    assert lib.adaptra_search_workspace_bytes(ctypes.byref(p), 6, 2) == 0                     # unknown neighbourhood
+    assert lib.adaptra_search(ctypes.byref(p), ctypes.byref(s), 1, 0, 0, 1, 1, None, None, 256, 1 << 30, None) == binding.EINVAL
+
