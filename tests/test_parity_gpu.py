@@ -458,19 +458,25 @@ ZB_CASES = [(1, 1, 1, 3, 2), (2, 2, 3, 9, 5), (3, 4, 8, 40, 21), (4, 8, 16, 70, 
             (9, 64, 6, 150, 130),         # the largest S; more pairs than resident threads
             (10, 2, 255, 70, 3),          # the most micro-batches the one-word form of the cursors takes
             (11, 3, 256, 30, 4),          # the fewest that need the two-word form
-            (12, 2, 300, 20, 6)]
+            (12, 2, 300, 20, 6),
+            # times in the millions: too large for the (time, stage) words of the earliest-action scan
+            (13, 8, 16, 70, 9, 20000), (14, 19, 9, 30, 5, 3000),
+            (15, 19, 9, 30, 5, 40)]       # 19 stages pad to 24: a stage-index field wider than needed
 
 
-@pytest.mark.parametrize("seed_,S,N,C,K", ZB_CASES, ids=[f"S{c[1]}_N{c[2]}_C{c[3]}_K{c[4]}" for c in ZB_CASES])
-def test_zb_parity(lib, oracle, seed_, S, N, C, K):
+@pytest.mark.parametrize("case", ZB_CASES, ids=["S%d_N%d_C%d_K%d" % c[1:5] + ("_x%d" % c[5] if len(c) > 5 else "") for c in ZB_CASES])
+def test_zb_parity(lib, oracle, case):
     import torch
     b = lib
+    seed_, S, N, C, K = case[:5]
+    scale = case[5] if len(case) > 5 else 1
     rng = np.random.default_rng(seed_)
     t_f, t_b, t_w = rng.integers(1, 60, S), rng.integers(1, 90, S), rng.integers(0, 50, S)
     w = np.sort(rng.integers(-1, N + 3, (S, C)), axis=0)[::-1]
     w[:, ::5] = rng.integers(0, N, (S, len(range(0, C, 5))))           # some not monotone
     cf = rng.integers(0, 400, (max(S - 1, 0), K))
     cb = rng.integers(0, 400, (max(S - 1, 0), K))
+    t_f, t_b, t_w, cf, cb = t_f * scale, t_b * scale, t_w * scale, cf * scale, cb * scale
     prob, t_w_d = _zb_problem(b, S, N, t_f, t_b, t_w, w, cf, cb)
     x = np.clip(w, 0, N - 1) + 1
     # the oracle sweeps every pair, or -- where that takes too long -- whole scenarios from
