@@ -41,6 +41,9 @@
 // by its lanes.  LDS per wavefront: (4 S + 8 ceil(S/8)) x 256 bytes -- the occupancy limit of
 // this kernel, whose step is a chain of dependent LDS round trips that only more resident
 // wavefronts can hide.
+//
+// Fixed plans (generated once per candidate under one scenario, then run under all of them) need
+// none of this when replayed: see k_zb_replay_scen, which puts the scenarios on the lanes.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -111,6 +114,11 @@ struct ZbArgs {
     uint8_t *plans;               // [C][S][3N], op types in the order a stage ran them (written by PHASE 1)
     const uint32_t *packed;       // [ceil(C/64)][S][packed_words(N)][64 candidates], the same at 2 bits per op (see
                                   // packed_words), read by PHASE 2: the lanes of a wavefront read neighbouring words
+    uint16_t *order;              // [C][order_stride] or null: stage | type << 6 | slot << 8 of every op in the order
+                                  // PHASE 1 started them -- a topological order of the plan's dependency graph; slot
+                                  // = micro-batch, N for a weight op (k_zb_replay_scen; N <= 255)
+    uint8_t *plan_ok;             // [C]: the recording ran to its end
+    long long order_stride;       // entries per candidate, a multiple of 16
     unsigned threads;             // of the launch = stride of the queues
     unsigned long long *next_unit;   // work counter of this launch, zero when it starts
 };
@@ -123,6 +131,7 @@ __device__ __forceinline__ int imax2(int a, int b) { return a > b ? a : b; }
 // ONE word, (op / 8), at bit 2 (op % 8).  Words per stage, including the window at the very end:
 __host__ __device__ inline int packed_words(int N) { return 3 * N / 8 + 1; }
 constexpr int kWindow = 8;            // ops of a plan held on chip per stage (16 bits of `hi`)
+constexpr long long kScenReplayFrom = 8;   // scenarios from which a replay puts them on the lanes
 
 // Next action of a stage from its own fields (Algorithm 3): the time it can act, or kInf if
 // nothing it may run has been posted yet.
@@ -256,7 +265,10 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
             const int done = nF + nB + nW;
             const int fin = t + (ty == 0 ? dur_i.x : (ty == 1 ? dur_i.y : dur_i.z));
             makespan = imax2(makespan, fin);
-            if (PHASE == 1 && live) plan[(long long)i * 3 * N + done] = (uint8_t)ty;
+            if (PHASE == 1 && live) {
+                plan[(long long)i * 3 * N + done] = (uint8_t)ty;
+                if (a.order) a.order[c * a.order_stride + step] = (uint16_t)(i | ty << 6 | (ty == 2 ? N : m) << 8);
+            }
             cur.started(ty);
             if (PHASE == 2) cur.advance_window();
             if (ty < 2) {
@@ -288,6 +300,7 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
                 }
             }
         }
+        if (PHASE == 1 && live && a.order) a.plan_ok[c] = makespan != kInf;
         if (PHASE != 1 && live) {
             const long long P = a.C * a.K, item = k * a.C + c;
             a.out_makespan[item] = makespan;
@@ -319,6 +332,93 @@ __global__ void k_zb_pack(const uint8_t *plans, uint32_t *packed, long long C, i
     }
 }
 
+// Fixed plans with the SCENARIOS on the lanes: one wavefront = one candidate's plan under 64
+// scenarios.  A fixed plan needs no decisions: its times are the longest paths of the dependency
+// graph of Section 3.1 (each stage's ops in the plan's order, F(i,m) after F(i-1,m) + delay,
+// B(i,m) after B(i+1,m) + delay), so the ops can be taken in ANY topological order -- here the
+// order in which the generating launch started them (an op starts after everything it depends on
+// has started, forward and backward ops lasting at least 1 us).  That order, with stage, type
+// and micro-batch of every op, is the same for all 64 lanes, i.e. scalar, and was written down
+// by the generating launch (ZbArgs::order); a lane keeps only times, in LDS [index][lane]: the
+// busy-until time of each stage and one ready time per micro-batch (written by the stage that
+// ran the micro-batch last, read by the next stage of its chain: the forward chain up to the
+// last stage, then the backward chain down again).  Every op is the same five steps,
+//     fin = max(busy[i], ready[slot]) + duration;  busy[i] = fin;  ready[slot] = fin + delay,
+// without a case distinction: a forward of stage 0 finds 0 in its slot, a backward of the last
+// stage its own forward's finish (not later than the stage is busy), and a weight op uses a slot
+// of its own with a "delay" of -2^30, so that what it leaves there never exceeds a busy time.
+// Per op: four LDS reads in one round trip (the duration is a broadcast read), one max, two
+// adds, two LDS writes, and the scalar decoding of the entry.
+struct ZbReplayRows {
+    int *busy, *ready, *delay;        // this lane's column of [S], [N + 1], [3][S] rows of 64 lanes
+    const int *dur;                   // [3][S] ints
+    int S;
+};
+__device__ __forceinline__ int zb_replay_op(const ZbReplayRows &t, unsigned entry, int makespan) {
+    const int i = entry & 63, row = (int)((entry >> 6) & 3) * t.S + i, slot = (int)(entry >> 8);
+    const int b = t.busy[i * 64], r = t.ready[slot * 64], d = t.delay[row * 64], length = t.dur[row];
+    const int fin = imax2(b, r) + length;
+    t.busy[i * 64] = fin;
+    t.ready[slot * 64] = fin + d;
+    return imax2(makespan, fin);
+}
+
+__global__ __launch_bounds__(kZbBlock) void k_zb_replay_scen(ZbArgs a) {
+    extern __shared__ int zb_lds[];
+    const int S = a.S, N = a.N, lane = threadIdx.x;
+    ZbReplayRows t;
+    t.S = S;
+    t.busy = zb_lds + lane;                           // [S][64]
+    t.ready = t.busy + S * 64;                        // [N + 1][64]; slot N is the weight ops'
+    t.delay = t.ready + (N + 1) * 64;                 // [3][S][64]: link i -> i+1, link i-1 <- i, -2^30
+    int *const dur = zb_lds + (4 * S + N + 1) * 64;   // [3][S]: t_f, t_b, t_w
+    t.dur = dur;
+    const long long n_tiles = (a.K + kZbBlock - 1) / kZbBlock;
+    const long long c = blockIdx.x / n_tiles;
+    const long long k_lane = (blockIdx.x % n_tiles) * kZbBlock + lane;
+    const bool live = k_lane < a.K;
+    const long long k = live ? k_lane : a.K - 1;
+    for (int i = lane; i < 3 * S; i += kZbBlock) dur[i] = i < S ? a.t_f[i] : (i < 2 * S ? a.t_b[i - S] : a.t_w[i - 2 * S]);
+    for (int i = 0; i < S; ++i) {
+        t.busy[i * 64] = 0;
+        t.delay[i * 64] = i < S - 1 ? a.cf[(long long)i * a.K + k] : 0;
+        t.delay[(S + i) * 64] = i > 0 ? a.cb[(long long)(i - 1) * a.K + k] : 0;
+        t.delay[(2 * S + i) * 64] = -(1 << 30);
+    }
+    for (int m = 0; m <= N; ++m) t.ready[m * 64] = 0;
+    __syncthreads();                                  // the durations (one wavefront: no more than a wait)
+    const uint16_t *const order = a.order + c * a.order_stride;
+    const int total = 3 * S * N;
+    int makespan = 0;
+    // 16 entries per (scalar) load, the next 16 fetched while these run
+    const uint4 *const order16 = reinterpret_cast<const uint4 *>(order);
+    const bool recorded = a.plan_ok[c] != 0;          // else the entries are not a plan: nothing is run
+    uint4 lo = order16[0], hi = order16[1];
+    int base = recorded ? 0 : total;
+    for (; base + 16 <= total; base += 16) {
+        const unsigned word[8] = {(unsigned)__builtin_amdgcn_readfirstlane((int)lo.x), (unsigned)__builtin_amdgcn_readfirstlane((int)lo.y),
+                                  (unsigned)__builtin_amdgcn_readfirstlane((int)lo.z), (unsigned)__builtin_amdgcn_readfirstlane((int)lo.w),
+                                  (unsigned)__builtin_amdgcn_readfirstlane((int)hi.x), (unsigned)__builtin_amdgcn_readfirstlane((int)hi.y),
+                                  (unsigned)__builtin_amdgcn_readfirstlane((int)hi.z), (unsigned)__builtin_amdgcn_readfirstlane((int)hi.w)};
+        if (base + 16 < total) {                      // inside the candidate's padded row
+            lo = order16[base / 8 + 2];
+            hi = order16[base / 8 + 3];
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) makespan = zb_replay_op(t, (word[j >> 1] >> ((j & 1) * 16)) & 0xffffu, makespan);
+    }
+    for (; base < total; ++base)
+        makespan = zb_replay_op(t, (unsigned)__builtin_amdgcn_readfirstlane((int)order[base]), makespan);
+    if (!recorded) makespan = kInf;                   // the recording stopped: so does every replay of it
+    if (live) {
+        const long long P = a.C * a.K, item = k * a.C + c;
+        a.out_makespan[item] = makespan;
+        if (a.out_bubble)
+            for (int i = 0; i < S; ++i)
+                a.out_bubble[(long long)i * P + item] = makespan == kInf ? kInf : makespan - N * (dur[i] + dur[S + i] + dur[2 * S + i]);
+    }
+}
+
 __global__ void k_zb_reset(unsigned long long *counters) {
     if (threadIdx.x < 2) counters[threadIdx.x] = 0;
 }
@@ -326,8 +426,10 @@ __global__ void k_zb_reset(unsigned long long *counters) {
 
 struct ZbPlan {
     bool narrow;                  // generation (PHASE 0, 1) in the one-word form of the cursors
+    bool scen_lanes;              // replay with the scenarios on the lanes (k_zb_replay_scen)
     unsigned threads, threads_replay;
-    size_t lds, lds_replay, off_counters, off_scratch, off_plans, off_packed, total;
+    long long order_stride;
+    size_t lds, lds_replay, lds_scen, off_counters, off_scratch, off_plans, off_packed, off_order, off_plan_ok, total;
 };
 
 // Enough threads to fill the chip at the occupancy the LDS state allows (at most 160 KiB per CU,
@@ -359,6 +461,15 @@ bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
     p->off_scratch = o; o += adaptra_detail::align256((size_t)p->threads * per_thread);
     p->off_plans = o;   o += adaptra_detail::align256((size_t)C * S * 3 * N);
     p->off_packed = o;  o += adaptra_detail::align256((size_t)((C + kZbBlock - 1) / kZbBlock) * kZbBlock * S * packed_words(N) * 4);
+    // Scenario lanes fill 64 lanes with K scenarios of one candidate, candidate lanes with 64
+    // candidates of one scenario, at several times the work per pair: scenario lanes from
+    // kScenReplayFrom scenarios on, while the slot of an op fits its entry's byte, a wavefront's
+    // state the LDS of a CU and the grid its limit.
+    p->order_stride = (3ll * S * N + 15) / 16 * 16 + 16;        // the loads run one block of 16 ahead
+    p->lds_scen = (((size_t)4 * S + (size_t)N + 1) * 64 + 3 * (size_t)S) * 4;
+    p->scen_lanes = K >= kScenReplayFrom && N <= 255 && p->lds_scen <= (160u << 10) && C * ((K + kZbBlock - 1) / kZbBlock) <= INT32_MAX;
+    p->off_order = o;   o += adaptra_detail::align256(p->scen_lanes ? (size_t)C * (size_t)p->order_stride * 2 : 0);
+    p->off_plan_ok = o; o += adaptra_detail::align256(p->scen_lanes ? (size_t)C : 0);
     p->total = o;
     return true;
 }
@@ -412,12 +523,25 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
     unsigned long long *counters = (unsigned long long *)((char *)workspace + p.off_counters);
     hipLaunchKernelGGL(k_zb_reset, dim3(1), dim3(64), 0, st, counters);
     ADAPTRA_CHECK_LAUNCH();
+    a.order = p.scen_lanes && plan_scenario >= 0 ? (uint16_t *)((char *)workspace + p.off_order) : nullptr;
+    a.plan_ok = (uint8_t *)workspace + p.off_plan_ok;
+    a.order_stride = p.order_stride;
     a.next_unit = counters;
     if (plan_scenario < 0)
         return p.narrow ? launch_zb<0, true>(a, a.K, p.threads, p.lds, st) : launch_zb<0, false>(a, a.K, p.threads, p.lds, st);
     // one plan per candidate, under the plan scenario
     int rc = p.narrow ? launch_zb<1, true>(a, 1, p.threads, p.lds, st) : launch_zb<1, false>(a, 1, p.threads, p.lds, st);
     if (rc) return rc;
+    if (p.scen_lanes) {
+        if (p.lds_scen > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute((const void *)k_zb_replay_scen, hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_scen);
+            if (e != hipSuccess) return adaptra_detail::hip_fail(e);
+        }
+        const long long blocks = a.C * ((a.K + kZbBlock - 1) / kZbBlock);
+        hipLaunchKernelGGL(k_zb_replay_scen, dim3((unsigned)blocks), dim3(kZbBlock), p.lds_scen, st, a);
+        ADAPTRA_CHECK_LAUNCH();
+        return ADAPTRA_OK;
+    }
     const long long words = (a.C + kZbBlock - 1) / kZbBlock * kZbBlock * a.S * packed_words(a.N);
     hipLaunchKernelGGL(k_zb_pack, dim3((unsigned)adaptra_detail::blocks_for(words, 1 << 16)), dim3(adaptra_detail::kThreadsPerBlock), 0, st,
                        a.plans, packed, a.C, a.S, a.N);

@@ -461,7 +461,9 @@ ZB_CASES = [(1, 1, 1, 3, 2), (2, 2, 3, 9, 5), (3, 4, 8, 40, 21), (4, 8, 16, 70, 
             (12, 2, 300, 20, 6),
             # times in the millions: too large for the (time, stage) words of the earliest-action scan
             (13, 8, 16, 70, 9, 20000), (14, 19, 9, 30, 5, 3000),
-            (15, 19, 9, 30, 5, 40)]       # 19 stages pad to 24: a stage-index field wider than needed
+            (15, 19, 9, 30, 5, 40),       # 19 stages pad to 24: a stage-index field wider than needed
+            # fixed plans are replayed with the scenarios on the lanes from 8 scenarios on, up to 255 micro-batches
+            (16, 2, 255, 20, 9), (17, 3, 256, 12, 9), (18, 5, 40, 9, 8), (19, 5, 40, 9, 7)]
 
 
 @pytest.mark.parametrize("case", ZB_CASES, ids=["S%d_N%d_C%d_K%d" % c[1:5] + ("_x%d" % c[5] if len(c) > 5 else "") for c in ZB_CASES])
@@ -489,14 +491,16 @@ def test_zb_parity(lib, oracle, case):
     assert np.array_equal(bub.cpu().numpy()[:, ks], ref["idle"])
     # fixed plans generated under scenario 1 (or 0), replayed under every scenario
     kp = 1 if K > 1 else 0
-    mkp, _ = b.adaptra_zb_eval(prob, t_w_d, kp, want_bubble=False)
+    mkp, bubp = b.adaptra_zb_eval(prob, t_w_d, kp)
     torch.cuda.synchronize()
-    mkp = mkp.cpu().numpy()
+    mkp, bubp = mkp.cpu().numpy(), bubp.cpu().numpy()
+    busy = N * (np.asarray(t_f) + np.asarray(t_b) + np.asarray(t_w))
     for c in range(0, C, max(1, C // 12)):
         gen = oracle.zb_simulate(S, N, t_f, t_b, t_w, cf[:, kp], cb[:, kp], x=x[:, c])
         for k in range(0, K, max(1, K // 6)):
             rep = oracle.zb_simulate(S, N, t_f, t_b, t_w, cf[:, k], cb[:, k], order=gen["order"])
             assert mkp[k, c] == rep["makespan"], (c, k)
+            assert np.array_equal(bubp[:, k, c], rep["makespan"] - busy), (c, k)
 
 
 def test_zb_benchmarked_shape(lib, oracle):
