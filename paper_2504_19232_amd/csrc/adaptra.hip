@@ -781,8 +781,14 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 64 || (VT && S >= 16) ? 2 : (
 // slot-major layout [slot][lane] keeps every access conflict-free.  The reads are software
 // pipelined: each is issued several stages (or, for the first stages, a whole backward
 // sweep) ahead of its use, so the LDS latency does not stall every stage.
+//
+// Blocks per CU: what the LDS rings allow.  With per-scenario stage times (VT) the S addends
+// are per lane and the 32-stage size needs about 150 VGPRs; held to 128 it spills 32 of them,
+// but only in the code between the three phases -- the loop over the steady rounds touches no
+// scratch memory -- and four wavefronts per SIMD instead of three are worth 23 % (16 stages:
+// six blocks instead of five, 6 %).
 template <int S, bool BEST, bool VT>
-__global__ __launch_bounds__(kBlock, S >= 32 ? (VT ? 3 : ADAPTRA_WAVES32) : (S >= 16 && VT ? 5 : 6)) void k_resolve_scen_lanes(KArgs) {
+__global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resolve_scen_lanes(KArgs) {
     // The arguments are read through kargs() where they are needed (see there), never
     // through the by-value parameter.
     extern __shared__ int lds[];
