@@ -1258,14 +1258,14 @@ bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws, bool 
 // the candidate-lanes kernel has a size.  The scenario-lanes kernel spends 6 VALU ops per
 // stage and round on 64 scenarios whether or not all 64 lanes carry one; the candidate-lanes
 // kernel spends 15 (13 in its plain form) on 64 pairs.  Measured at 16 and 32 stages they cross
-// at about 28 scenarios on 65 536 candidates and at about 40 on 8 192, where the scenario-lanes
+// at about 29 scenarios on 65 536 candidates and at about 44 on 8 192, where the scenario-lanes
 // kernel works through one candidate per wavefront and its set-up per scenario is not spread
 // over a chunk.  The candidate-lanes kernel is also the only one for the search's paired form.
 // With per-scenario stage times it keeps 5 S values per lane in registers (two wavefronts per
 // SIMD from 16 stages on) and has no 64-stage size; where it is missing the scenario-lanes
 // kernel wins from 6 scenarios against the general one.
 enum ResolveKernel { kScenarioLanes, kCandidateLanes, kGeneralOnly };
-ResolveKernel choose_kernel(int S, long long K, bool stage_times, bool paired) {
+ResolveKernel choose_kernel(int S, long long K, long long C, bool stage_times, bool paired) {
     const bool scen_ok = hot_kernel_stages(S) != 0 && !paired;
     const bool cand_ok = cand_kernel_stages(S) != 0 && !(stage_times && cand_kernel_stages(S) >= 64);
     switch (g_kernel_mode) {
@@ -1275,7 +1275,8 @@ ResolveKernel choose_kernel(int S, long long K, bool stage_times, bool paired) {
         case 4: return cand_ok ? kCandidateLanes : kGeneralOnly;
         default: break;
     }
-    if (scen_ok && (K >= 32 || (!cand_ok && K >= 6))) return kScenarioLanes;
+    const long long scen_from = C >= 32768 ? 29 : 44;          // the measured crossover
+    if (scen_ok && (K >= scen_from || (!cand_ok && K >= 6))) return kScenarioLanes;
     if (cand_ok) return kCandidateLanes;
     return kGeneralOnly;
 }
@@ -1467,7 +1468,7 @@ template <bool BEST>
 int launch_resolve(KArgs a, const Workspace &ws, int w_bound, hipStream_t st, int *direct = nullptr) {
     int rc;
     if (direct) *direct = -1;
-    const ResolveKernel which = choose_kernel(a.S, a.K, a.tfs != nullptr, a.pair_div != 0);
+    const ResolveKernel which = choose_kernel(a.S, a.K, a.C, a.tfs != nullptr, a.pair_div != 0);
     if (which != kGeneralOnly) {
         const bool hot = which == kScenarioLanes;
         a.cls_hi = kNumRingClasses - 1;
