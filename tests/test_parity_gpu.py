@@ -463,7 +463,8 @@ ZB_CASES = [(1, 1, 1, 3, 2), (2, 2, 3, 9, 5), (3, 4, 8, 40, 21), (4, 8, 16, 70, 
             (13, 8, 16, 70, 9, 20000), (14, 19, 9, 30, 5, 3000),
             (15, 19, 9, 30, 5, 40),       # 19 stages pad to 24: a stage-index field wider than needed
             # fixed plans are replayed with the scenarios on the lanes from 8 scenarios on, up to 255 micro-batches
-            (16, 2, 255, 20, 9), (17, 3, 256, 12, 9), (18, 5, 40, 9, 8), (19, 5, 40, 9, 7)]
+            (16, 2, 255, 20, 9), (17, 3, 256, 12, 9), (18, 5, 40, 9, 8), (19, 5, 40, 9, 7),
+            (20, 64, 255, 3, 8)]          # the largest per-wavefront state of that replay (129 KiB of LDS)
 
 
 @pytest.mark.parametrize("case", ZB_CASES, ids=["S%d_N%d_C%d_K%d" % c[1:5] + ("_x%d" % c[5] if len(c) > 5 else "") for c in ZB_CASES])
