@@ -132,6 +132,7 @@ __device__ __forceinline__ int imax2(int a, int b) { return a > b ? a : b; }
 __host__ __device__ inline int packed_words(int N) { return 3 * N / 8 + 1; }
 constexpr int kWindow = 8;            // ops of a plan held on chip per stage (16 bits of `hi`)
 constexpr long long kScenReplayFrom = 8;   // scenarios from which a replay puts them on the lanes
+constexpr int kXcds = 8;              // accelerator dies of an MI355X; workgroup b is dispatched to die b mod 8
 
 // Next action of a stage from its own fields (Algorithm 3): the time it can act, or kInf if
 // nothing it may run has been posted yet.
@@ -373,9 +374,18 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_replay_scen(ZbArgs a) {
     t.delay = t.ready + (N + 1) * 64;                 // [3][S][64]: link i -> i+1, link i-1 <- i, -2^30
     int *const dur = zb_lds + (4 * S + N + 1) * 64;   // [3][S]: t_f, t_b, t_w
     t.dur = dur;
+    // Block -> (candidate, tile of 64 scenarios).  A lane's results lie C ints apart, so the 4-byte
+    // stores of one wavefront share no cache line; those of NEIGHBOURING candidates do (16 per 64
+    // bytes).  Workgroups go round the 8 XCDs by their index, each XCD with an L2 of its own, so
+    // each XCD takes one contiguous eighth of the candidates: the wavefronts that fill a line then
+    // run next to each other on the same L2, which merges their stores before the line goes to
+    // memory (with candidate = block index the same stores reached HBM as 11 times the bytes).
     const long long n_tiles = (a.K + kZbBlock - 1) / kZbBlock;
-    const long long c = blockIdx.x / n_tiles;
-    const long long k_lane = (blockIdx.x % n_tiles) * kZbBlock + lane;
+    const long long per_xcd = (a.C + kXcds - 1) / kXcds;
+    const long long in_xcd = blockIdx.x / kXcds;
+    const long long c = (blockIdx.x % kXcds) * per_xcd + in_xcd / n_tiles;
+    if (in_xcd / n_tiles >= per_xcd || c >= a.C) return;          // the last eighth may be short
+    const long long k_lane = (in_xcd % n_tiles) * kZbBlock + lane;
     const bool live = k_lane < a.K;
     const long long k = live ? k_lane : a.K - 1;
     for (int i = lane; i < 3 * S; i += kZbBlock) dur[i] = i < S ? a.t_f[i] : (i < 2 * S ? a.t_b[i - S] : a.t_w[i - 2 * S]);
@@ -467,7 +477,8 @@ bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
     // state the LDS of a CU and the grid its limit.
     p->order_stride = (3ll * S * N + 15) / 16 * 16 + 16;        // the loads run one block of 16 ahead
     p->lds_scen = (((size_t)4 * S + (size_t)N + 1) * 64 + 3 * (size_t)S) * 4;
-    p->scen_lanes = K >= kScenReplayFrom && N <= 255 && p->lds_scen <= (160u << 10) && C * ((K + kZbBlock - 1) / kZbBlock) <= INT32_MAX;
+    p->scen_lanes = K >= kScenReplayFrom && N <= 255 && p->lds_scen <= (160u << 10) &&
+                    ((C + kXcds - 1) / kXcds) * kXcds * ((K + kZbBlock - 1) / kZbBlock) <= INT32_MAX;
     p->off_order = o;   o += adaptra_detail::align256(p->scen_lanes ? (size_t)C * (size_t)p->order_stride * 2 : 0);
     p->off_plan_ok = o; o += adaptra_detail::align256(p->scen_lanes ? (size_t)C : 0);
     p->total = o;
@@ -537,7 +548,7 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
             hipError_t e = hipFuncSetAttribute((const void *)k_zb_replay_scen, hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_scen);
             if (e != hipSuccess) return adaptra_detail::hip_fail(e);
         }
-        const long long blocks = a.C * ((a.K + kZbBlock - 1) / kZbBlock);
+        const long long blocks = (a.C + kXcds - 1) / kXcds * kXcds * ((a.K + kZbBlock - 1) / kZbBlock);
         hipLaunchKernelGGL(k_zb_replay_scen, dim3((unsigned)blocks), dim3(kZbBlock), p.lds_scen, st, a);
         ADAPTRA_CHECK_LAUNCH();
         return ADAPTRA_OK;
