@@ -133,6 +133,7 @@ __host__ __device__ inline int packed_words(int N) { return 3 * N / 8 + 1; }
 constexpr int kWindow = 8;            // ops of a plan held on chip per stage (16 bits of `hi`)
 constexpr long long kScenReplayFrom = 8;   // scenarios from which a replay puts them on the lanes
 constexpr int kXcds = 8;              // accelerator dies of an MI355X; workgroup b is dispatched to die b mod 8
+constexpr int kCus = 256;             // compute units of an MI355X
 
 // Next action of a stage from its own fields (Algorithm 3): the time it can act, or kInf if
 // nothing it may run has been posted yet.
@@ -151,7 +152,10 @@ __device__ __forceinline__ int next_action(int busy, const Cursors<NARROW> &c, u
 
 // PHASE 0: generate with the policy and write the outputs; 1: generate under the plan scenario
 // and record each stage's op types; 2: replay the recorded plans under every scenario.
-template <int PHASE, bool NARROW>
+// QLDS: the two queues per stage in LDS behind the other state instead of in global scratch --
+// for a launch whose wavefronts are so few (the recording of fixed plans: one scenario) that each
+// has a CU's LDS to itself and nothing hides the latency of its queue accesses to memory.
+template <int PHASE, bool NARROW, bool QLDS = false>
 __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
     static_assert(!(PHASE == 2 && NARROW), "a replay keeps its window of coming ops in the wide form");
     typedef Cursors<NARROW> Cur;
@@ -166,8 +170,9 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
         const int s = i >> 2, ty = i & 3;
         dur[i] = ty == 0 ? a.t_f[s] : (ty == 1 ? a.t_b[s] : (ty == 2 ? a.t_w[s] : 0));
     }
-    int *const queue = a.scratch + ((long long)blockIdx.x * kZbBlock + threadIdx.x);
-    const unsigned nt = a.threads;
+    // queue entry e of this lane at queue[e * nt]
+    int *const queue = QLDS ? delay + 2 * S + threadIdx.x : a.scratch + ((long long)blockIdx.x * kZbBlock + threadIdx.x);
+    const unsigned nt = QLDS ? (unsigned)kZbBlock : a.threads;
     // A unit of work = one scenario x 64 consecutive candidates (the last chunk may be short:
     // its spare lanes repeat the last candidate and write nothing).  Wavefronts draw units from
     // a counter, so one that becomes resident late (the launch may hold a few more than fit at
@@ -485,15 +490,15 @@ bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
     return true;
 }
 
-template <int PHASE, bool NARROW>
+template <int PHASE, bool NARROW, bool QLDS = false>
 int launch_zb(ZbArgs a, long long scenarios, unsigned full, size_t lds, hipStream_t st) {
     if (lds > 48 * 1024) {                                   // above the default dynamic-LDS limit
-        hipError_t e = hipFuncSetAttribute((const void *)k_zb<PHASE, NARROW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute((const void *)k_zb<PHASE, NARROW, QLDS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return adaptra_detail::hip_fail(e);
     }
     const long long units = (a.C + kZbBlock - 1) / kZbBlock * scenarios;   // one wavefront each, at most `full` threads at a time
     a.threads = (unsigned)(units < (long long)(full / kZbBlock) ? units : (long long)(full / kZbBlock)) * kZbBlock;
-    hipLaunchKernelGGL((k_zb<PHASE, NARROW>), dim3(a.threads / kZbBlock), dim3(kZbBlock), lds, st, a);
+    hipLaunchKernelGGL((k_zb<PHASE, NARROW, QLDS>), dim3(a.threads / kZbBlock), dim3(kZbBlock), lds, st, a);
     ADAPTRA_CHECK_LAUNCH();
     return ADAPTRA_OK;
 }
@@ -541,7 +546,14 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
     if (plan_scenario < 0)
         return p.narrow ? launch_zb<0, true>(a, a.K, p.threads, p.lds, st) : launch_zb<0, false>(a, a.K, p.threads, p.lds, st);
     // one plan per candidate, under the plan scenario
-    int rc = p.narrow ? launch_zb<1, true>(a, 1, p.threads, p.lds, st) : launch_zb<1, false>(a, 1, p.threads, p.lds, st);
+    // With no more wavefronts than CUs each has a CU's LDS to itself: the queues go there.
+    const size_t lds_queues = p.lds + (size_t)2 * a.S * a.N * kZbBlock * 4;
+    const bool queues_in_lds = (a.C + kZbBlock - 1) / kZbBlock <= kCus && lds_queues <= (160u << 10);
+    int rc;
+    if (queues_in_lds)
+        rc = p.narrow ? launch_zb<1, true, true>(a, 1, kCus * kZbBlock, lds_queues, st) : launch_zb<1, false, true>(a, 1, kCus * kZbBlock, lds_queues, st);
+    else
+        rc = p.narrow ? launch_zb<1, true>(a, 1, p.threads, p.lds, st) : launch_zb<1, false>(a, 1, p.threads, p.lds, st);
     if (rc) return rc;
     if (p.scen_lanes) {
         if (p.lds_scen > 48 * 1024) {
