@@ -972,6 +972,17 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resol
                         ADAPTRA_READ_AHEAD(s);
                     });
                     ADAPTRA_READ_NEXT_ROUND();
+                    if constexpr (!VT) {
+                        // The stages out of forwards run B after B: their backward duration is
+                        // added first (independent adds, the sweep over them ends at `done`),
+                        // then the backward sweep is the steady one, without a test per stage.
+                        stages_below<0, S>(done, ADAPTRA_STAGE_LAMBDA(si) {
+                            constexpr int s = decltype(si)::value;
+                            L[s] += ADAPTRA_TB(s);
+                        });
+                        ADAPTRA_B_SWEEP();
+                        continue;
+                    }
                     int carry = 0;
                     __builtin_amdgcn_s_setprio(kPrioBackward);
                     stages_down<S - 1, 0>(ADAPTRA_STAGE_LAMBDA(si) {
