@@ -931,21 +931,45 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : 6) void k_resol
         __builtin_amdgcn_s_setprio(kPrioForward);                               \
     } while (0)
 
-            // warm-up rounds r = -W .. 0: forwards only, each after a forward.  Stage s has
-            // started once w[s] + r >= 0; w is non-increasing, so the running stages are
-            // 0 .. nv-1 and the sweep stops at the first one that has not started.
-            {
-                int nv = 0;
-                for (int r = -W; r <= 0; ++r) {
-                    while (nv < S && __builtin_amdgcn_readlane(wq_lanes, nv) + r >= 0) ++nv;
-                    stages_below<0, S>(nv, ADAPTRA_STAGE_LAMBDA(si) {
-                        constexpr int s = decltype(si)::value;
-                        ADAPTRA_F_OP(s, add_f[s]);
-                        ADAPTRA_READ_AHEAD(s);
-                    });
-                    ADAPTRA_READ_NEXT_ROUND();
+            // warm-up rounds r = -W .. 0: forwards only, each after a forward; stage s takes part
+            // once w[s] + r >= 0, i.e. with its micro-batches 0 .. w[s].
+            // They are taken stage by stage rather than round by round: stage s runs its
+            // w[s] + 1 forwards back to back.  Everything they wait for is there -- the stage
+            // before has run at least as many (w is non-increasing) -- so a link without slack
+            // needs no special case here, the ring is read four micro-batches at a time ahead of
+            // their use, no stage is tested for having started, and the ring ends up exactly as
+            // after the rounds (micro-batch m in slot m, left by the last stage that ran it; no
+            // slot index wraps, since w[0] + 1 <= D).
+            stages_up<0, S>(ADAPTRA_STAGE_LAMBDA(si) {
+                constexpr int s = decltype(si)::value;
+                const int n = __builtin_amdgcn_readlane(wq_lanes, s) + 1;
+                unsigned at = ring + bias;                        // slot 0 of this lane
+                int i = 0;
+                for (; i + 4 <= n; i += 4) {
+                    int from_before[4];
+                    if constexpr (s > 0) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) from_before[j] = *(lds_int *)(at + 256u * j);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        L[s] += add_f[s];
+                        if constexpr (s > 0) L[s] = imax(L[s], from_before[j]);
+                        if constexpr (s < S - 1) *(lds_int *)(at + 256u * j) = L[s];
+                    }
+                    at += 1024u;
                 }
-            }
+                for (; i < n; ++i) {
+                    L[s] += add_f[s];
+                    if constexpr (s > 0) L[s] = imax(L[s], *(lds_int *)at);
+                    if constexpr (s < S - 1) *(lds_int *)at = L[s];
+                    at += 256u;
+                }
+                // the stage's next micro-batch: slot n, or slot 0 again if the ring has just n slots
+                const unsigned next = bias + 256u * (unsigned)n;     // 0 = one past the last slot
+                soff[s] = next == 0u ? bias : next;
+            });
+            ADAPTRA_READ_NEXT_ROUND();
             ADAPTRA_B_SWEEP();                    // B(s, 0): each after a forward
 #pragma unroll
             for (int s = 0; s < S; ++s) add_f[s] += ADAPTRA_TB(s);
