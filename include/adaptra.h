@@ -261,7 +261,7 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
 
 /* Kernel selection, process-wide; for tests and measurements.
  *   0  automatic (default): up to 32 stages, the register/LDS kernel with scenarios on the
- *      lanes from 44 scenarios on (from 29 with at least 32768 candidates), below that -- and
+ *      lanes from 48 scenarios on (from 33 with at least 32768 candidates), below that -- and
  *      from 33 to 64 stages always -- the kernel with candidates on the lanes, in its read-ahead
  *      form (the measured crossover); the general kernel for what fits
  *      neither (per-scenario stage times at more than 32 stages, warm-ups deeper than the LDS

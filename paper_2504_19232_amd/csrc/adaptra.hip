@@ -559,9 +559,9 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
 //   w                    S bytes packed into S / 4 VGPRs
 //   fwd[m]               LDS ring [slot][lane], D slots per wavefront as in the hot kernel,
 //                        slot = m mod D with a per-lane index (bank = lane: conflict-free)
-// Plain form of the Section 3.1 recurrence (see the general kernel).  All lanes walk the
-// rounds r = -max w[0] .. M-1 together; a lane's forward step of stage s counts only if its
-// micro-batch w[s] + r exists (a select, no divergence).  The write of a step that does not
+// Plain form of the Section 3.1 recurrence (see the general kernel).  After the fill phase (taken
+// stage by stage, see there) all lanes walk the rounds r = 0 .. M-1 together; a lane's forward
+// step of stage s counts only if its micro-batch w[s] + r exists (a select, no divergence).  The write of a step that does not
 // count lands in a slot no live micro-batch uses: slots of live micro-batches differ from it
 // by less than D.  Ring reads follow the previous stage's write in program order, so a link
 // with equal w needs no special case.  S is padded as in the hot kernel.
@@ -627,13 +627,44 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 64 || (VT && S >= 16) ? 2 : (
                 tbv[s] = real ? kargs()->tbs[(long long)s * kargs()->Kin + kin] : 0;
             }
         }
-        int w0max = (int)(wpk[0] & 0xffu);
+        // The rounds before r = 1 hold only forwards up to the last one, and what those wait for
+        // is there once the stage before has run its own (w is non-increasing): they are taken
+        // stage by stage.  Stage s runs its micro-batches 0 .. w[s] back to back; micro-batch i
+        // sits in slot i for every lane (no index wraps: w < D), a lane whose stage has fewer
+        // warm-up forwards than another lane's keeps its state and puts back what it read.  No
+        // per-lane slot arithmetic, no test for the micro-batch's existence beyond i <= w[s], no
+        // special case for links without slack -- and no rounds in which only a few stages of a
+        // few lanes have work.  (Four micro-batches per iteration with their ring values read
+        // together measured slower: 64 against 52 ms on the guided search.)
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) w0max = imax(w0max, __shfl_xor(w0max, off));
-        w0max = uni(w0max);
-        int b = w0max == 0 ? 0 : D - w0max;              // (-w0max) mod D: the ring slot of micro-batch r
-        for (int r = -w0max; r < M; ++r) {
-            if constexpr (AHEAD) {                       // forward sweep, ring reads three stages ahead
+        for (int s = 0; s < S; ++s) {
+            const int ws = (int)((wpk[s / 4] >> (8 * (s % 4))) & 0xffu);
+            int t_f_s;
+            if constexpr (VT) t_f_s = tfv[s];
+            else t_f_s = ((const ConstInt *)kargs()->tpad)[s];
+            int *p = ring;
+            int arrived = s > 0 ? *p : 0;
+            for (int i = 0;; ++i) {
+                const bool valid = i <= ws;              // implies i < D
+                if (__ballot(valid) == 0ull) break;
+                int arrived_next = 0;
+                if (s > 0 && i + 1 < D) arrived_next = p[64];      // the next slot, read ahead
+                const int fin = (s == 0 ? last[0] : imax(last[s], arrived + cf[s > 0 ? s - 1 : 0])) + t_f_s;
+                last[s] = valid ? fin : last[s];
+                if (s == 0) {
+                    if (valid && S > 1) *p = fin;
+                } else if (s < S - 1) {
+                    *p = valid ? fin : arrived;
+                }
+                p += 64;
+                arrived = arrived_next;
+            }
+        }
+        int b = 0;                                       // the ring slot of micro-batch r (r mod D)
+        for (int r = 0; r < M; ++r) {
+            if (r == 0) {
+                // round 0's forwards were the last of the fill phase
+            } else if constexpr (AHEAD) {                // forward sweep, ring reads three stages ahead
                 constexpr int kAhead = S - 1 < 3 ? S - 1 : 3;
                 int *slot_of[S];
                 int ahead[S];
@@ -1293,7 +1324,7 @@ bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws, bool 
 // the candidate-lanes kernel has a size.  The scenario-lanes kernel spends 6 VALU ops per
 // stage and round on 64 scenarios whether or not all 64 lanes carry one; the candidate-lanes
 // kernel spends 15 (13 in its plain form) on 64 pairs.  Measured at 16 and 32 stages they cross
-// at about 29 scenarios on 65 536 candidates and at about 44 on 8 192, where the scenario-lanes
+// at about 33 scenarios on 65 536 candidates and at about 48 on 8 192, where the scenario-lanes
 // kernel works through one candidate per wavefront and its set-up per scenario is not spread
 // over a chunk.  The candidate-lanes kernel is also the only one for the search's paired form.
 // With per-scenario stage times it keeps 5 S values per lane in registers (two wavefronts per
@@ -1310,7 +1341,7 @@ ResolveKernel choose_kernel(int S, long long K, long long C, bool stage_times, b
         case 4: return cand_ok ? kCandidateLanes : kGeneralOnly;
         default: break;
     }
-    const long long scen_from = C >= 32768 ? 29 : 44;          // the measured crossover
+    const long long scen_from = C >= 32768 ? 33 : 48;          // the measured crossover
     if (scen_ok && (K >= scen_from || (!cand_ok && K >= 6))) return kScenarioLanes;
     if (cand_ok) return kCandidateLanes;
     return kGeneralOnly;
