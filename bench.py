@@ -56,31 +56,67 @@ class HipEvents:
         self.hip.hipEventDestroy(ev)
 
 
-def traffic_from_profile(S: int, config: int):
-    """HBM bytes per launch of the resolve kernel, as measured with rocprofv3 (FETCH_SIZE and
-    WRITE_SIZE, scaled by a copy of known size) and recorded in the committed summary; None
-    if there is no summary for this workload.  It cannot be measured from inside this process."""
+def kernel_source_sha256() -> str:
+    """Hash of the library's sources (csrc/ and include/): rocprofv3 summaries under profiles/
+    carry the hash of the sources they were measured on, so that figures taken from them can be
+    dropped when the kernels have changed since."""
+    import hashlib
+    h = hashlib.sha256()
+    for folder in (os.path.join(ROOT, "paper_2504_19232_amd", "csrc"), os.path.join(ROOT, "include")):
+        for name in sorted(os.listdir(folder)):
+            if name.endswith((".hip", ".h")):
+                h.update(name.encode())
+                h.update(open(os.path.join(folder, name), "rb").read())
+    return h.hexdigest()
+
+
+def from_profile(S: int, config: int) -> dict:
+    """Figures that cannot be measured from inside this process, read from the committed
+    rocprofv3 summary of the resolve kernel on this workload: HBM bytes per launch (FETCH_SIZE
+    and WRITE_SIZE, scaled by a copy of known size) and the vector instructions the kernel
+    issues per launch (SQ_INSTS_VALU), split into the ones that take a full issue slot and the
+    selects.  Every value is None when there is no summary or when the summary was measured on
+    other sources than the ones in the tree now."""
+    out = {"traffic": None, "valu_instructions": None, "valu_select_instructions": None, "profile_is_current": False}
     path = os.path.join(ROOT, "profiles", f"resolve_scen_lanes_S{S}_config{config}.txt")
     try:
-        for line in open(path):
-            if line.strip().startswith("traffic_bytes_per_launch["):
-                return int(line.split("=")[1])
+        lines = open(path).read().splitlines()
     except OSError:
-        pass
-    return None
-
-
-def issued_from_profile(S: int, config: int):
-    """Issued int32 VALU lane-ops/s of the resolve kernel from the committed rocprofv3 counter
-    summary (SQ_INSTS_VALU x 64 / kernel time), in T lane-ops/s; None without a summary."""
-    path = os.path.join(ROOT, "profiles", f"resolve_scen_lanes_S{S}_config{config}.txt")
+        return out
+    found = {}
+    for line in lines:
+        s = line.strip()
+        for key in ("source_sha256", "traffic_bytes_per_launch", "valu_instructions_per_launch",
+                    "valu_select_instructions_per_launch"):
+            if s.startswith(key) and "=" in s:
+                found[key] = s.split("=")[1].strip()
+    if found.get("source_sha256") != kernel_source_sha256():
+        return out
+    out["profile_is_current"] = True
     try:
-        for line in open(path):
-            if "derived: issued int32 VALU lane-ops/s" in line:
-                return float(line.split("=")[1].split("T")[0])
-    except (OSError, ValueError):
+        out["traffic"] = int(found["traffic_bytes_per_launch"])
+        out["valu_instructions"] = float(found["valu_instructions_per_launch"])
+        out["valu_select_instructions"] = float(found["valu_select_instructions_per_launch"])
+    except (KeyError, ValueError):
         pass
-    return None
+    return out
+
+
+def probe_rates(binding, torch, dev, iters: int = 400) -> dict:
+    """Issue rate of every probe mix of the library (vector instructions per second over the
+    whole chip), each timed with events on the stream it runs on."""
+    scr = torch.zeros(64, dtype=torch.int32, device=dev)
+    rates = {}
+    for mix, name in enumerate(binding.PROBE_MIXES):
+        binding.adaptra_valu_probe(mix, 8192, 20, scr)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        n = binding.adaptra_valu_probe(mix, 8192, iters, scr)
+        e1.record()
+        torch.cuda.synchronize()
+        rates[name] = n / (e0.elapsed_time(e1) * 1e-3)
+    return rates
 
 
 def cpu_baseline(wl, target_seconds: float = 16.0) -> dict:
@@ -125,6 +161,8 @@ def main():
     ap.add_argument("--no-sens", action="store_true",
                     help="skip the per-scenario stage time and link sensitivity side measurements")
     ap.add_argument("--kernel-mode", type=int, default=0)
+    ap.add_argument("--probe-only", action="store_true",
+                    help="run only the instruction issue-rate probes (for a counter profile of them)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy before the timed region (a kernel of "
                          "known traffic, to scale the FETCH_SIZE / WRITE_SIZE counters in a profile)")
@@ -143,6 +181,12 @@ def main():
         sys.exit(1)
     binding.load()
     binding.adaptra_set_kernel_mode(args.kernel_mode)
+    if args.probe_only:
+        rates = probe_rates(binding, torch, torch.device("cuda:0"))
+        slots = 256 * 4 * 2.4e9 / 4               # vector issue slots per second at one per SIMD per four cycles
+        print(json.dumps({"probe_valu_instructions_per_s": rates,
+                          "fraction_of_one_per_four_cycles_at_2.4GHz": {k: v / slots for k, v in rates.items()}}))
+        return
 
     wl = workloads.config(args.config)
     S, M, C, K = wl.S, wl.M, wl.n_cand, wl.n_scen
@@ -210,16 +254,21 @@ def main():
     t_eval = timed(lambda: binding.adaptra_eval(prob, mk, bub, fl, want_bubble=bub is not None, workspace=ws))
     t_best = timed(lambda: binding.adaptra_best(prob, bidx, bmk, bbub, hist, workspace=ws))
 
-    # sustained int32 VALU rate of this GPU (independent v_add_u32 / v_max_i32 chains, no memory)
-    scr = torch.zeros(64, dtype=torch.int32, device=dev)
-    binding.adaptra_valu_probe(8192, 100, scr)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    probe_ops = binding.adaptra_valu_probe(8192, 1000, scr)
-    e1.record()
-    torch.cuda.synchronize()
-    measured_peak = probe_ops / (e0.elapsed_time(e1) * 1e-3)
+    # sustained issue rates of this GPU for the instructions the kernel is made of (no memory traffic)
+    rates = probe_rates(binding, torch, dev)
+    measured_peak = rates["add_max"] * 64          # int32 lane-ops/s of independent v_add_u32 / v_max_i32 chains
+
+    def device_ms(fn, n):
+        """Average duration of fn() over n back-to-back calls, by events on the stream fn enqueues on."""
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
 
     # the analytic planning kernel (Algorithm 1 / 2 / Eq. (1)): HBM-bound, timed at 2^20 scenarios
     seed_info = None
@@ -231,11 +280,13 @@ def main():
         cbs = torch.from_numpy(g.integers(0, 50000, (S - 1, Ks)).astype(np.int32)).to(dev)
         sprob = binding.Problem(M, prob.tensors[0], prob.tensors[1], prob.tensors[2], cfs, cbs)
         w_cur = torch.from_numpy(np.arange(S - 1, -1, -1, dtype=np.int32)).to(dev)
-        binding.adaptra_seed(sprob, S, w_cur, want_not_absorbed=True)
-        t_seed = timed(lambda: binding.adaptra_seed(sprob, S, w_cur, want_not_absorbed=True), n=5)
-        seed_bytes = Ks * (8 * (S - 1) + 4 * S + (S - 1))
+        seed_out = binding.adaptra_seed(sprob, S, w_cur, want_not_absorbed=True)
+        t_seed = device_ms(lambda: binding.adaptra_seed(sprob, S, w_cur, out=seed_out), n=20) * 1e-3
+        seed_bytes = Ks * (8 * (S - 1) + 4 * S + (S - 1))     # delays read once, w_adapted and the Eq. (1) bytes written
         seed_info = {"scenarios": Ks, "ms": t_seed * 1e3, "algorithmic_GBps": seed_bytes / t_seed / 1e9,
-                     "frac_of_hbm_peak": seed_bytes / t_seed / 8e12, "includes": "output allocation by the binding"}
+                     "frac_of_hbm_peak": seed_bytes / t_seed / 8e12,
+                     "timing": "HIP events around 20 launches of k_seed, outputs preallocated"}
+        del seed_out
         del cfs, cbs, sprob
         # how far the paper's own pick (Algorithm 2, one vector per scenario) is from the exhaustive
         # argmin over this workload's candidates: each vector evaluated under its own scenario
@@ -290,12 +341,12 @@ def main():
         sprob2 = binding.Problem.from_workload(sub, dev, w_bound)
         sws = torch.empty(binding.load().adaptra_sensitivity_workspace_bytes(ctypes.byref(sprob2.params), sprob2.C, sprob2.K),
                           dtype=torch.uint8, device=dev)
-        binding.adaptra_sensitivity(sprob2, 1, workspace=sws)
-        t_sens = timed(lambda: binding.adaptra_sensitivity(sprob2, 1, workspace=sws))
+        sens_out = binding.adaptra_sensitivity(sprob2, 1, workspace=sws)
+        t_sens = device_ms(lambda: binding.adaptra_sensitivity(sprob2, 1, workspace=sws, out=sens_out), n=10) * 1e-3
         sens_info = {"candidates": int(sprob2.C), "scenarios": int(K), "links": S - 1, "ms": t_sens * 1e3,
                      "evaluations_per_s": sprob2.C * K * S / t_sens,
-                     "includes": "output allocation by the binding"}
-        del sws, sprob2
+                     "timing": "HIP events around 10 calls, outputs preallocated"}
+        del sws, sprob2, sens_out
 
     # guided search (neighbourhood descent on batched evaluation) over the same scenarios,
     # from the plain 1F1B schedule; compared with the exhaustive argmin over the workload's candidates
@@ -342,6 +393,7 @@ def main():
     ms_step = dt / args.steps * 1e3
     kernel_avg_ms = float(np.mean(kernel_ms))
     achieved = 3.0 * ops_eval / (kernel_avg_ms * 1e-3)
+    prof = from_profile(hot_S, args.config)
 
     out = {
         "metric": "schedule_evaluations_per_sec",
@@ -365,9 +417,8 @@ def main():
         "best": {"ms": t_best * 1e3, "evaluations_per_s": C * K / t_best, "resolved_ops_per_s": ops_best / t_best},
         "roofline": {"bound": "alu", "kernel": f"k_resolve_scen_lanes<{hot_S}, false, false>",
                      "achieved": achieved / 1e12, "peak": INT32_VALU_PEAK / 1e12, "unit": "Tint32op/s",
-                     "frac": achieved / INT32_VALU_PEAK, "traffic": traffic_from_profile(S, args.config),
+                     "frac": achieved / INT32_VALU_PEAK, "traffic": prof["traffic"],
                      "peak_measured": measured_peak / 1e12, "frac_of_measured": achieved / measured_peak,
-                     "issued_from_profile": issued_from_profile(S, args.config),
                      "kernel_ms": kernel_avg_ms, "resolved_ops_per_launch": ops_eval,
                      "algorithmic_ops_per_resolved_op": 3},
     }

@@ -39,8 +39,8 @@
  * Conventions for every entry point:
  *   - The three structs live in HOST memory; every pointer inside them, every
  *     out_* pointer and the workspace are DEVICE pointers owned by the caller.
- *     The library allocates no device memory and keeps no state between calls
- *     except the option set by adaptra_set_kernel_mode.
+ *     The library allocates no device memory and keeps no state between calls (the test
+ *     and measurement switches of adaptra_testing.h aside).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     adaptra_eval, adaptra_best, adaptra_eval_best, adaptra_seed,
  *     adaptra_sensitivity and adaptra_zb_eval only enqueue kernels on it and return; they do not
@@ -65,8 +65,8 @@ extern "C" {
 #define ADAPTRA_EINVAL      1   /* null pointer, S/M/n out of range, bad histogram spec      */
 #define ADAPTRA_EWORKSPACE  2   /* workspace missing, misaligned (256 B) or too small         */
 #define ADAPTRA_EHIP        3   /* a HIP call failed; see adaptra_last_hip_error              */
-#define ADAPTRA_ERANGE      4   /* adaptra_check_inputs: a negative time, delay or w          */
-#define ADAPTRA_EOVERFLOW   5   /* adaptra_check_inputs: 2 M S (max t + max c) >= 2^31        */
+#define ADAPTRA_ERANGE      4   /* adaptra_check_inputs, adaptra_zb_check_inputs: a time, delay or w out of range */
+#define ADAPTRA_EOVERFLOW   5   /* the same: 2 M S (max t + max c) >= 2^31 (3 M S with weight ops)             */
 
 #define ADAPTRA_FLAG_FEASIBLE 1
 #define ADAPTRA_FLAG_DEADLOCK 2
@@ -243,7 +243,8 @@ int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *sc
  * F(s,m) becomes available when F(s-1,m) has finished plus c_fwd[s-1], B(s,m) when B(s+1,m)
  * has finished plus c_bwd[s] (B(S-1,m) when F(S-1,m) has finished), W(s,m) when B(s,m) has
  * finished.  Precondition beyond adaptra_eval's: t_f, t_b >= 1 (no two dependent ops in one
- * instant), and 3 M S (max time + max delay) < 2^31.  mem_cap and the histogram fields of
+ * instant), and 3 M S (max time + max delay) < 2^31 -- adaptra_zb_check_inputs tests both on
+ * the device data.  mem_cap and the histogram fields of
  * params are ignored; w is clamped into [0, M-1].
  *   plan_scenario = -1  every pair generates its schedule under its own scenario's delays
  *                       (the pipeline as Adaptra would re-plan it);
@@ -254,37 +255,22 @@ int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *sc
  *   out_bubble    DEVICE int32 [S][n_scen][n_cand] = makespan - M (t_f + t_b + t_w), or NULL
  * The workspace size comes from adaptra_zb_workspace_bytes.  Asynchronous on `stream`. */
 size_t adaptra_zb_workspace_bytes(const adaptra_params_t *params, int64_t n_cand, int64_t n_scen);
+
+/* SYNCHRONOUS validation of adaptra_zb_eval's preconditions on the device data (Section 3.1:
+ * an op runs for its duration and its successor waits for it -- with forward and backward times
+ * of at least 1 us no two dependent ops share an instant, which is what lets adaptra_zb_eval
+ * decide stage by stage in order of time).  Enqueues a scan on `stream`, waits for it and
+ * returns ADAPTRA_ERANGE if a forward or backward time is below 1, or a weight time, delay or
+ * w is negative; ADAPTRA_EOVERFLOW if 3 M S (max time + max delay) >= 2^31; else ADAPTRA_OK.
+ * Outside these ranges adaptra_zb_eval still returns, but its schedule may differ from the
+ * policy's.  Workspace as for adaptra_zb_eval.  Optional: adaptra_zb_eval does not call it. */
+int adaptra_zb_check_inputs(const adaptra_params_t *params, const int32_t *t_w, const adaptra_candidates_t *cands,
+                            const adaptra_scenarios_t *scens, void *workspace, size_t workspace_bytes, void *stream);
+
 int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const adaptra_candidates_t *cands,
                     const adaptra_scenarios_t *scens, int64_t plan_scenario,
                     int32_t *out_makespan, int32_t *out_bubble,
                     void *workspace, size_t workspace_bytes, void *stream);
-
-/* Kernel selection, process-wide; for tests and measurements.
- *   0  automatic (default): up to 32 stages, the register/LDS kernel with scenarios on the
- *      lanes from 48 scenarios on (from 33 with at least 32768 candidates), below that -- and
- *      from 33 to 64 stages always -- the kernel with candidates on the lanes, in its read-ahead
- *      form (the measured crossover); the general kernel for what fits
- *      neither (per-scenario stage times at more than 32 stages, warm-ups deeper than the LDS
- *      ring of 128 slots)
- *   1  general kernel only (any S, M, warm-up depth)
- *   2  scenario-lanes kernel wherever its limits allow, regardless of lane efficiency
- *   3  candidate-lanes kernel wherever its limits allow, in its plain form
- *   4  the same, in its read-ahead form (what automatic mode uses)
- * Returns the previous mode, or -1 for an unknown mode (nothing changes). */
-int adaptra_set_kernel_mode(int mode);
-
-/* Measurement hook, process-wide: when both are non-NULL hipEvent_t handles, adaptra_eval
- * and adaptra_best record `before` on the stream just ahead of their resolve kernels
- * (the max-plus recurrence) and `after` right behind them, so that a caller can time
- * exactly those launches.  Pass NULL, NULL to switch it off.  Always returns ADAPTRA_OK. */
-int adaptra_set_resolve_events(void *before, void *after);
-
-/* Measurement aid for callers that report a roofline (bench.py): enqueue a kernel of
- * `blocks` x 256 threads in which every lane performs iters x 512 independent int32
- * VALU operations (v_add_u32 / v_max_i32 pairs, the two ops of the recurrence), with no
- * memory traffic.  `scratch` is a DEVICE int32 (never written in practice).  *lane_ops
- * (HOST, may be NULL) receives the number of lane operations enqueued.  Asynchronous. */
-int adaptra_valu_probe(int32_t blocks, int32_t iters, int32_t *scratch, void *stream, int64_t *lane_ops);
 
 /* hipError_t (as int) of the last failed HIP call on this thread, 0 if none. */
 int adaptra_last_hip_error(void);

@@ -55,7 +55,7 @@ def search(S: int, M: int, t_f, t_b, mem_cap, w_start, c_fwd, c_bwd, *, neighbou
     cur_mk = np.full(K, INT32_MAX, dtype=np.int64)
     rounds = 0
     evaluated = 0
-    moved_in_round = []
+    history = []                                        # every scenario's makespan after each round
     per_point = len(mv) + 1
     while rounds < max_iters:
         rounds += 1
@@ -93,8 +93,8 @@ def search(S: int, M: int, t_f, t_b, mem_cap, w_start, c_fwd, c_bwd, *, neighbou
                 cur[:, k] = pool[:, k * per_point + j]
                 cur_mk[k] = best["best_makespan"][0]
                 moved += 1
-        moved_in_round.append(moved)
+        history.append(cur_mk.copy())
         if moved == 0:
             break
     return {"w": cur.astype(np.int32), "makespan": cur_mk.astype(np.int32), "rounds": rounds,
-            "evaluated": evaluated, "moved_in_round": moved_in_round}
+            "evaluated": evaluated, "makespan_history": np.stack(history).astype(np.int32)}

@@ -21,12 +21,15 @@ ERROR_NAMES = {0: "ADAPTRA_OK", 1: "ADAPTRA_EINVAL", 2: "ADAPTRA_EWORKSPACE", 3:
 FLAG_FEASIBLE, FLAG_DEADLOCK, FLAG_MEMCAP = 1, 2, 4
 INT32_MAX = 2 ** 31 - 1
 
+# include/adaptra.h
 EXPORTS = ("adaptra_workspace_bytes", "adaptra_best_workspace_bytes", "adaptra_search_workspace_bytes", "adaptra_search",
-           "adaptra_check_inputs", "adaptra_eval", "adaptra_best", "adaptra_eval_best", "adaptra_seed",
-           "adaptra_sensitivity_workspace_bytes", "adaptra_sensitivity",
-           "adaptra_zb_workspace_bytes", "adaptra_zb_eval",
-           "adaptra_set_kernel_mode", "adaptra_set_resolve_events", "adaptra_valu_probe", "adaptra_last_hip_error",
-           "adaptra_version")
+           "adaptra_check_inputs", "adaptra_eval", "adaptra_best", "adaptra_eval_best",
+           "adaptra_seed", "adaptra_sensitivity_workspace_bytes", "adaptra_sensitivity",
+           "adaptra_zb_workspace_bytes", "adaptra_zb_check_inputs", "adaptra_zb_eval",
+           "adaptra_last_hip_error", "adaptra_version")
+# include/adaptra_testing.h
+TESTING_EXPORTS = ("adaptra_set_kernel_mode", "adaptra_set_resolve_events", "adaptra_valu_probe")
+PROBE_MIXES = ("add_max", "add_vgpr", "add_sgpr", "add_inline", "add_literal", "add_e64", "sub", "add_co", "add3", "max", "max_sgpr", "max_e64", "max_u32", "min", "max3", "med3", "and", "or", "xor", "lshl", "mov", "cndmask", "cndmask_sgpr", "cndmask_bfe", "cmp_cndmask", "add_max_alt", "add_max_batch", "add_max_batch_nop", "add_max_alt_dense", "readlane", "forward_step")
 
 
 class AdaptraError(RuntimeError):
@@ -98,7 +101,10 @@ def load() -> ctypes.CDLL:
         lib.adaptra_set_resolve_events.restype = ctypes.c_int
         lib.adaptra_set_resolve_events.argtypes = [vp, vp]
         lib.adaptra_valu_probe.restype = ctypes.c_int
-        lib.adaptra_valu_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp, ctypes.POINTER(ctypes.c_int64)]
+        lib.adaptra_valu_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp,
+                                           ctypes.POINTER(ctypes.c_int64)]
+        lib.adaptra_zb_check_inputs.restype = ctypes.c_int
+        lib.adaptra_zb_check_inputs.argtypes = [P, vp, C, Sc, vp, sz, vp]
         lib.adaptra_last_hip_error.restype = ctypes.c_int
         lib.adaptra_version.restype = ctypes.c_int
         _lib = lib
@@ -260,14 +266,18 @@ def adaptra_eval_best(prob: Problem, out_makespan=None, out_bubble=None, out_fea
 
 
 def adaptra_seed(prob: Problem, x_max: int = 1, w_current=None, *, want_init: bool = True,
-                 want_adapted: bool = True, want_not_absorbed: bool = False, stream=None):
+                 want_adapted: bool = True, want_not_absorbed: bool = False, out=None, stream=None):
     """Enqueue the analytic planning; returns (w_init [S] | None, w_adapted [S,K] | None,
-    not_absorbed [S-1,K] | None)."""
+    not_absorbed [S-1,K] | None).  out: the three outputs of an earlier call, written again
+    instead of allocating new ones."""
     import torch
     dev = prob.device
-    w_init = torch.empty(prob.S, dtype=torch.int32, device=dev) if want_init else None
-    w_ad = torch.empty((prob.S, prob.K), dtype=torch.int32, device=dev) if want_adapted else None
-    na = torch.empty((max(prob.S - 1, 0), prob.K), dtype=torch.uint8, device=dev) if want_not_absorbed else None
+    if out is not None:
+        w_init, w_ad, na = out
+    else:
+        w_init = torch.empty(prob.S, dtype=torch.int32, device=dev) if want_init else None
+        w_ad = torch.empty((prob.S, prob.K), dtype=torch.int32, device=dev) if want_adapted else None
+        na = torch.empty((max(prob.S - 1, 0), prob.K), dtype=torch.uint8, device=dev) if want_not_absorbed else None
     _check_i32(w_current, "w_current", (prob.S,))
     rc = load().adaptra_seed(ctypes.byref(prob.params), ctypes.byref(prob.scens), int(x_max), _ptr(w_current),
                              _ptr(w_init), _ptr(w_ad), _ptr(na), _stream(stream))
@@ -275,14 +285,19 @@ def adaptra_seed(prob: Problem, x_max: int = 1, w_current=None, *, want_init: bo
     return w_init, w_ad, na
 
 
-def adaptra_sensitivity(prob: Problem, delta: int = 1, *, want_makespan: bool = True, workspace=None, stream=None):
+def adaptra_sensitivity(prob: Problem, delta: int = 1, *, want_makespan: bool = True, workspace=None, out=None,
+                        stream=None):
     """Enqueue the per-link finite differences; returns (makespan [C,K] | None, flag [C,K] | None,
-    sens [C,S-1,K]) -- candidate-major, unlike adaptra_eval."""
+    sens [C,S-1,K]) -- candidate-major, unlike adaptra_eval.  out: the three outputs of an
+    earlier call, written again instead of allocating new ones."""
     import torch
     dev = prob.device
-    mk = torch.empty((prob.C, prob.K), dtype=torch.int32, device=dev) if want_makespan else None
-    fl = torch.empty((prob.C, prob.K), dtype=torch.uint8, device=dev) if want_makespan else None
-    sens = torch.empty((prob.C, prob.S - 1, prob.K), dtype=torch.int32, device=dev)
+    if out is not None:
+        mk, fl, sens = out
+    else:
+        mk = torch.empty((prob.C, prob.K), dtype=torch.int32, device=dev) if want_makespan else None
+        fl = torch.empty((prob.C, prob.K), dtype=torch.uint8, device=dev) if want_makespan else None
+        sens = torch.empty((prob.C, prob.S - 1, prob.K), dtype=torch.int32, device=dev)
     if workspace is None:
         n = int(load().adaptra_sensitivity_workspace_bytes(ctypes.byref(prob.params), prob.C, prob.K))
         if n == 0:
@@ -318,6 +333,23 @@ def adaptra_search(prob: Problem, w_start, neighbourhood: int = 0, max_iters: in
     return w, mk, int(rounds.value), int(evaluated.value)
 
 
+def adaptra_zb_check_inputs(prob: Problem, t_w, workspace=None, stream=None) -> int:
+    """Returns the library's code (OK, ERANGE, EOVERFLOW) without raising for data findings."""
+    import torch
+    _check_i32(t_w, "t_w", (prob.S,))
+    if workspace is None:
+        n = int(load().adaptra_zb_workspace_bytes(ctypes.byref(prob.params), prob.C, prob.K))
+        if n == 0:
+            raise AdaptraError(EINVAL, "adaptra_zb_workspace_bytes")
+        workspace = torch.empty(n, dtype=torch.uint8, device=prob.device)
+    rc = load().adaptra_zb_check_inputs(ctypes.byref(prob.params), t_w.data_ptr(), ctypes.byref(prob.cands),
+                                        ctypes.byref(prob.scens), workspace.data_ptr(), workspace.numel(),
+                                        _stream(stream))
+    if rc in (EINVAL, EWORKSPACE, EHIP):
+        _raise(rc, "adaptra_zb_check_inputs")
+    return rc
+
+
 def adaptra_zb_eval(prob: Problem, t_w, plan_scenario: int = -1, *, want_bubble: bool = True,
                     workspace=None, stream=None):
     """Enqueue the ZeroBubble (F / B / W) evaluation; returns (makespan [K,C], bubble [S,K,C] | None)."""
@@ -347,10 +379,12 @@ def adaptra_set_resolve_events(before: Optional[int], after: Optional[int]) -> i
     return int(load().adaptra_set_resolve_events(before, after))
 
 
-def adaptra_valu_probe(blocks: int, iters: int, scratch, stream=None) -> int:
-    """Enqueue the integer-VALU rate probe; returns the number of lane operations enqueued."""
+def adaptra_valu_probe(mix: int, blocks: int, iters: int, scratch, stream=None) -> int:
+    """Enqueue one issue-rate probe (mix: index into PROBE_MIXES); returns the number of vector
+    instructions (wavefront instructions) the launch issues."""
     n = ctypes.c_int64(0)
-    rc = load().adaptra_valu_probe(int(blocks), int(iters), scratch.data_ptr(), _stream(stream), ctypes.byref(n))
+    rc = load().adaptra_valu_probe(int(mix), int(blocks), int(iters), scratch.data_ptr(), _stream(stream),
+                                   ctypes.byref(n))
     _raise(rc, "adaptra_valu_probe")
     return int(n.value)
 

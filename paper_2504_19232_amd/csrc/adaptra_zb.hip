@@ -438,6 +438,38 @@ __global__ void k_zb_reset(unsigned long long *counters) {
     if (threadIdx.x < 2) counters[threadIdx.x] = 0;
 }
 
+// Range scan for adaptra_zb_check_inputs.  found[0] counts entries out of range: a forward or
+// backward time below 1 (two dependent ops would share an instant, which the evaluation order
+// of k_zb excludes), a negative weight time, delay or w; found[1] / found[2] = largest time /
+// delay.  found[] is zero when the kernel starts.
+__global__ __launch_bounds__(adaptra_detail::kThreadsPerBlock) void k_zb_check(ZbArgs a, int *found) {
+    const long long nw = (long long)a.S * a.C, nc = (long long)(a.S - 1) * a.K;
+    const long long n = nw + 2 * nc + 3 * a.S;
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    int bad = 0, maxt = 0, maxc = 0;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        if (i < nw) {
+            bad += a.w[i] < 0;
+        } else if (i < nw + 2 * nc) {
+            const int v = i < nw + nc ? a.cf[i - nw] : a.cb[i - nw - nc];
+            bad += v < 0;
+            maxc = imax2(maxc, v);
+        } else {
+            const long long j = i - nw - 2 * nc;
+            const int v = j < a.S ? a.t_f[j] : (j < 2 * a.S ? a.t_b[j - a.S] : a.t_w[j - 2 * a.S]);
+            bad += j < 2 * a.S ? v < 1 : v < 0;
+            maxt = imax2(maxt, v);
+        }
+    }
+    if (bad) atomicAdd(&found[0], bad);
+    if (maxt) atomicMax(&found[1], maxt);
+    if (maxc) atomicMax(&found[2], maxc);
+}
+
+__global__ void k_zb_check_reset(int *found) {
+    if (threadIdx.x < 4) found[threadIdx.x] = 0;
+}
+
 
 struct ZbPlan {
     bool narrow;                  // generation (PHASE 0, 1) in the one-word form of the cursors
@@ -511,6 +543,35 @@ size_t adaptra_zb_workspace_bytes(const adaptra_params_t *params, int64_t n_cand
     ZbPlan p;
     if (!params || !plan_zb(params->S, params->M, n_cand, n_scen, &p)) return 0;
     return p.total;
+}
+
+int adaptra_zb_check_inputs(const adaptra_params_t *params, const int32_t *t_w, const adaptra_candidates_t *cands,
+                            const adaptra_scenarios_t *scens, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!params || !cands || !scens || !t_w) return ADAPTRA_EINVAL;
+    ZbPlan p;
+    if (!plan_zb(params->S, params->M, cands->n, scens->n, &p)) return ADAPTRA_EINVAL;
+    if (!params->t_f || !params->t_b || !cands->w) return ADAPTRA_EINVAL;
+    if (params->S > 1 && (!scens->c_fwd || !scens->c_bwd)) return ADAPTRA_EINVAL;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < p.total) return ADAPTRA_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    ZbArgs a{};
+    a.S = params->S; a.N = params->M;
+    a.t_f = params->t_f; a.t_b = params->t_b; a.t_w = t_w;
+    a.C = cands->n; a.K = scens->n;
+    a.w = cands->w; a.cf = scens->c_fwd; a.cb = scens->c_bwd;
+    int *found = (int *)((char *)workspace + p.off_counters) + 16;     // behind the work counters
+    hipLaunchKernelGGL(k_zb_check_reset, dim3(1), dim3(64), 0, st, found);
+    ADAPTRA_CHECK_LAUNCH();
+    const long long n = (long long)a.S * a.C + 2ll * (a.S - 1) * a.K + 3 * a.S;
+    hipLaunchKernelGGL(k_zb_check, dim3((unsigned)adaptra_detail::blocks_for(n, 4096)), dim3(adaptra_detail::kThreadsPerBlock), 0, st, a, found);
+    ADAPTRA_CHECK_LAUNCH();
+    int host[4] = {0, 0, 0, 0};
+    hipError_t e = hipMemcpyAsync(host, found, sizeof(host), hipMemcpyDeviceToHost, st);
+    if (e != hipSuccess) return adaptra_detail::hip_fail(e);
+    if ((e = hipStreamSynchronize(st)) != hipSuccess) return adaptra_detail::hip_fail(e);
+    if (host[0] != 0) return ADAPTRA_ERANGE;
+    if (3ll * a.N * a.S * ((long long)host[1] + (long long)host[2]) >= (1ll << 31)) return ADAPTRA_EOVERFLOW;
+    return ADAPTRA_OK;
 }
 
 int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const adaptra_candidates_t *cands,

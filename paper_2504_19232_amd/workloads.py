@@ -240,6 +240,27 @@ def random_workload(seed: int, S: int, M: int, C: int, K: int, *, t_lo: int = 20
                     hist_bins=hist_bins, hist_shift=hist_shift)
 
 
+def near_bound_workload(seed: int, S: int, M: int, C: int, K: int, frac: float = 0.99, **kw) -> Workload:
+    """A random_workload whose times and delays are rescaled so that the precondition of the
+    int32 path, 2 M S (max time + max delay) < 2^31, holds with only (1 - frac) to spare: the
+    largest time is planted at 60 % and the largest delay at 40 % of frac * 2^31 / (2 M S), the
+    other entries spread below them.  Input generation only."""
+    wl = random_workload(seed, S, M, C, K, **kw)
+    rng = _rng(seed + 7919)
+    budget = int(frac * 2 ** 31 / (2 * M * S))
+    t_max, c_max = (budget * 6) // 10, budget - (budget * 6) // 10
+    wl.t_f = _i32(rng.integers(t_max // 8, t_max + 1, S))
+    wl.t_b = _i32(rng.integers(t_max // 8, t_max + 1, S))
+    wl.t_b[int(rng.integers(0, S))] = t_max
+    if S > 1:
+        slow = rng.random((2 * (S - 1), K)) < 0.3
+        c = np.where(slow, rng.integers(c_max // 2, c_max + 1, slow.shape), rng.integers(0, max(1, c_max // 64), slow.shape))
+        c[int(rng.integers(0, 2 * (S - 1))), int(rng.integers(0, K))] = c_max
+        wl.c_fwd, wl.c_bwd = _i32(c[: S - 1]), _i32(c[S - 1:])
+    wl.name = f"nearbound_s{seed}_S{S}_M{M}_C{C}_K{K}"
+    return wl
+
+
 def sample_pairs(seed: int, n_cand: int, n_scen: int, n: int):
     """n seeded (candidate, scenario) index pairs, for sampled parity at sizes
     the oracle cannot sweep."""

@@ -1,4 +1,4 @@
-"""The C-ABI library loads and exports every function include/adaptra.h declares.
+"""The C-ABI library loads and exports every function include/*.h declares.
 No compute call is made here (no GPU needed)."""
 import ctypes
 import os
@@ -9,8 +9,8 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "adaptra.h")).read()
+def declared_functions(header="adaptra.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(adaptra_[a-z_]+)\s*\(", text)))
 
@@ -32,9 +32,15 @@ def test_header_declares_the_entry_points():
 
 def test_library_exports_every_declared_symbol(binding):
     lib = ctypes.CDLL(binding.LIB_PATH)
-    for name in declared_functions():
-        assert hasattr(lib, name), f"{name} is declared in adaptra.h but not exported"
-    assert set(binding.EXPORTS) == set(declared_functions())
+    headers = sorted(f for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h"))
+    assert headers == ["adaptra.h", "adaptra_testing.h"]
+    for header in headers:
+        for name in declared_functions(header):
+            assert hasattr(lib, name), f"{name} is declared in {header} but not exported"
+    assert set(binding.EXPORTS) == set(declared_functions("adaptra.h"))
+    assert set(binding.TESTING_EXPORTS) == set(declared_functions("adaptra_testing.h"))
+    # the product header carries no test switch or probe
+    assert not set(binding.TESTING_EXPORTS) & set(declared_functions("adaptra.h"))
 
 
 def test_host_only_calls(binding):
@@ -78,4 +84,16 @@ def test_zb_and_search_reject_bad_arguments_without_touching_the_gpu(binding):
     assert lib.adaptra_zb_workspace_bytes(ctypes.byref(p), 10, 6) > 0
     assert lib.adaptra_search_workspace_bytes(ctypes.byref(p), 6, 2) == 0                     # unknown neighbourhood
     assert lib.adaptra_search(ctypes.byref(p), ctypes.byref(s), 1, 0, 0, 1, 1, None, None, 256, 1 << 30, None) == binding.EINVAL
+    assert lib.adaptra_zb_check_inputs(None, None, None, None, None, 0, None) == binding.EINVAL
+    assert lib.adaptra_zb_check_inputs(*args, 256, 64, None) == binding.EWORKSPACE
+
+
+def test_grid_limits_are_checked_before_anything_is_enqueued(binding):
+    """2^31 - 1 candidates x 2^31 - 1 scenarios make more 64 x 64 tiles than a grid holds: EINVAL
+    from the planning, ahead of the workspace test and of every launch."""
+    lib = binding.load()
+    p = binding.Params(4, 8, 1, 1, None, 0, 0)
+    c = binding.Candidates(2 ** 31 - 1, 1, -1)
+    s = binding.Scenarios(2 ** 31 - 1, 1, 1, None, None)
+    assert lib.adaptra_best(ctypes.byref(p), ctypes.byref(c), ctypes.byref(s), 1, 1, None, None, 256, 1 << 62, None) == binding.EINVAL
 

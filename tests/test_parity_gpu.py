@@ -123,6 +123,13 @@ RAGGED = [
     (30, 33, 40, 20, 10, dict(d_max=2)),        # beyond the hot kernel: general kernel
     (31, 4, 400, 40, 64, dict(w_extra=300)),    # warm-ups deeper than the 128-slot LDS ring: general kernel
     (32, 8, 160, 30, 3, dict(w_extra=120)),     # the same with few scenarios
+    # the kernel sizes between the powers of two (12, 24, 48 stages) and pipelines padded into them
+    (33, 10, 30, 90, 70, dict(d_max=3, hist_bins=16, hist_shift=9)),
+    (34, 20, 50, 80, 66, dict(d_max=3)),
+    (35, 24, 128, 64, 64, dict(d_max=4, c_hi=30000)),
+    (36, 48, 40, 30, 20, dict(d_max=2)),
+    (37, 40, 64, 50, 5, dict(d_max=2)),
+    (38, 12, 100, 40, 64, dict(w_extra=70)),    # 12 stages with deep warm-ups
 ]
 
 
@@ -151,32 +158,69 @@ def test_zero_times_and_zero_delays(lib, oracle):
 
 
 def _sampled_parity(lib, oracle, index, n_sample, full_scenarios):
-    """Full-size configuration, launch shape as benchmarked: every pair is evaluated on the
-    GPU; the oracle checks (a) a seeded sample of pairs, (b) whole scenarios including the
-    search over all candidates; (c) adaptra_best must equal a host argmin over the GPU's own
-    complete evaluation for every scenario."""
+    """A full-size configuration through the very call bench.py times -- adaptra_eval_best with
+    a w_bound hint, every output preallocated, bubbles on, histogram where the configuration has
+    one -- checked against the oracle on
+      (a) a seeded sample of n_sample pairs: flag, makespan and all S bubbles, read from the
+          GPU's own output arrays;
+      (b) whole scenarios (every candidate): evaluation and the search's pick;
+    and, at any size, on properties of the complete arrays:
+      (c) flags depend on the candidate only; deadlocked pairs carry the sentinels; every live
+          bubble plane equals makespan - M (t_f + t_b);
+      (d) the search equals a host argmin over the GPU's complete evaluation, the histogram a
+          numpy.bincount over it;
+      (e) adaptra_eval followed by adaptra_best gives the same arrays as the one call."""
+    import torch
     wl = workloads.config(index)
     w_bound = int(wl.w.max())                          # as bench.py passes it
-    say(f"config {index}: {wl.name}: GPU eval of {wl.n_pairs} pairs")
-    mk, _, fl = gpu_eval(lib, wl, want_bubble=False, w_bound=w_bound)
+    S, K, C = wl.S, wl.n_scen, wl.n_cand
+    say(f"config {index}: {wl.name}: adaptra_eval_best on {wl.n_pairs} pairs, bubbles on, w_bound {w_bound}")
+    lib.adaptra_set_kernel_mode(0)
+    prob = lib.Problem.from_workload(wl, w_bound=w_bound)
+    dev = prob.device
+    ws = lib.alloc_workspace(prob)
+    d_mk = torch.empty((K, C), dtype=torch.int32, device=dev)
+    d_fl = torch.empty((K, C), dtype=torch.uint8, device=dev)
+    d_bub = torch.empty((S, K, C), dtype=torch.int32, device=dev)
+    d_idx = torch.empty(K, dtype=torch.int32, device=dev)
+    d_bmk = torch.empty(K, dtype=torch.int32, device=dev)
+    d_bbub = torch.empty((K, S), dtype=torch.int32, device=dev)
+    d_hist = torch.empty((S, wl.hist_bins), dtype=torch.int64, device=dev) if wl.hist_bins else None
+    lib.adaptra_eval_best(prob, d_mk, d_bub, d_fl, d_idx, d_bmk, d_bbub, d_hist, workspace=ws)
+    torch.cuda.synchronize()
+    mk, fl = d_mk.cpu().numpy(), d_fl.cpu().numpy()
+    idx, bmk, bbub = d_idx.cpu().numpy(), d_bmk.cpu().numpy(), d_bbub.cpu().numpy()
+    hist = None if d_hist is None else d_hist.cpu().numpy().astype(np.uint64)
     tau = (wl.t_f + wl.t_b).astype(np.int64)
-    # (a) sampled pairs, with bubbles from a second, bubble-enabled pass over a sub-problem
-    pc, ps = workloads.sample_pairs(900 + index, wl.n_cand, wl.n_scen, n_sample)
-    say(f"  oracle on {n_sample} sampled pairs")
+    # (a) sampled pairs: the GPU's arrays, gathered on the device, against the oracle
+    pc, ps = workloads.sample_pairs(900 + index, C, K, n_sample)
+    say(f"  (a) oracle on {n_sample} sampled pairs, bubbles included")
     ref = oracle.eval_workload(wl, pair_cand=pc, pair_scen=ps)
-    assert np.array_equal(fl[ps, pc], ref["flag"])
-    assert np.array_equal(mk[ps, pc], ref["makespan"])
-    live = (ref["flag"] & 2) == 0
-    assert np.array_equal((mk[ps, pc].astype(np.int64)[None, :] - wl.M * tau[:, None])[:, live],
-                          ref["bubble"][:, live].astype(np.int64))
-    # (c) search == argmin over the GPU's evaluation
-    say("  GPU best vs host argmin over the GPU evaluation")
-    idx, bmk, bbub, hist = gpu_best(lib, wl, w_bound=w_bound)
+    t_pc, t_ps = torch.from_numpy(pc).to(dev), torch.from_numpy(ps).to(dev)
+    assert np.array_equal(d_fl[t_ps, t_pc].cpu().numpy(), ref["flag"])
+    assert np.array_equal(d_mk[t_ps, t_pc].cpu().numpy(), ref["makespan"])
+    for s in range(S):
+        assert np.array_equal(d_bub[s][t_ps, t_pc].cpu().numpy(), ref["bubble"][s]), f"bubble plane {s}"
+    assert ((ref["flag"] & 2) == 0).sum() > n_sample // 2          # the sample is mostly live pairs
+    # (c) the complete arrays
+    say("  (c) complete arrays: flags, sentinels, bubble planes")
+    assert bool((d_fl == d_fl[0:1]).all())
+    dead = (d_fl[0] & 2) != 0
+    assert bool((d_mk[:, dead] == INT32_MAX).all())
+    t_tau = torch.from_numpy(tau).to(dev)
+    for s in range(S):
+        want = torch.where(dead[None, :], torch.full_like(d_mk, INT32_MAX), d_mk - int(wl.M * tau[s]))
+        assert bool((d_bub[s] == want).all()), f"bubble plane {s} is not makespan - M (t_f + t_b)"
+        del want
+    del t_tau
+    # (d) search == argmin over the GPU's evaluation
+    say("  (d) search vs host argmin over the GPU evaluation")
     masked = np.where(fl == 1, mk.astype(np.int64), np.int64(2) ** 40)
     want_idx = masked.argmin(axis=1).astype(np.int32)
     any_ok = (fl == 1).any(axis=1)
     want_idx[~any_ok] = -1
     want_mk = np.where(any_ok, masked.min(axis=1), INT32_MAX).astype(np.int32)
+    del masked
     assert np.array_equal(idx, want_idx)
     assert np.array_equal(bmk, want_mk)
     want_bub = np.where(any_ok[:, None], want_mk.astype(np.int64)[:, None] - wl.M * tau[None, :], INT32_MAX)
@@ -188,39 +232,68 @@ def _sampled_parity(lib, oracle, index, n_sample, full_scenarios):
             b = np.minimum(wl.hist_bins - 1, (mk[ok].astype(np.int64) - wl.M * tau[s]) >> wl.hist_shift)
             want[s] = np.bincount(b, minlength=wl.hist_bins).astype(np.uint64)
         assert np.array_equal(hist, want)
-    # (c') the one-call form gives the same evaluation and the same search
-    say("  adaptra_eval_best vs the two calls")
-    import torch
-    out = lib.adaptra_eval_best(lib.Problem.from_workload(wl, w_bound=int(np.clip(wl.w, 0, wl.M - 1).max())),
-                                want_bubble=False)
+    # (e) the two separate calls write the same arrays
+    say("  (e) adaptra_eval + adaptra_best vs the one call")
+    e_mk, e_fl = torch.empty_like(d_mk), torch.empty_like(d_fl)
+    d_bub2 = torch.empty_like(d_bub)
+    lib.adaptra_eval(prob, e_mk, d_bub2, e_fl, workspace=ws)
+    b_out = lib.adaptra_best(prob, workspace=ws)
     torch.cuda.synchronize()
-    assert np.array_equal(out[0].cpu().numpy(), mk) and np.array_equal(out[2].cpu().numpy(), fl)
-    assert np.array_equal(out[3].cpu().numpy(), idx) and np.array_equal(out[4].cpu().numpy(), bmk)
+    assert bool((e_mk == d_mk).all()) and bool((e_fl == d_fl).all()) and bool((d_bub2 == d_bub).all())
+    del d_bub2, e_mk, e_fl
+    assert np.array_equal(b_out[0].cpu().numpy(), idx) and np.array_equal(b_out[1].cpu().numpy(), bmk)
+    assert np.array_equal(b_out[2].cpu().numpy(), bbub)
     if wl.hist_bins:
-        assert np.array_equal(out[6].cpu().numpy().astype(np.uint64), hist)
-    del out
+        assert np.array_equal(b_out[3].cpu().numpy().astype(np.uint64), hist)
     # (b) whole scenarios through the oracle, search included
     for k in full_scenarios:
-        say(f"  oracle on all {wl.n_cand} candidates of scenario {k}")
-        cand = np.arange(wl.n_cand, dtype=np.int64)
-        ref = oracle.eval_workload(wl, pair_cand=cand, pair_scen=np.full(wl.n_cand, k, dtype=np.int64),
-                                   want_bubble=False)
+        say(f"  (b) oracle on all {C} candidates of scenario {k}")
+        cand = np.arange(C, dtype=np.int64)
+        ref = oracle.eval_workload(wl, pair_cand=cand, pair_scen=np.full(C, k, dtype=np.int64))
         assert np.array_equal(fl[k], ref["flag"])
         assert np.array_equal(mk[k], ref["makespan"])
-        rb = oracle.best_from_eval(ref["makespan"][None, :], ref["flag"][None, :])
+        assert np.array_equal(d_bub[:, k, :].cpu().numpy(), ref["bubble"])
+        rb = oracle.best_from_eval(ref["makespan"][None, :], ref["flag"][None, :], ref["bubble"][:, None, :])
         assert idx[k] == rb["best_idx"][0] and bmk[k] == rb["best_makespan"][0]
+        assert np.array_equal(bbub[k], rb["best_bubble"][0])
 
 
 def test_config2_sampled_parity(lib, oracle):
-    _sampled_parity(lib, oracle, 2, 1 << 15, (0, 131))
+    _sampled_parity(lib, oracle, 2, 1 << 20, (0, 131))
 
 
 def test_config3_sampled_parity(lib, oracle):
-    _sampled_parity(lib, oracle, 3, 1 << 13, (0, 517))
+    _sampled_parity(lib, oracle, 3, 1 << 20, (0, 517))
 
 
 def test_config4_sampled_parity(lib, oracle):
-    _sampled_parity(lib, oracle, 4, 1 << 14, (37,))
+    _sampled_parity(lib, oracle, 4, 1 << 20, (37, 63))
+
+
+NEAR_BOUND = [
+    # seed, S, M, C, K, kwargs: 2 M S (max time + max delay) is 99 % of 2^31
+    (81, 8, 32, 200, 70, dict(hist_bins=16, hist_shift=24)),
+    (82, 4, 1, 70, 64, {}),                       # one micro-batch: the largest times of all
+    (83, 16, 2, 90, 65, dict(d_max=1)),
+    (84, 32, 64, 64, 64, dict(d_max=4)),
+    (85, 5, 300, 40, 33, dict(w_extra=20)),       # padded to 8 stages, deep warm-ups
+    (86, 2, 4000, 10, 64, dict(d_max=1)),
+]
+
+
+@pytest.mark.parametrize("seed,S,M,C,K,kw", NEAR_BOUND, ids=[f"S{r[1]}_M{r[2]}_C{r[3]}_K{r[4]}" for r in NEAR_BOUND])
+def test_times_near_the_int32_bound(lib, oracle, seed, S, M, C, K, kw):
+    """Times and delays so large that the precondition 2 M S (max t + max c) < 2^31 holds with
+    1 % to spare: the shifted times of the scenario-lanes kernel and its "no earlier op"
+    sentinel of -2^30 are closest to their limits here.  Every kernel mode, element by element."""
+    wl = workloads.near_bound_workload(seed, S, M, C, K, **kw)
+    bound = 2 * M * S * (int(max(wl.t_f.max(), wl.t_b.max())) + int(max(wl.c_fwd.max(), wl.c_bwd.max())))
+    assert 0.98 * 2 ** 31 <= bound < 2 ** 31
+    clean = workloads.near_bound_workload(seed, S, M, C, K, **kw)
+    np.maximum(clean.w, 0, out=clean.w)                 # the generator plants negative w to test the clamp
+    assert lib.adaptra_check_inputs(lib.Problem.from_workload(clean)) == lib.OK
+    say(f"near the bound: {wl.name}, 2MS(t+c) = {bound / 2 ** 31:.4f} x 2^31")
+    check_full(lib, oracle, wl)
 
 
 @pytest.mark.parametrize("promise", ["kept", "broken"])
@@ -537,6 +610,45 @@ def test_zb_benchmarked_shape(lib, oracle):
             assert mkp[k, c] == rep["makespan"], (c, k)
 
 
+def test_zb_check_inputs(lib):
+    """adaptra_zb_check_inputs: the preconditions of adaptra_zb_eval on the device data --
+    forward and backward times of at least 1 us (weight times may be 0), nothing negative,
+    3 M S (max time + max delay) below 2^31."""
+    b = lib
+    S, N, C, K = 4, 8, 20, 6
+    rng = np.random.default_rng(5)
+    good = dict(t_f=rng.integers(1, 60, S), t_b=rng.integers(1, 90, S), t_w=rng.integers(0, 50, S),
+                w=np.sort(rng.integers(0, N, (S, C)), axis=0)[::-1],
+                cf=rng.integers(0, 400, (S - 1, K)), cb=rng.integers(0, 400, (S - 1, K)))
+    good["t_w"][1] = 0                                     # a stage without weight work is fine
+
+    def code(**change):
+        a = {k: np.array(v) for k, v in good.items()}
+        for name, (where, value) in change.items():
+            a[name][where] = value
+        prob, t_w = _zb_problem(b, S, N, a["t_f"], a["t_b"], a["t_w"], a["w"], a["cf"], a["cb"])
+        return b.adaptra_zb_check_inputs(prob, t_w)
+
+    assert code() == b.OK
+    assert code(t_f=(2, 0)) == b.ERANGE                   # a forward that takes no time
+    assert code(t_b=(0, 0)) == b.ERANGE
+    assert code(t_w=(3, -1)) == b.ERANGE
+    assert code(cf=((1, 2), -5)) == b.ERANGE
+    assert code(cb=((0, 0), -1)) == b.ERANGE
+    assert code(w=((2, 7), -1)) == b.ERANGE
+    limit = 2 ** 31 // (3 * N * S)                         # 3 M S t reaches 2^31 at t = limit + 1 (2^31 has no factor 3)
+    top = int(max(good["cf"].max(), good["cb"].max()))
+    assert code(t_w=(0, limit - top)) == b.OK              # 3 M S (t + c) just below 2^31
+    assert code(t_w=(0, limit - top + 1)) == b.EOVERFLOW
+    assert code(t_b=(3, limit + 1)) == b.EOVERFLOW
+    assert code(cf=((2, 5), limit + 1)) == b.EOVERFLOW
+    # the F/B bound (2 M S) is the weaker one: adaptra_check_inputs accepts what this rejects
+    a = {k: np.array(v) for k, v in good.items()}
+    a["t_b"][3] = limit + 1
+    prob, _ = _zb_problem(b, S, N, a["t_f"], a["t_b"], a["t_w"], a["w"], a["cf"], a["cb"])
+    assert b.adaptra_check_inputs(prob) == b.OK
+
+
 # ----------------------------------------------------------------------------------------
 # Per-scenario stage times (computation stragglers) and link sensitivities
 STAGE_TIME_CASES = [
@@ -724,8 +836,14 @@ def test_guided_search_parity(lib, oracle, seed, S, M, K, nb, iters, vt, kw):
         w, mk, rounds, evaluated = lib.adaptra_search(prob, torch.from_numpy(start).cuda(), nb, iters)
         lib.adaptra_set_kernel_mode(0)
         assert rounds == ref["rounds"], f"mode {mode}"
-        # the GPU path does not evaluate a scenario again once it has come to rest
-        still_moving = [K] + ref["moved_in_round"][:-1] if S > 1 and M > 1 else [K] * ref["rounds"]
+        # The GPU path does not evaluate a scenario again once it has come to rest (its pool
+        # would be the same in every later round), the oracle keeps evaluating all of them.  A
+        # move is a strict improvement, so the scenarios that moved in round r are those whose
+        # makespan differs between rounds r - 1 and r of the oracle's trajectory; round r + 1
+        # evaluates exactly those.
+        hist = np.concatenate([np.full((1, K), INT32_MAX, dtype=np.int64), ref["makespan_history"].astype(np.int64)])
+        moved = (hist[1:] != hist[:-1]).sum(axis=1)
+        still_moving = [K] + list(moved[:-1]) if S > 1 and M > 1 else [K] * ref["rounds"]
         assert evaluated == sum(still_moving[:ref["rounds"]]) * (len(osearch.moves(S, nb)) + 1)
         assert np.array_equal(mk.cpu().numpy(), ref["makespan"])
         assert np.array_equal(w.cpu().numpy(), ref["w"])
