@@ -68,6 +68,8 @@ extern "C" {
 #define ADAPTRA_ERANGE      4   /* adaptra_check_inputs, adaptra_zb_check_inputs: a time, delay or w out of range */
 #define ADAPTRA_EOVERFLOW   5   /* the same: 2 M S (max t + max c) >= 2^31 (3 M S with weight ops)             */
 
+#define ADAPTRA_ELIMIT      6   /* adaptra_best_static: a size beyond the maxima it states                 */
+
 #define ADAPTRA_FLAG_FEASIBLE 1
 #define ADAPTRA_FLAG_DEADLOCK 2
 #define ADAPTRA_FLAG_MEMCAP   4
@@ -151,6 +153,29 @@ int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *can
                  int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
                  uint64_t *out_hist,
                  void *workspace, size_t workspace_bytes, void *stream);
+
+/* adaptra_best for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops that re-decide on every measured scenario,
+ * harnesses that forbid hipMalloc.  Same arguments, outputs and results as adaptra_best, minus
+ * the workspace: the scratch the kernels need (candidate flags, packed warm-up counts, search
+ * keys, the general kernel's per-thread state) lives in a fixed array of
+ * ADAPTRA_STATIC_SCRATCH_MIB MiB of device memory inside the library, one copy per GPU the
+ * library is used on, held until the process ends.  The call itself allocates and frees
+ * nothing (its first call on a device looks the array's address up, so make that call outside
+ * a graph capture).  Limits, checked first: n_cand <= ADAPTRA_STATIC_MAX_CANDIDATES, n_scen <=
+ * ADAPTRA_STATIC_MAX_SCENARIOS, M <= ADAPTRA_STATIC_MAX_MICROBATCHES, else ADAPTRA_ELIMIT and
+ * nothing is enqueued.  All calls on one GPU share that GPU's array: calls that overlap in time
+ * on one GPU (different streams or threads) race and give undefined results -- run them on one
+ * stream, or serialise them.  The array keeps the last call's contents; nothing in it needs to
+ * be cleared by the caller.  Asynchronous on `stream`. */
+#define ADAPTRA_STATIC_SCRATCH_MIB        21
+#define ADAPTRA_STATIC_MAX_CANDIDATES     65536
+#define ADAPTRA_STATIC_MAX_SCENARIOS      4096
+#define ADAPTRA_STATIC_MAX_MICROBATCHES   1024
+int adaptra_best_static(const adaptra_params_t *params, const adaptra_candidates_t *cands,
+                        const adaptra_scenarios_t *scens,
+                        int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
+                        uint64_t *out_hist, void *stream);
 
 /* adaptra_eval and adaptra_best in one call, every pair resolved once: the search and the
  * histogram read the makespans the evaluation has just produced instead of running the

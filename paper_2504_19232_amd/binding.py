@@ -15,15 +15,16 @@ from typing import Optional
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libadaptra.so")
 
-OK, EINVAL, EWORKSPACE, EHIP, ERANGE, EOVERFLOW = 0, 1, 2, 3, 4, 5
+OK, EINVAL, EWORKSPACE, EHIP, ERANGE, EOVERFLOW, ELIMIT = 0, 1, 2, 3, 4, 5, 6
 ERROR_NAMES = {0: "ADAPTRA_OK", 1: "ADAPTRA_EINVAL", 2: "ADAPTRA_EWORKSPACE", 3: "ADAPTRA_EHIP",
-               4: "ADAPTRA_ERANGE", 5: "ADAPTRA_EOVERFLOW"}
+               4: "ADAPTRA_ERANGE", 5: "ADAPTRA_EOVERFLOW", 6: "ADAPTRA_ELIMIT"}
+STATIC_MAX_CANDIDATES, STATIC_MAX_SCENARIOS, STATIC_MAX_MICROBATCHES = 65536, 4096, 1024
 FLAG_FEASIBLE, FLAG_DEADLOCK, FLAG_MEMCAP = 1, 2, 4
 INT32_MAX = 2 ** 31 - 1
 
 # include/adaptra.h
 EXPORTS = ("adaptra_workspace_bytes", "adaptra_best_workspace_bytes", "adaptra_search_workspace_bytes", "adaptra_search",
-           "adaptra_check_inputs", "adaptra_eval", "adaptra_best", "adaptra_eval_best",
+           "adaptra_check_inputs", "adaptra_eval", "adaptra_best", "adaptra_best_static", "adaptra_eval_best",
            "adaptra_seed", "adaptra_sensitivity_workspace_bytes", "adaptra_sensitivity",
            "adaptra_zb_workspace_bytes", "adaptra_zb_check_inputs", "adaptra_zb_eval",
            "adaptra_last_hip_error", "adaptra_version")
@@ -103,6 +104,8 @@ def load() -> ctypes.CDLL:
         lib.adaptra_valu_probe.restype = ctypes.c_int
         lib.adaptra_valu_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp,
                                            ctypes.POINTER(ctypes.c_int64)]
+        lib.adaptra_best_static.restype = ctypes.c_int
+        lib.adaptra_best_static.argtypes = [P, C, Sc, vp, vp, vp, vp, vp]
         lib.adaptra_zb_check_inputs.restype = ctypes.c_int
         lib.adaptra_zb_check_inputs.argtypes = [P, vp, C, Sc, vp, sz, vp]
         lib.adaptra_last_hip_error.restype = ctypes.c_int
@@ -231,6 +234,17 @@ def adaptra_best(prob: Problem, out_best_idx=None, out_best_makespan=None, out_b
                              out_best_idx.data_ptr(), out_best_makespan.data_ptr(), _ptr(out_best_bubble),
                              _ptr(out_hist), ws.data_ptr(), ws.numel(), _stream(stream))
     _raise(rc, "adaptra_best")
+    return out_best_idx, out_best_makespan, out_best_bubble, out_hist
+
+
+def adaptra_best_static(prob: Problem, out_best_idx, out_best_makespan, out_best_bubble=None, out_hist=None, *,
+                        stream=None):
+    """Enqueue the per-scenario search on the library's own fixed scratch: the caller passes every
+    output, nothing is allocated here or in the library."""
+    rc = load().adaptra_best_static(ctypes.byref(prob.params), ctypes.byref(prob.cands), ctypes.byref(prob.scens),
+                                    out_best_idx.data_ptr(), out_best_makespan.data_ptr(), _ptr(out_best_bubble),
+                                    _ptr(out_hist), _stream(stream))
+    _raise(rc, "adaptra_best_static")
     return out_best_idx, out_best_makespan, out_best_bubble, out_hist
 
 

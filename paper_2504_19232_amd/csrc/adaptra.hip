@@ -37,6 +37,13 @@
 #include "adaptra_kernels.h"
 #include "adaptra_testing.h"
 
+// Scratch of adaptra_best_static, the entry point for callers that cannot allocate: one copy per
+// GPU the library runs on, held until the process ends.  Host code never uses this name as an
+// address (it is a host-side stand-in): the device address comes from hipGetSymbolAddress, once
+// per device (static_scratch below).
+constexpr size_t kStaticScratchBytes = (size_t)ADAPTRA_STATIC_SCRATCH_MIB << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 using namespace adaptra_detail;
@@ -505,20 +512,22 @@ struct Workspace {
 };
 
 // The general kernel keeps (2 S + M) ints per thread in scratch; bound the scratch to
-// about 256 MiB by limiting the number of resident threads.
-long long general_thread_count(int S, int M) {
+// about 256 MiB by limiting the number of resident threads.  small: the 16 MiB that
+// adaptra_best_static's fixed scratch sets aside for it (at least one block of threads; its
+// size limits keep that inside the 16 MiB).
+long long general_thread_count(int S, int M, bool small) {
     const long long per_thread = (2ll * S + M) * 4;
-    long long nt = (256ll << 20) / per_thread;
+    long long nt = ((small ? 16ll : 256ll) << 20) / per_thread;
     if (nt > 65536) nt = 65536;
-    if (nt < 4096) nt = 4096;
+    if (nt < (small ? kBlock : 4096)) nt = small ? kBlock : 4096;
     return nt / kBlock * kBlock;
 }
 
-bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws, bool with_mkt = true) {
+bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws, bool with_mkt = true, bool small = false) {
     if (S < 1 || S > ADAPTRA_MAX_STAGES || M < 1 || M > ADAPTRA_MAX_MICROBATCHES) return false;
     if (C < 1 || C > INT32_MAX || K < 1 || K > INT32_MAX) return false;
     ws->wq_stride = (cand_kernel_stages(S) + 3) & ~3;
-    ws->general_threads = general_thread_count(S, M);
+    ws->general_threads = general_thread_count(S, M, small);
     size_t o = 0;
     ws->off_flag = o;    o += adaptra_detail::align256((size_t)C);
     ws->off_class = o;   o += adaptra_detail::align256((size_t)C);
@@ -576,9 +585,9 @@ int grid_for(long long n, long long cap = 1 << 20) {
 
 int validate_common(const adaptra_params_t *p, const adaptra_candidates_t *cd,
                     const adaptra_scenarios_t *sc, void *workspace, size_t workspace_bytes,
-                    Workspace *ws, bool with_mkt = true) {
+                    Workspace *ws, bool with_mkt = true, bool small = false) {
     if (!p || !cd || !sc) return ADAPTRA_EINVAL;
-    if (!plan_workspace(p->S, p->M, cd->n, sc->n, ws, with_mkt)) return ADAPTRA_EINVAL;
+    if (!plan_workspace(p->S, p->M, cd->n, sc->n, ws, with_mkt, small)) return ADAPTRA_EINVAL;
     if (!p->t_f || !p->t_b || !cd->w) return ADAPTRA_EINVAL;
     if (p->S > 1 && (!sc->c_fwd || !sc->c_bwd)) return ADAPTRA_EINVAL;
     if ((sc->t_f == nullptr) != (sc->t_b == nullptr)) return ADAPTRA_EINVAL;
@@ -703,6 +712,27 @@ int launch_resolve(KArgs a, const Workspace &ws, int w_bound, hipStream_t st, in
     if ((rc = record_event(g_ev_before, st))) return rc;
     if ((rc = launch_general<BEST>(a, ws, true, st))) return rc;
     return record_event(g_ev_after, st);
+}
+
+// Device address of the current GPU's copy of `scratch`.  Looked up on the first call on each
+// device, with that device current, and kept: every GPU holds its own copy of the array at its
+// own address.  (Two threads racing through the first call store the same value.)
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_static_scratch[kMaxDevices];
+int static_scratch(void **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return ADAPTRA_EINVAL;
+    void *ptr = g_static_scratch[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (!ptr || ((uintptr_t)ptr & 255)) return ADAPTRA_EWORKSPACE;
+        g_static_scratch[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return ADAPTRA_OK;
 }
 
 }  // namespace
@@ -890,6 +920,24 @@ int adaptra_best(const adaptra_params_t *params, const adaptra_candidates_t *can
                                 out_hist, workspace, workspace_bytes, stream);
 }
 
+int adaptra_best_static(const adaptra_params_t *params, const adaptra_candidates_t *cands,
+                        const adaptra_scenarios_t *scens,
+                        int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
+                        uint64_t *out_hist, void *stream) {
+    if (!params || !cands || !scens) return ADAPTRA_EINVAL;
+    if (cands->n > ADAPTRA_STATIC_MAX_CANDIDATES || scens->n > ADAPTRA_STATIC_MAX_SCENARIOS ||
+        params->M > ADAPTRA_STATIC_MAX_MICROBATCHES)
+        return ADAPTRA_ELIMIT;
+    void *ptr = nullptr;
+    const int rc = static_scratch(&ptr);
+    if (rc) return rc;
+    // Every kernel takes the workspace through its arguments, exactly as in adaptra_best; what
+    // must start at zero (status words, search keys, histogram) is cleared by the kernels of
+    // the call itself, so the previous call's contents do not matter.
+    return adaptra_detail::best(params, cands, scens, 0, out_best_idx, out_best_makespan, out_best_bubble,
+                                out_hist, ptr, kStaticScratchBytes, stream, true);
+}
+
 
 }  // extern "C"
 
@@ -900,9 +948,9 @@ int adaptra_detail::best(const adaptra_params_t *params, const adaptra_candidate
                          const adaptra_scenarios_t *scens, int pair_div,
                          int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
                          uint64_t *out_hist,
-                         void *workspace, size_t workspace_bytes, void *stream) {
+                         void *workspace, size_t workspace_bytes, void *stream, bool small_scratch) {
     Workspace ws;
-    int rc = validate_common(params, cands, scens, workspace, workspace_bytes, &ws, false);
+    int rc = validate_common(params, cands, scens, workspace, workspace_bytes, &ws, false, small_scratch);
     if (rc) return rc;
     if (!out_best_idx || !out_best_makespan) return ADAPTRA_EINVAL;
     if (params->hist_bins < 0 || params->hist_bins > 65536) return ADAPTRA_EINVAL;

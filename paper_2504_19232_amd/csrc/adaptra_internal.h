@@ -16,11 +16,12 @@ constexpr int kThreadsPerBlock = 256;
 // Records the hipError_t for adaptra_last_hip_error and returns ADAPTRA_EHIP.
 int hip_fail(hipError_t e);
 
-// adaptra_best with one more argument: pair_div > 0 evaluates candidate c under scenario
-// c / pair_div only (0: every candidate under every scenario).
+// adaptra_best with two more arguments: pair_div > 0 evaluates candidate c under scenario
+// c / pair_div only (0: every candidate under every scenario); small_scratch plans the
+// workspace with the general kernel's share held to 16 MiB (adaptra_best_static).
 int best(const adaptra_params_t *params, const adaptra_candidates_t *cands, const adaptra_scenarios_t *scens,
          int pair_div, int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
-         uint64_t *out_hist, void *workspace, size_t workspace_bytes, void *stream);
+         uint64_t *out_hist, void *workspace, size_t workspace_bytes, void *stream, bool small_scratch = false);
 
 // Workspace sections start on 256-byte boundaries.
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }

@@ -88,6 +88,20 @@ def test_zb_and_search_reject_bad_arguments_without_touching_the_gpu(binding):
     assert lib.adaptra_zb_check_inputs(*args, 256, 64, None) == binding.EWORKSPACE
 
 
+def test_static_entry_point_rejects_sizes_beyond_its_limits_without_touching_the_gpu(binding):
+    lib = binding.load()
+    p = binding.Params(4, 8, 1, 1, None, 0, 0)
+    s = binding.Scenarios(6, 1, 1, None, None)
+    too_many = binding.Candidates(binding.STATIC_MAX_CANDIDATES + 1, 1, -1)
+    assert lib.adaptra_best_static(ctypes.byref(p), ctypes.byref(too_many), ctypes.byref(s), 1, 1, None, None, None) == binding.ELIMIT
+    c = binding.Candidates(10, 1, -1)
+    wide = binding.Scenarios(binding.STATIC_MAX_SCENARIOS + 1, 1, 1, None, None)
+    assert lib.adaptra_best_static(ctypes.byref(p), ctypes.byref(c), ctypes.byref(wide), 1, 1, None, None, None) == binding.ELIMIT
+    long_ = binding.Params(4, binding.STATIC_MAX_MICROBATCHES + 1, 1, 1, None, 0, 0)
+    assert lib.adaptra_best_static(ctypes.byref(long_), ctypes.byref(c), ctypes.byref(s), 1, 1, None, None, None) == binding.ELIMIT
+    assert lib.adaptra_best_static(None, None, None, None, None, None, None, None) == binding.EINVAL
+
+
 def test_grid_limits_are_checked_before_anything_is_enqueued(binding):
     """2^31 - 1 candidates x 2^31 - 1 scenarios make more 64 x 64 tiles than a grid holds: EINVAL
     from the planning, ahead of the workspace test and of every launch."""
