@@ -10,9 +10,21 @@ outputs, the feasible pairs resolved a second time by the search).  `value` coun
 (candidate, scenario) pair once per step.
 
 Prints ONE JSON line (see the fields below).  `roofline` prices the dominant kernel (the
-recurrence kernel of adaptra_eval) against the integer-VALU peak: 3 int32 operations per
-resolved op (add the link delay, max with the stage frontier, add the duration), divided by
-the kernel's duration measured with HIP events recorded by the library on its own stream.
+recurrence kernel of adaptra_eval) against the integer-VALU peak, with the kernel's duration
+measured by HIP events the library records on its own stream:
+  frac              3 int32 operations per resolved op (add the link delay, max with the stage
+                    frontier, add the duration) against 256 CUs x 64 lanes x 2.4 GHz.  Not bounded
+                    by 1: the kernel's formulation needs 2 operations, and adds issue at twice
+                    the rate of the peak's one instruction per SIMD per four cycles.
+  frac_formulation  the least time the kernel's own formulation could take on this chip -- per
+                    resolved op one add on vector operands (two cycles of a SIMD per wavefront,
+                    the measured double rate) and one max (four cycles) -- over the time it
+                    takes.  At most 1 by construction.
+  valu_busy_min/max share of the SIMDs' cycles in which the vector ALU is occupied by this kernel,
+                    from the instruction count of the committed rocprofv3 summary: max prices
+                    every instruction at four cycles, min prices one add per resolved op at two
+                    (the adds on vector operands, if each of them got the double rate).  null
+                    when the summary was measured on other sources than the ones in the tree.
 `cpu_baseline` is the CPU oracle timed on a bounded sample of the same pairs.
 """
 import argparse
@@ -74,10 +86,10 @@ def from_profile(S: int, config: int) -> dict:
     """Figures that cannot be measured from inside this process, read from the committed
     rocprofv3 summary of the resolve kernel on this workload: HBM bytes per launch (FETCH_SIZE
     and WRITE_SIZE, scaled by a copy of known size) and the vector instructions the kernel
-    issues per launch (SQ_INSTS_VALU), split into the ones that take a full issue slot and the
-    selects.  Every value is None when there is no summary or when the summary was measured on
+    issues per launch (SQ_INSTS_VALU) with the shader clock cycles that launch took
+    (GRBM_GUI_ACTIVE per XCD).  Every value is None when there is no summary or when the summary was measured on
     other sources than the ones in the tree now."""
-    out = {"traffic": None, "valu_instructions": None, "valu_select_instructions": None, "profile_is_current": False}
+    out = {"traffic": None, "valu_instructions": None, "cycles": None, "profile_is_current": False}
     path = os.path.join(ROOT, "profiles", f"resolve_scen_lanes_S{S}_config{config}.txt")
     try:
         lines = open(path).read().splitlines()
@@ -87,7 +99,7 @@ def from_profile(S: int, config: int) -> dict:
     for line in lines:
         s = line.strip()
         for key in ("source_sha256", "traffic_bytes_per_launch", "valu_instructions_per_launch",
-                    "valu_select_instructions_per_launch"):
+                    "shader_cycles_per_launch"):
             if s.startswith(key) and "=" in s:
                 found[key] = s.split("=")[1].strip()
     if found.get("source_sha256") != kernel_source_sha256():
@@ -96,7 +108,7 @@ def from_profile(S: int, config: int) -> dict:
     try:
         out["traffic"] = int(found["traffic_bytes_per_launch"])
         out["valu_instructions"] = float(found["valu_instructions_per_launch"])
-        out["valu_select_instructions"] = float(found["valu_select_instructions_per_launch"])
+        out["cycles"] = float(found["shader_cycles_per_launch"])
     except (KeyError, ValueError):
         pass
     return out
@@ -394,6 +406,14 @@ def main():
     kernel_avg_ms = float(np.mean(kernel_ms))
     achieved = 3.0 * ops_eval / (kernel_avg_ms * 1e-3)
     prof = from_profile(hot_S, args.config)
+    simds = 256 * 4
+    # the kernel's own formulation: per resolved op one add at the double rate (2 SIMD cycles per
+    # wavefront instruction) and one max (4 cycles), nothing else
+    floor_s = ops_eval / 64 * (2 + 4) / (simds * 2.4e9)
+    busy_min = busy_max = None
+    if prof["valu_instructions"] and prof["cycles"]:
+        busy_max = prof["valu_instructions"] * 4 / (simds * prof["cycles"])
+        busy_min = (prof["valu_instructions"] * 4 - ops_eval / 64 * 2) / (simds * prof["cycles"])
 
     out = {
         "metric": "schedule_evaluations_per_sec",
@@ -418,9 +438,12 @@ def main():
         "roofline": {"bound": "alu", "kernel": f"k_resolve_scen_lanes<{hot_S}, false, false>",
                      "achieved": achieved / 1e12, "peak": INT32_VALU_PEAK / 1e12, "unit": "Tint32op/s",
                      "frac": achieved / INT32_VALU_PEAK, "traffic": prof["traffic"],
+                     "frac_formulation": floor_s / (kernel_avg_ms * 1e-3),
+                     "valu_busy_min": busy_min, "valu_busy_max": busy_max,
                      "peak_measured": measured_peak / 1e12, "frac_of_measured": achieved / measured_peak,
+                     "probe_valu_instructions_per_simd_per_4_cycles": {k: v / (simds * 2.4e9 / 4) for k, v in rates.items()},
                      "kernel_ms": kernel_avg_ms, "resolved_ops_per_launch": ops_eval,
-                     "algorithmic_ops_per_resolved_op": 3},
+                     "algorithmic_ops_per_resolved_op": 3, "profile_is_current": prof["profile_is_current"]},
     }
     if seed_info:
         out["seed"] = seed_info

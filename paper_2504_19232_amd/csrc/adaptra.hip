@@ -62,6 +62,7 @@ __global__ __launch_bounds__(kBlock) void k_prepass(KArgs a) {
     }
     __syncthreads();
     long long c = (long long)blockIdx.x * kBlock + threadIdx.x;
+    bool listed = false;
     if (c < a.C) {
     const int S = a.S, M = a.M;
     bool dead = false, mem = false;
@@ -94,6 +95,19 @@ __global__ __launch_bounds__(kBlock) void k_prepass(KArgs a) {
     a.cand_flag[c] = (unsigned char)flag;
     a.cand_class[c] = (unsigned char)cls;
     if (!dead) atomicAdd(&class_count[cls == kClassDeep ? kNumRingClasses : cls], 1);
+    listed = flag == ADAPTRA_FLAG_FEASIBLE && cls < kNumRingClasses;
+    }
+    // The feasible candidates that an on-chip kernel can take, as a list for the search of the
+    // candidate-lanes kernel: one atomic per wavefront reserves its entries' places.
+    if (a.live_list) {
+        const unsigned long long votes = __ballot(listed);
+        if (votes) {
+            const int lane = threadIdx.x & 63;
+            int base = 0;
+            if (lane == __ffsll((long long)votes) - 1) base = atomicAdd(&a.status[48], __popcll(votes));
+            base = __builtin_amdgcn_readlane(base, __ffsll((long long)votes) - 1);
+            if (listed) a.live_list[base + __popcll(votes & ((1ull << lane) - 1ull))] = (int)c;
+        }
     }
     __syncthreads();       // how many candidates need which ring depth: lets the kernels that
     if (threadIdx.x <= kNumRingClasses && class_count[threadIdx.x])   // have no share exit at once
@@ -506,7 +520,7 @@ thread_local hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;
 
 
 struct Workspace {
-    size_t off_flag, off_class, off_wq, off_keys, off_status, off_tpad, off_scratch, off_mkt, total;
+    size_t off_flag, off_class, off_wq, off_live, off_keys, off_status, off_tpad, off_scratch, off_mkt, total;
     int wq_stride;
     long long general_threads;
 };
@@ -532,6 +546,7 @@ bool plan_workspace(int S, int M, long long C, long long K, Workspace *ws, bool 
     ws->off_flag = o;    o += adaptra_detail::align256((size_t)C);
     ws->off_class = o;   o += adaptra_detail::align256((size_t)C);
     ws->off_wq = o;      o += adaptra_detail::align256((size_t)C * ws->wq_stride);
+    ws->off_live = o;    o += adaptra_detail::align256((size_t)C * 4);
     ws->off_keys = o;    o += adaptra_detail::align256((size_t)K * 8);
     ws->off_status = o;  o += 256;
     ws->off_tpad = o;    o += 512;
@@ -610,6 +625,7 @@ void fill_args(KArgs *a, const adaptra_params_t *p, const adaptra_candidates_t *
     a->wq_stride = ws.wq_stride;
     a->keys = (unsigned long long *)(base + ws.off_keys);
     a->status = (int *)(base + ws.off_status);
+    a->live_list = nullptr;                // adaptra_best sets it: only the search walks the list
     a->tpad = (int *)(base + ws.off_tpad);
     a->scratch = (int *)(base + ws.off_scratch);
     a->mk_t = (int *)(base + ws.off_mkt);
@@ -968,6 +984,7 @@ int adaptra_detail::best(const adaptra_params_t *params, const adaptra_candidate
     a.hist_in_lds = (size_t)a.S * a.hist_bins * 4 <= (size_t)kMaxLdsHistBytes;
     if (pair_div < 0 || (pair_div > 0 && (cands->n + pair_div - 1) / pair_div > scens->n)) return ADAPTRA_EINVAL;
     a.pair_div = pair_div;
+    a.live_list = (int *)((char *)workspace + ws.off_live);
     if (!grids_fit(a)) return ADAPTRA_EINVAL;
     hipLaunchKernelGGL(k_zero_status, dim3(1), dim3(64), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();

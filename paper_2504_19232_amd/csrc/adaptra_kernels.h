@@ -73,7 +73,8 @@ struct KArgs {
     long long n_chunks;
     int chunk;                             // candidates per wavefront of the hot kernel (1..kChunk)
     int n_ktiles;
-    int *status;                           // [0..3] input check, [16..32] candidates per ring class
+    int *status;                           // [0..3] input check, [16..32] candidates per ring class, [48] entries of live_list
+    int *live_list;                        // search only: the feasible candidates an on-chip kernel can take, in any order
     int *mk_t;                             // eval: makespan, candidate-major [C][K]
     int *tpad;                             // t_f at [0..63], t_b at [64..127], zero beyond stage S-1
     int kernel_mode;                       // host side only: the kernel selection this call runs under
@@ -265,7 +266,13 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 48 || (VT && S >= 16) ? 2 : (
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int D = kargs()->ring_slots, M = kargs()->M;
     int *const ring = lds + wv * D * 64 + lane;          // slot i of this lane at ring[i * 64]
-    const long long ctiles = (kargs()->C + 63) / 64;
+    // The search (BEST) walks the pre-pass's list of feasible candidates instead of the candidate
+    // axis itself, 64 list entries per tile: a tile costs the same however many of its lanes carry
+    // a pair, and among all candidates the feasible ones can be few (the guided search's pools hold
+    // every neighbour of a point, most of which break Lemma 1 or a memory cap).  The order of the
+    // list is arbitrary; the result -- a minimum over (makespan, candidate) keys -- is not.
+    const long long n_cand = BEST ? (long long)uni(kargs()->status[48]) : kargs()->C;
+    const long long ctiles = (n_cand + 63) / 64;
     const long long ntiles = kargs()->pair_div ? ctiles : kargs()->K * ctiles;
     const long long nwaves = (long long)gridDim.x * kWavesPerBlock;
     // Stage times come from the zero-padded table, re-read in blocks of 16 stages inside the
@@ -274,12 +281,15 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 48 || (VT && S >= 16) ? 2 : (
     constexpr int kTimesBlock = 16;
     typedef __attribute__((address_space(4))) int ConstInt;   // written by k_prepass, constant here
     for (long long tile = (long long)blockIdx.x * kWavesPerBlock + wv; tile < ntiles; tile += nwaves) {
-        const long long c = (tile % ctiles) * 64 + lane;
-        const long long k = kargs()->pair_div ? (c < kargs()->C ? c / kargs()->pair_div : 0) : tile / ctiles;
+        const long long at = (tile % ctiles) * 64 + lane;
+        const bool have = at < n_cand;
+        long long c = at;
+        if constexpr (BEST) c = have ? kargs()->live_list[at] : 0;
+        const long long k = kargs()->pair_div ? (have ? c / kargs()->pair_div : 0) : tile / ctiles;
         const long long kin = k % kargs()->Kin;
         const int link_up = (int)(k / kargs()->Kin) - 1;
         bool run = false;
-        if (c < kargs()->C) {
+        if (have) {
             const int flag = kargs()->cand_flag[c];
             const int cls = kargs()->cand_class[c];
             run = (BEST ? (flag == ADAPTRA_FLAG_FEASIBLE) : !(flag & ADAPTRA_FLAG_DEADLOCK)) &&
