@@ -331,10 +331,23 @@ def main():
         t_zb = timed(lambda: binding.adaptra_zb_eval(zprob, t_w, -1, workspace=zws), n=2)
         t_zbp = timed(lambda: binding.adaptra_zb_eval(zprob, t_w, 0, workspace=zws), n=2)
         zops = zprob.C * zprob.K * 3 * wz.S * wz.M
+        # Integer work a started op cannot do without.  Policy: the earliest-action scan over the
+        # stages (S - 1 comparisons), the choice among backward / forward / weight op (2), the
+        # start (one max), the finish and the arrival it posts (two adds): S + 4.  A fixed plan
+        # replayed: max, add, add.
+        zb_policy_ops, zb_replay_ops = wz.S + 4, 3
         zb_info = {"workload": f"{wz.name} + W ops: {zprob.C} candidates x {zprob.K} scenarios",
                    "policy_ms": t_zb * 1e3, "policy_evaluations_per_s": zprob.C * zprob.K / t_zb,
                    "policy_resolved_ops_per_s": zops / t_zb,
-                   "fixed_plan_ms": t_zbp * 1e3, "fixed_plan_evaluations_per_s": zprob.C * zprob.K / t_zbp}
+                   "fixed_plan_ms": t_zbp * 1e3, "fixed_plan_evaluations_per_s": zprob.C * zprob.K / t_zbp,
+                   "roofline": {"bound": "alu", "peak": INT32_VALU_PEAK / 1e12, "unit": "Tint32op/s",
+                                "policy": {"algorithmic_ops_per_resolved_op": zb_policy_ops,
+                                           "achieved": zb_policy_ops * zops / t_zb / 1e12,
+                                           "frac": zb_policy_ops * zops / t_zb / INT32_VALU_PEAK},
+                                "fixed_plan": {"algorithmic_ops_per_resolved_op": zb_replay_ops,
+                                               "achieved": zb_replay_ops * zops / t_zbp / 1e12,
+                                               "frac": zb_replay_ops * zops / t_zbp / INT32_VALU_PEAK,
+                                               "includes": "the recording launch (one scenario) and the replay under all"}}}
         del zws, zprob
 
     # computation stragglers (per-scenario stage times) on the same workload, and the link

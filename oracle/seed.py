@@ -1,4 +1,4 @@
-"""The paper's analytic warm-up planning, written out step by step -- TEST INFRASTRUCTURE.
+"""The paper's analytic warm-up planning, written from its definitions -- TEST INFRASTRUCTURE.
 
 Plain Python integers, one function per algorithm, in the paper's notation
 (x_i = warm-up forward count of stage i, Delta_i = x_i - x_{i+1}).  Results are
@@ -9,45 +9,46 @@ import this module.  Pinned by tests/test_oracle_seed_pins.py.
 from __future__ import annotations
 
 
-def get_init_warmup_fwds(S: int, x_max: int):
-    """Algorithm 1 (initial planning): the first stage holds x_max forwards, the slack
-    x_max - 1 is spread over the S - 1 links as evenly as possible, the first
-    (x_max - 1) mod (S - 1) links getting one more.  x_max = floor(M / M^F) is passed in."""
+def initial_plan(S: int, x_max: int):
+    """Algorithm 1 (initial planning), from what it is defined to achieve: stage 0 holds x_max
+    warm-up forwards (the memory limit, x_max = floor(M / M^F), passed in), the last stage 1, and
+    the x_max - 1 units of slack in between are shared out over the S - 1 links as evenly as
+    integers allow, the links nearest stage 0 taking the units left over.  x_i is x_max minus
+    the slack of the links above stage i."""
     if S < 1 or x_max < 1:
         raise ValueError("S >= 1 and x_max >= 1 required")
-    x = [x_max]
     if S == 1:
-        return x
-    d_avg = (x_max - 1) // (S - 1)
-    r = (x_max - 1) % (S - 1)
-    for i in range(1, S):
-        d = d_avg + 1 if i <= r else d_avg
-        x.append(x[i - 1] - d)
-    return x
+        return [x_max]
+    share, left_over = divmod(x_max - 1, S - 1)
+    slack = [share + 1] * left_over + [share] * (S - 1 - left_over)          # link 0 first
+    return [x_max - sum(slack[:i]) for i in range(S)]
 
 
-def get_adapted_warmup_fwds(S: int, N: int, t_f, t_b, c_fwd, c_bwd):
-    """Algorithm 2 (dynamic adaptation): x_{S-1} = 1 and, from the last link backwards,
-    Delta_i = min(N - 2S, max(ceil((t^F_i + t^B_i + 2 c_i) / (t^F_{i+1} + t^B_{i+1})), 2)),
-    x_i = x_{i+1} + Delta_i.
+def link_slack(N: int, S: int, tau_i: int, tau_next: int, c_fwd_i: int, c_bwd_i: int) -> int:
+    """The slack Algorithm 2 gives link i: the smallest Delta >= 2 for which Eq. (1) holds,
+    tau_i + 2 c_i <= Delta tau_{i+1}, clipped at N - 2 S.
 
     Readings (the paper is silent): the two directions of a link may differ, so 2 c_i is
     c_fwd[i] + c_bwd[i]; a zero denominator makes the ratio infinite (the clip decides);
-    the clip N - 2S can be below 0, so Delta_i is floored at 0 (Lemma 1) and x_i is capped
-    at N (a stage cannot warm up more forwards than there are micro-batches)."""
-    x = [0] * S
-    x[S - 1] = 1
-    for i in range(S - 2, -1, -1):
-        num = int(t_f[i]) + int(t_b[i]) + int(c_fwd[i]) + int(c_bwd[i])
-        den = int(t_f[i + 1]) + int(t_b[i + 1])
-        clip = N - 2 * S
-        if den == 0:
-            d = clip
-        else:
-            d = min(clip, max(-(-num // den), 2))
-        d = max(d, 0)
-        x[i] = min(x[i + 1] + d, N)
-    return x
+    the clip N - 2S can be below 0, so the slack is floored at 0 (Lemma 1)."""
+    clip = N - 2 * S
+    if tau_next == 0:
+        want = clip
+    else:
+        load = tau_i + c_fwd_i + c_bwd_i
+        want = min(clip, max(-(-load // tau_next), 2))            # ceiling division
+    return max(want, 0)
+
+
+def adapted_plan(S: int, N: int, t_f, t_b, c_fwd, c_bwd):
+    """Algorithm 2 (dynamic adaptation): the last stage holds one warm-up forward and every
+    stage above it as many more as the slacks of the links below it add up to, x_i = 1 +
+    sum of Delta_j for j >= i, capped at N (a stage cannot warm up more forwards than there
+    are micro-batches; the slacks are not negative, so capping the sums equals capping every
+    step of the listing's recurrence x_i = x_{i+1} + Delta_i)."""
+    tau = [int(t_f[i]) + int(t_b[i]) for i in range(S)]
+    slack = [link_slack(N, S, tau[i], tau[i + 1], int(c_fwd[i]), int(c_bwd[i])) for i in range(S - 1)]
+    return [min(N, 1 + sum(slack[i:])) for i in range(S)]
 
 
 def absorbed(S: int, t_f, t_b, w, c_fwd, c_bwd):

@@ -442,7 +442,7 @@ __global__ void k_zero_status(KArgs a) {
 
 // ---------------------------------------------------------------------------------------
 // The paper's analytic planning, one thread per scenario (Section 4.2).
-//   Algorithm 1 (initial planning, scenario independent; thread 0 only): x_0 = x_max, the
+//   Algorithm 1 (initial planning, scenario independent; the first S threads): x_0 = x_max, the
 //     slack x_max - 1 spread over the S - 1 links as evenly as possible, x_{S-1} = 1.
 //   Algorithm 2 (dynamic adaptation): x_{S-1} = 1, and from the last link backwards
 //     Delta_i = min(M - 2S, max(ceil((t_f[i] + t_b[i] + c_fwd[i] + c_bwd[i]) / (t_f[i+1] + t_b[i+1])), 2)),
@@ -461,51 +461,70 @@ struct SeedArgs {
 __global__ __launch_bounds__(kBlock) void k_seed(SeedArgs a) {
     const long long k = (long long)blockIdx.x * kBlock + threadIdx.x;
     const int S = a.S;
-    if (k == 0 && a.w_init) {
+    // Algorithm 1: the x_max - 1 units of slack go to the S - 1 links in equal shares, the
+    // links nearest stage 0 taking the units left over; stage s holds x_max minus the slack of
+    // the s links above it.  One thread per stage.
+    if (k < S && a.w_init) {
+        const int s = (int)k;
         int x = a.x_max;
-        a.w_init[0] = x - 1;
         if (S > 1) {
-            const int avg = (a.x_max - 1) / (S - 1), r = (a.x_max - 1) % (S - 1);
-            for (int i = 1; i < S; ++i) {
-                x -= (i <= r) ? avg + 1 : avg;
-                a.w_init[i] = x - 1;
-            }
+            const int share = (a.x_max - 1) / (S - 1), left_over = (a.x_max - 1) % (S - 1);
+            x -= s * share + (s < left_over ? s : left_over);
         }
+        a.w_init[s] = x - 1;
     }
     if (k >= a.K) return;
     auto tau = [&](int i) -> long long {       // t_f + t_b of stage i as this scenario sees it
         return a.tfs ? (long long)a.tfs[(long long)i * a.K + k] + a.tbs[(long long)i * a.K + k]
                      : (long long)a.t_f[i] + a.t_b[i];
     };
-    // One pass over the links, last to first, serves both outputs: the delays are read once.
+    // One pass over the links, last to first, serves both outputs: the delays are read once,
+    // four links at a time so that their loads are in flight together (a link's slack needs
+    // the one below it only through the running sum x).
+    const int *__restrict__ const cf = a.cf + k, *__restrict__ const cb = a.cb + k;
+    int *__restrict__ const w_adapted = a.w_adapted ? a.w_adapted + k : nullptr;
+    unsigned char *__restrict__ const not_absorbed = a.not_absorbed ? a.not_absorbed + k : nullptr;
+    const long long K = a.K;
     int x = 1;
-    if (a.w_adapted) a.w_adapted[(long long)(S - 1) * a.K + k] = 0;
+    if (w_adapted) w_adapted[(long long)(S - 1) * K] = 0;
     const int clip = a.M - 2 * S;
     long long tau_next = S > 1 ? tau(S - 1) : 0;
-    for (int i = S - 2; i >= 0; --i) {
-        const long long tau_i = tau(i);
-        const long long num = tau_i + a.cf[(long long)i * a.K + k] + a.cb[(long long)i * a.K + k];
-        const long long den = tau_next;
-        if (a.w_adapted) {
-            long long d = clip;
-            if (den != 0) {
-                // ceil(num / den); both are sums of non-negative int32 values, and whenever they fit
-                // 32 bits (always, under adaptra_check_inputs' bound) a 32-bit division does
-                const long long up = num + den - 1;
-                long long ratio = ((unsigned long long)(up | den) >> 32) == 0 ? (long long)((unsigned)up / (unsigned)den) : up / den;
-                if (ratio < 2) ratio = 2;
-                if (ratio < d) d = ratio;
+    constexpr int kLinks = 4;
+    for (int i0 = S - 2; i0 >= 0; i0 -= kLinks) {
+        long long load_i[kLinks], tau_i[kLinks];
+#pragma unroll
+        for (int j = 0; j < kLinks; ++j) {
+            const int i = i0 - j;
+            if (i < 0) break;
+            tau_i[j] = tau(i);
+            load_i[j] = tau_i[j] + cf[(long long)i * K] + cb[(long long)i * K];
+        }
+#pragma unroll
+        for (int j = 0; j < kLinks; ++j) {
+            const int i = i0 - j;
+            if (i < 0) break;
+            const long long num = load_i[j], den = tau_next;
+            if (w_adapted) {
+                long long d = clip;
+                if (den != 0) {
+                    // ceil(num / den); both are sums of non-negative int32 values, and whenever they fit
+                    // 32 bits (always, under adaptra_check_inputs' bound) a 32-bit division does
+                    const long long up = num + den - 1;
+                    long long ratio = ((unsigned long long)(up | den) >> 32) == 0 ? (long long)((unsigned)up / (unsigned)den) : up / den;
+                    if (ratio < 2) ratio = 2;
+                    if (ratio < d) d = ratio;
+                }
+                if (d < 0) d = 0;
+                const long long nx = x + d;
+                x = nx > a.M ? a.M : (int)nx;
+                w_adapted[(long long)i * K] = x - 1;
             }
-            if (d < 0) d = 0;
-            const long long nx = x + d;
-            x = nx > a.M ? a.M : (int)nx;
-            a.w_adapted[(long long)i * a.K + k] = x - 1;
+            if (not_absorbed) {
+                const long long rhs = ((long long)a.w_cur[i] - a.w_cur[i + 1]) * den;
+                not_absorbed[(long long)i * K] = num <= rhs ? 0 : 1;
+            }
+            tau_next = tau_i[j];
         }
-        if (a.not_absorbed) {
-            const long long rhs = ((long long)a.w_cur[i] - a.w_cur[i + 1]) * den;
-            a.not_absorbed[(long long)i * a.K + k] = num <= rhs ? 0 : 1;
-        }
-        tau_next = tau_i;
     }
 }
 
@@ -644,11 +663,13 @@ void fill_args(KArgs *a, const adaptra_params_t *p, const adaptra_candidates_t *
 
 // Every grid of the evaluation path that grows with the problem, checked before the first
 // launch, so that ADAPTRA_EINVAL always means that nothing was enqueued: the 64 x 64 tiles of
-// the epilogue and of the search over an evaluation, and the scenario-lanes kernel's blocks.
-bool grids_fit(const KArgs &a) {
+// the epilogue and of the search over an evaluation (only where an evaluation is written out),
+// and the scenario-lanes kernel's blocks (never used in the paired form, whose kernels walk
+// their tiles in a loop).
+bool grids_fit(const KArgs &a, bool writes_evaluation) {
     const long long tiles = ((a.C + 63) / 64) * ((a.K + 63) / 64);
-    const long long hot_blocks = (a.n_chunks * a.n_ktiles + kWavesPerBlock - 1) / kWavesPerBlock;
-    return tiles <= INT32_MAX && hot_blocks <= INT32_MAX;
+    const long long hot_blocks = a.pair_div ? 0 : (a.n_chunks * a.n_ktiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    return (!writes_evaluation || tiles <= INT32_MAX) && hot_blocks <= INT32_MAX;
 }
 
 template <bool BEST>
@@ -811,7 +832,7 @@ int adaptra_eval(const adaptra_params_t *params, const adaptra_candidates_t *can
     a.out_makespan = out_makespan;
     a.out_bubble = out_bubble;
     a.out_feasible = out_feasible;
-    if (!grids_fit(a)) return ADAPTRA_EINVAL;
+    if (!grids_fit(a, true)) return ADAPTRA_EINVAL;
     hipLaunchKernelGGL(k_zero_status, dim3(1), dim3(64), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_prepass, dim3(grid_for(a.C, INT32_MAX)), dim3(kBlock), 0, st, a);
@@ -852,7 +873,7 @@ int adaptra_eval_best(const adaptra_params_t *params, const adaptra_candidates_t
     a.hist_bins = params->hist_bins;
     a.hist_shift = params->hist_shift;
     a.hist_in_lds = (size_t)a.S * a.hist_bins * 4 <= (size_t)kMaxLdsHistBytes;
-    if (!grids_fit(a)) return ADAPTRA_EINVAL;
+    if (!grids_fit(a, true)) return ADAPTRA_EINVAL;
     hipLaunchKernelGGL(k_zero_status, dim3(1), dim3(64), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_prepass, dim3(grid_for(a.C, INT32_MAX)), dim3(kBlock), 0, st, a);
@@ -915,7 +936,7 @@ int adaptra_sensitivity(const adaptra_params_t *params, const adaptra_candidates
     a.out_makespan = out_makespan;
     a.out_feasible = out_feasible;
     a.out_bubble = out_sens;
-    if (!grids_fit(a)) return ADAPTRA_EINVAL;
+    if (!grids_fit(a, true)) return ADAPTRA_EINVAL;
     hipLaunchKernelGGL(k_zero_status, dim3(1), dim3(64), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_prepass, dim3(grid_for(a.C, INT32_MAX)), dim3(kBlock), 0, st, a);
@@ -985,7 +1006,7 @@ int adaptra_detail::best(const adaptra_params_t *params, const adaptra_candidate
     if (pair_div < 0 || (pair_div > 0 && (cands->n + pair_div - 1) / pair_div > scens->n)) return ADAPTRA_EINVAL;
     a.pair_div = pair_div;
     a.live_list = (int *)((char *)workspace + ws.off_live);
-    if (!grids_fit(a)) return ADAPTRA_EINVAL;
+    if (!grids_fit(a, false)) return ADAPTRA_EINVAL;
     hipLaunchKernelGGL(k_zero_status, dim3(1), dim3(64), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_prepass, dim3(grid_for(a.C, INT32_MAX)), dim3(kBlock), 0, st, a);

@@ -11,15 +11,15 @@ from oracle import seed
 
 def test_algorithm1_hand_worked_values():
     # S=4, x_max=7: avg = 6 // 3 = 2, r = 0            -> 7 5 3 1
-    assert seed.get_init_warmup_fwds(4, 7) == [7, 5, 3, 1]
+    assert seed.initial_plan(4, 7) == [7, 5, 3, 1]
     # S=4, x_max=8: avg = 7 // 3 = 2, r = 1, link 0 +1 -> 8 5 3 1
-    assert seed.get_init_warmup_fwds(4, 8) == [8, 5, 3, 1]
+    assert seed.initial_plan(4, 8) == [8, 5, 3, 1]
     # S=5, x_max=3: avg = 0, r = 2                     -> 3 2 1 1 1
-    assert seed.get_init_warmup_fwds(5, 3) == [3, 2, 1, 1, 1]
-    assert seed.get_init_warmup_fwds(1, 6) == [6]
-    assert seed.get_init_warmup_fwds(3, 1) == [1, 1, 1]
+    assert seed.initial_plan(5, 3) == [3, 2, 1, 1, 1]
+    assert seed.initial_plan(1, 6) == [6]
+    assert seed.initial_plan(3, 1) == [1, 1, 1]
     # x_max = S is plain 1F1B
-    assert seed.to_w(seed.get_init_warmup_fwds(6, 6)) == [5, 4, 3, 2, 1, 0]
+    assert seed.to_w(seed.initial_plan(6, 6)) == [5, 4, 3, 2, 1, 0]
 
 
 @pytest.mark.parametrize("S", [2, 3, 4, 5])
@@ -27,7 +27,7 @@ def test_algorithm1_maximises_the_minimum_slack(S):
     """Section 4.2: the initial plan maximises min_i Delta_i under x_0 <= x_max, x_{S-1} >= 1
     and Lemma 1; its slack is as balanced as possible; x_0 = x_max, x_{S-1} = 1."""
     for x_max in range(1, 10):
-        x = seed.get_init_warmup_fwds(S, x_max)
+        x = seed.initial_plan(S, x_max)
         d = [x[i] - x[i + 1] for i in range(S - 1)]
         assert x[0] == x_max and x[-1] == 1
         assert all(v >= 0 for v in d) and max(d) - min(d) <= 1
@@ -42,16 +42,16 @@ def test_algorithm1_maximises_the_minimum_slack(S):
 def test_algorithm2_hand_worked_values():
     # S=3, t_f=10, t_b=20 everywhere, delay 15 both ways on link 0 only, N large:
     # link 1: ceil(30/30) = 1 -> 2, x_1 = 3;  link 0: ceil((30+30)/30) = 2, x_0 = 5
-    assert seed.get_adapted_warmup_fwds(3, 100, [10] * 3, [20] * 3, [15, 0], [15, 0]) == [5, 3, 1]
+    assert seed.adapted_plan(3, 100, [10] * 3, [20] * 3, [15, 0], [15, 0]) == [5, 3, 1]
     # a slower delay: ceil((30+2*40)/30) = 4
-    assert seed.get_adapted_warmup_fwds(3, 100, [10] * 3, [20] * 3, [40, 0], [40, 0]) == [7, 3, 1]
+    assert seed.adapted_plan(3, 100, [10] * 3, [20] * 3, [40, 0], [40, 0]) == [7, 3, 1]
     # the clip N - 2S = 3 bites on link 0
-    assert seed.get_adapted_warmup_fwds(3, 9, [10] * 3, [20] * 3, [400, 0], [400, 0]) == [6, 3, 1]
+    assert seed.adapted_plan(3, 9, [10] * 3, [20] * 3, [400, 0], [400, 0]) == [6, 3, 1]
     # N - 2S = 0: no slack at all; N - 2S < 0 is floored at 0 (Lemma 1)
-    assert seed.get_adapted_warmup_fwds(4, 8, [10] * 4, [20] * 4, [5] * 3, [5] * 3) == [1, 1, 1, 1]
-    assert seed.get_adapted_warmup_fwds(4, 6, [10] * 4, [20] * 4, [5] * 3, [5] * 3) == [1, 1, 1, 1]
+    assert seed.adapted_plan(4, 8, [10] * 4, [20] * 4, [5] * 3, [5] * 3) == [1, 1, 1, 1]
+    assert seed.adapted_plan(4, 6, [10] * 4, [20] * 4, [5] * 3, [5] * 3) == [1, 1, 1, 1]
     # heterogeneous stages: link 1 ceil((8+12+6)/(20+30)) = 1 -> 2; link 0 ceil((50+70+20)/(8+12)) = 7
-    assert seed.get_adapted_warmup_fwds(3, 64, [50, 8, 20], [70, 12, 30], [10, 3], [10, 3]) == [10, 3, 1]
+    assert seed.adapted_plan(3, 64, [50, 8, 20], [70, 12, 30], [10, 3], [10, 3]) == [10, 3, 1]
 
 
 def test_algorithm2_gives_the_smallest_slack_that_satisfies_eq1():
@@ -61,7 +61,7 @@ def test_algorithm2_gives_the_smallest_slack_that_satisfies_eq1():
         N = 10 ** 6          # neither the clip N - 2S nor the cap x <= N applies
         t_f, t_b = rng.integers(1, 100, S), rng.integers(1, 200, S)
         cf, cb = rng.integers(0, 3000, S - 1), rng.integers(0, 3000, S - 1)
-        x = seed.get_adapted_warmup_fwds(S, N, t_f, t_b, cf, cb)
+        x = seed.adapted_plan(S, N, t_f, t_b, cf, cb)
         w = seed.to_w(x)
         assert x[-1] == 1 and all(x[i] - x[i + 1] >= 2 for i in range(S - 1))
         assert all(seed.absorbed(S, t_f, t_b, w, cf, cb))
@@ -81,7 +81,7 @@ def test_algorithm2_schedule_does_not_cascade_on_the_simulator(oracle):
         S = int(rng.integers(2, 7))
         t_f, t_b = rng.integers(5, 60, S), rng.integers(5, 90, S)
         cf, cb = rng.integers(0, 600, S - 1), rng.integers(0, 600, S - 1)
-        w = seed.to_w(seed.get_adapted_warmup_fwds(S, 10 ** 6, t_f, t_b, cf, cb))
+        w = seed.to_w(seed.adapted_plan(S, 10 ** 6, t_f, t_b, cf, cb))
         M0 = 3 * w[0] + 300                       # well past the transient
         a = oracle.timeline(S, M0, t_f, t_b, w, cf, cb)["makespan"]
         b = oracle.timeline(S, M0 + 25, t_f, t_b, w, cf, cb)["makespan"]

@@ -444,11 +444,11 @@ def test_analytic_seed_parity(lib, index):
     _, _, na = b.adaptra_seed(prob, 1, w_init, want_init=False, want_adapted=False, want_not_absorbed=True)
     torch.cuda.synchronize()
     w_init, w_ad, na = w_init.cpu().numpy(), w_ad.cpu().numpy(), na.cpu().numpy()
-    ref_init = seed.to_w(seed.get_init_warmup_fwds(wl.S, x_max))
+    ref_init = seed.to_w(seed.initial_plan(wl.S, x_max))
     assert list(w_init) == ref_init
     ks = range(wl.n_scen) if wl.n_scen <= 64 else range(0, wl.n_scen, 7)
     for k in ks:
-        ref = seed.to_w(seed.get_adapted_warmup_fwds(wl.S, wl.M, wl.t_f, wl.t_b, wl.c_fwd[:, k], wl.c_bwd[:, k]))
+        ref = seed.to_w(seed.adapted_plan(wl.S, wl.M, wl.t_f, wl.t_b, wl.c_fwd[:, k], wl.c_bwd[:, k]))
         assert list(w_ad[:, k]) == ref, k
         ok = seed.absorbed(wl.S, wl.t_f, wl.t_b, ref_init, wl.c_fwd[:, k], wl.c_bwd[:, k])
         assert list(na[:, k]) == [0 if v else 1 for v in ok], k
@@ -467,10 +467,10 @@ def test_analytic_seed_edge_cases(lib):
         for x_max in (1, 2, S, 3 * S + 1):
             w_init, w_ad, _ = b.adaptra_seed(prob, x_max)
             torch.cuda.synchronize()
-            assert list(w_init.cpu().numpy()) == seed.to_w(seed.get_init_warmup_fwds(S, x_max))
+            assert list(w_init.cpu().numpy()) == seed.to_w(seed.initial_plan(S, x_max))
         w_ad = w_ad.cpu().numpy()
         for k in range(K):
-            ref = seed.to_w(seed.get_adapted_warmup_fwds(S, M, wl.t_f, wl.t_b, wl.c_fwd[:, k], wl.c_bwd[:, k]))
+            ref = seed.to_w(seed.adapted_plan(S, M, wl.t_f, wl.t_b, wl.c_fwd[:, k], wl.c_bwd[:, k]))
             assert list(w_ad[:, k]) == ref
     with pytest.raises(b.AdaptraError):
         b.adaptra_seed(prob, 0)                  # x_max must be >= 1 for Algorithm 1
@@ -713,12 +713,12 @@ def test_per_scenario_stage_times_checked_and_seeded(lib, oracle):
     tfs, tbs = workloads.straggler_stage_times(71, wl, p_slow=0.4)
     prob = lib.Problem.from_workload(wl, t_f_scen=tfs, t_b_scen=tbs)
     assert lib.adaptra_check_inputs(prob) == lib.OK
-    w_cur = torch.tensor(oseed.to_w(oseed.get_init_warmup_fwds(wl.S, 12)), dtype=torch.int32, device="cuda:0")
+    w_cur = torch.tensor(oseed.to_w(oseed.initial_plan(wl.S, 12)), dtype=torch.int32, device="cuda:0")
     w_init, w_ad, na = lib.adaptra_seed(prob, 12, w_current=w_cur, want_not_absorbed=True)
     torch.cuda.synchronize()
     w_ad, na = w_ad.cpu().numpy(), na.cpu().numpy()
     for k in range(wl.n_scen):
-        x = oseed.get_adapted_warmup_fwds(wl.S, wl.M, tfs[:, k], tbs[:, k], wl.c_fwd[:, k], wl.c_bwd[:, k])
+        x = oseed.adapted_plan(wl.S, wl.M, tfs[:, k], tbs[:, k], wl.c_fwd[:, k], wl.c_bwd[:, k])
         assert list(w_ad[:, k]) == oseed.to_w(x), k
         ab = oseed.absorbed(wl.S, tfs[:, k], tbs[:, k], w_cur.cpu().numpy(), wl.c_fwd[:, k], wl.c_bwd[:, k])
         assert list(na[:, k]) == [0 if a else 1 for a in ab], k
@@ -875,7 +875,7 @@ def test_guided_search_against_exhaustive_argmin(lib, oracle, index):
     wl = workloads.config(index)
     S, M, K = wl.S, wl.M, wl.n_scen
     x_max = int(wl.mem_cap[0]) if wl.mem_cap is not None else S
-    start = np.array(oseed.to_w(oseed.get_init_warmup_fwds(S, x_max)), dtype=np.int32)
+    start = np.array(oseed.to_w(oseed.initial_plan(S, x_max)), dtype=np.int32)
     prob = lib.Problem.from_workload(wl)
     idx, bmk, _, _ = lib.adaptra_best(prob)
     w, mk, rounds, evaluated = lib.adaptra_search(prob, torch.from_numpy(start).cuda(), 1, 200)
