@@ -48,6 +48,10 @@ constexpr int kPrioForward = 2, kPrioBackward = 0;
 #ifndef ADAPTRA_WAVES32
 #define ADAPTRA_WAVES32 4
 #endif
+#ifndef ADAPTRA_DRAIN_BLOCK
+#define ADAPTRA_DRAIN_BLOCK 4
+#endif
+constexpr int kDrainBlock = ADAPTRA_DRAIN_BLOCK;   // stages per copy of the cool-down round (see the hot kernel)
 constexpr int kPrefetchStages = ADAPTRA_PD;        // ring reads run this many stages ahead of their use
 constexpr unsigned long long kNoKey = ~0ull;
 
@@ -162,6 +166,14 @@ __device__ __forceinline__ void stages_below(int limit, F &&f) {
         }
     }
 }
+// kBegin, kBegin + kStep, ... below kEnd
+template <int kBegin, int kEnd, int kStep, class F>
+__device__ __forceinline__ void stage_blocks_up(F &&f) {
+    if constexpr (kBegin < kEnd) {
+        f(StageIndex<kBegin>{});
+        stage_blocks_up<kBegin + kStep, kEnd, kStep>(f);
+    }
+}
 #define ADAPTRA_STAGE_LAMBDA(si) [&](auto si) __attribute__((always_inline))
 
 // Kernel arguments of the hot kernel, read where they are used.  The struct is the
@@ -176,10 +188,16 @@ __device__ __forceinline__ KArgsPtr kargs() {
     return p;
 }
 // A wavefront-uniform value held in a vector register on purpose: v_add_u32 with two vector
-// operands issues at twice the rate of the same add with a scalar operand on this chip (see
-// adaptra_probe.hip), so the addends of the recurrence's steady loop live in VGPRs.
+// operands can issue at twice the rate of the same add with a scalar operand on this chip (see
+// adaptra_probe.hip), so the addends of the recurrence's steady loop live in VGPRs -- where there
+// is room: at 32 stages the S registers are worth more to the cool-down phase's copies (below),
+// which spill without them (measured 41.1 against 44.0 ms on configuration 3; at 8 and 16
+// stages the vector form is 1-2 % ahead).
+// (Per-lane addends -- per-scenario stage times -- pass through the same empty statement: it
+// also keeps the compiler from re-deriving them from memory inside the loops.)
+template <int S, bool VT>
 __device__ __forceinline__ int in_vgpr(int v) {
-    asm("" : "+v"(v));
+    if constexpr (S < 32 || VT) asm("" : "+v"(v));
     return v;
 }
 __device__ __forceinline__ int clampw(int w, int M) { return w < 0 ? 0 : (w > M - 1 ? M - 1 : w); }
@@ -606,7 +624,7 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : (S >= 24 ? 5 : 
                 L[s] = kNeg;
                 x[s] = 0;
                 soff[s] = bias;   // micro-batch 0 sits in slot 0
-                add_f[s] = in_vgpr(ADAPTRA_TF(s));
+                add_f[s] = in_vgpr<S, VT>(ADAPTRA_TF(s));
             }
             L[0] = -add_f[0];
 
@@ -694,7 +712,7 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : (S >= 24 ? 5 : 
             ADAPTRA_READ_NEXT_ROUND();
             ADAPTRA_B_SWEEP();                    // B(s, 0): each after a forward
 #pragma unroll
-            for (int s = 0; s < S; ++s) add_f[s] = in_vgpr(add_f[s] + ADAPTRA_TB(s));
+            for (int s = 0; s < S; ++s) add_f[s] = in_vgpr<S, VT>(add_f[s] + ADAPTRA_TB(s));
             // steady rounds r = 1 .. M-1-W: F after B, B after F on every stage
             for (int r = M - 1 - W; r > 0; --r) {
                 stages_up<0, S>(ADAPTRA_STAGE_LAMBDA(si) {
@@ -706,8 +724,18 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : (S >= 24 ? 5 : 
                 ADAPTRA_B_SWEEP();
             }
             // cool-down rounds r = M-W .. M-1: stage s is out of forwards once
-            // w[s] + r > M-1, which holds for the stages 0 .. done-1.
-            {
+            // w[s] + r > M-1, which holds for the stages 0 .. done-1 (w is non-increasing), and
+            // `done` only grows.  The rounds are taken by one copy of the round's code per block
+            // of kDrainBlock stages: the copy for the block [D0, D1) runs while `done` lies in
+            // it.  In that copy the stages below D0 have no forward step, no test, and no ring
+            // read issued on their behalf; the stages from D1 on run the steady forward step
+            // untested; only the block's own stages are tested.  The finished stages' backward
+            // durations are added ahead of the steady backward sweep (independent adds).
+            if constexpr (VT) {
+                // per-scenario stage times: one copy of the round for all stages (the compiler
+                // fails on several -- "illegal VGPR to SGPR copy" -- when the per-lane addends
+                // change inside them); a stage that has just run out of forwards gets t_b as its
+                // addend, applied inside the backward sweep
                 int done = 0;
                 for (int r = M - W; r <= M - 1; ++r) {
                     const int done_before = done;
@@ -718,17 +746,6 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : (S >= 24 ? 5 : 
                         ADAPTRA_READ_AHEAD(s);
                     });
                     ADAPTRA_READ_NEXT_ROUND();
-                    if constexpr (!VT) {
-                        // The stages out of forwards run B after B: their backward duration is
-                        // added first (independent adds, the sweep over them ends at `done`),
-                        // then the backward sweep is the steady one, without a test per stage.
-                        stages_below<0, S>(done, ADAPTRA_STAGE_LAMBDA(si) {
-                            constexpr int s = decltype(si)::value;
-                            L[s] += ADAPTRA_TB(s);
-                        });
-                        ADAPTRA_B_SWEEP();
-                        continue;
-                    }
                     int carry = 0;
                     __builtin_amdgcn_s_setprio(kPrioBackward);
                     stages_down<S - 1, 0>(ADAPTRA_STAGE_LAMBDA(si) {
@@ -743,6 +760,39 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : (S >= 24 ? 5 : 
                     });
                     __builtin_amdgcn_s_setprio(kPrioForward);
                 }
+            } else {
+                int done = 0, r = M - W;
+                stage_blocks_up<0, S, kDrainBlock>(ADAPTRA_STAGE_LAMBDA(bi) {
+                    constexpr int D0 = decltype(bi)::value;
+                    constexpr int D1 = D0 + kDrainBlock < S ? D0 + kDrainBlock : S;
+                    for (; r <= M - 1; ++r) {
+                        while (done < S && __builtin_amdgcn_readlane(wq_lanes, done) + r > M - 1) ++done;
+                        done = uni(done);      // said again for the compiler, which otherwise loses it across the copies
+                        if (D1 < S && done >= D1) break;      // the next block's copy takes this round
+                        stages_up<0, S>(ADAPTRA_STAGE_LAMBDA(si) {
+                            constexpr int s = decltype(si)::value;
+                            if constexpr (s >= D1) {
+                                ADAPTRA_F_OP(s, add_f[s]);
+                            } else if constexpr (s >= D0) {
+                                if (s >= done) ADAPTRA_F_OP(s, add_f[s]);
+                            }
+                            if constexpr (s + kPD >= D0) ADAPTRA_READ_AHEAD(s);
+                        });
+                        stages_up<(D0 > 1 ? D0 : 1), kPD + 1>(ADAPTRA_STAGE_LAMBDA(sj) {      // next round's first reads
+                            constexpr int j = decltype(sj)::value;
+                            x[j] = *(lds_int *)(ring + soff[j]);
+                        });
+                        stages_up<0, D0>(ADAPTRA_STAGE_LAMBDA(si) {
+                            constexpr int s = decltype(si)::value;
+                            L[s] += ADAPTRA_TB(s);
+                        });
+                        stages_up<D0, D1>(ADAPTRA_STAGE_LAMBDA(si) {
+                            constexpr int s = decltype(si)::value;
+                            if (s < done) L[s] += ADAPTRA_TB(s);
+                        });
+                        ADAPTRA_B_SWEEP();
+                    }
+                });
             }
 #undef ADAPTRA_F_OP
 #undef ADAPTRA_READ_AHEAD
