@@ -170,7 +170,10 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
         const int s = i >> 2, ty = i & 3;
         dur[i] = ty == 0 ? a.t_f[s] : (ty == 1 ? a.t_b[s] : (ty == 2 ? a.t_w[s] : 0));
     }
-    // queue entry e of this lane at queue[e * nt]
+    // queue entry e of this lane at queue[e * nt].  Entry numbers stay below 2 S N <= 2^22 and nt
+    // below 2^20, their product below the 2^29 ints of the queue memory (threads_for): both
+    // products of the address are 24-bit multiplies (full rate; a 32 x 32 -> 64-bit one runs at a
+    // quarter of it, and two of those per queue access were a fifth of a step's vector cycles)
     int *const queue = QLDS ? delay + 2 * S + threadIdx.x : a.scratch + ((long long)blockIdx.x * kZbBlock + threadIdx.x);
     const unsigned nt = QLDS ? (unsigned)kZbBlock : a.threads;
     // A unit of work = one scenario x 64 consecutive candidates (the last chunk may be short:
@@ -284,7 +287,7 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
                 const bool own = ty == 0 ? first : last;
                 const int posted = ty == 0 ? (first ? N : prev.nF()) : (last ? cur.nF() : next.nB());
                 unsigned head = ~0u;
-                if (m + 1 < posted) head = own ? 0u : (unsigned)queue[(unsigned long long)(unsigned)((i * 2 + ty) * N + m + 1) * nt];
+                if (m + 1 < posted) head = own ? 0u : (unsigned)queue[__umul24(__umul24((unsigned)(i * 2 + ty), (unsigned)N) + (unsigned)(m + 1), nt)];
                 if (ty == 0) headF = head; else headB = head;
             }
             if (is_empty(headF)) headF = empty_head(fin);       // busy until fin from now on
@@ -302,7 +305,7 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
                     sj[ty == 0 ? Cur::kHeadF : Cur::kHeadB] = r;
                     act[j * 64] = next_action<PHASE>((int)~slot, cur_j, headF_j, headB_j);
                 } else {
-                    queue[(unsigned long long)(unsigned)((j * 2 + ty) * N + m) * nt] = r;
+                    queue[__umul24(__umul24((unsigned)(j * 2 + ty), (unsigned)N) + (unsigned)m, nt)] = r;
                 }
             }
         }
