@@ -54,6 +54,7 @@ using namespace adaptra_detail;
 // (Algorithm 1, x_max).  Also packs w' into bytes for the hot kernel and bins the
 // candidate by the ring depth it needs, w'[0] + 1 slots.
 __global__ __launch_bounds__(kBlock) void k_prepass(KArgs a) {
+    if (a.gate && *a.gate == 0) return;
     __shared__ int class_count[kNumRingClasses + 1];
     if (threadIdx.x <= kNumRingClasses) class_count[threadIdx.x] = 0;
     if (blockIdx.x == 0 && threadIdx.x < 128) {             // stage times padded with zeros (candidate-lanes kernel)
@@ -181,6 +182,7 @@ __global__ __launch_bounds__(kBlock) void k_sens_epilogue(KArgs a) {
 }
 
 __global__ __launch_bounds__(kBlock) void k_best_init(KArgs a) {
+    if (a.gate && *a.gate == 0) return;
     const long long n = a.K + (a.hist ? (long long)a.S * a.hist_bins : 0);
     const long long stride = (long long)gridDim.x * kBlock;
     for (long long i = (long long)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) {
@@ -294,6 +296,7 @@ __global__ __launch_bounds__(kBlock) void k_best_from_eval(KArgs a) {
 // key = makespan << 32 | candidate: the minimum key is the smallest makespan, ties to the
 // lowest index.  Bubbles of the winner: makespan - M (t_f + t_b) per stage.
 __global__ __launch_bounds__(kBlock) void k_best_finalize(KArgs a) {
+    if (a.gate && *a.gate == 0) return;
     const long long k = (long long)blockIdx.x * kBlock + threadIdx.x;
     if (k >= a.K) return;
     const unsigned long long key = a.keys[k];
@@ -317,6 +320,7 @@ __global__ __launch_bounds__(kBlock) void k_best_finalize(KArgs a) {
 //   last[S], w'[S], fwd[M] (finish time of micro-batch m's latest forward).
 template <bool BEST>
 __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
+    if (a.gate && *a.gate == 0) return;
     const int S = a.S, M = a.M;
     const long long NT = (long long)gridDim.x * kBlock;
     const long long tid = (long long)blockIdx.x * kBlock + threadIdx.x;
@@ -437,6 +441,7 @@ __global__ __launch_bounds__(kBlock) void k_check_inputs(KArgs a) {
 }
 
 __global__ void k_zero_status(KArgs a) {
+    if (a.gate && *a.gate == 0) return;
     a.status[threadIdx.x] = 0;      // launched with 64 threads: all of status
 }
 
@@ -645,6 +650,7 @@ void fill_args(KArgs *a, const adaptra_params_t *p, const adaptra_candidates_t *
     a->keys = (unsigned long long *)(base + ws.off_keys);
     a->status = (int *)(base + ws.off_status);
     a->live_list = nullptr;                // adaptra_best sets it: only the search walks the list
+    a->gate = nullptr;
     a->tpad = (int *)(base + ws.off_tpad);
     a->scratch = (int *)(base + ws.off_scratch);
     a->mk_t = (int *)(base + ws.off_mkt);
@@ -985,7 +991,7 @@ int adaptra_detail::best(const adaptra_params_t *params, const adaptra_candidate
                          const adaptra_scenarios_t *scens, int pair_div,
                          int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
                          uint64_t *out_hist,
-                         void *workspace, size_t workspace_bytes, void *stream, bool small_scratch) {
+                         void *workspace, size_t workspace_bytes, void *stream, bool small_scratch, const int *gate) {
     Workspace ws;
     int rc = validate_common(params, cands, scens, workspace, workspace_bytes, &ws, false, small_scratch);
     if (rc) return rc;
@@ -1006,6 +1012,7 @@ int adaptra_detail::best(const adaptra_params_t *params, const adaptra_candidate
     if (pair_div < 0 || (pair_div > 0 && (cands->n + pair_div - 1) / pair_div > scens->n)) return ADAPTRA_EINVAL;
     a.pair_div = pair_div;
     a.live_list = (int *)((char *)workspace + ws.off_live);
+    a.gate = gate;
     if (!grids_fit(a, false)) return ADAPTRA_EINVAL;
     hipLaunchKernelGGL(k_zero_status, dim3(1), dim3(64), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();

@@ -18,10 +18,13 @@ int hip_fail(hipError_t e);
 
 // adaptra_best with two more arguments: pair_div > 0 evaluates candidate c under scenario
 // c / pair_div only (0: every candidate under every scenario); small_scratch plans the
-// workspace with the general kernel's share held to 16 MiB (adaptra_best_static).
+// workspace with the general kernel's share held to 16 MiB (adaptra_best_static); gate, a
+// DEVICE int, makes every kernel of the call exit at once when it is 0 at that time (the guided
+// search enqueues several rounds between two host read-backs).
 int best(const adaptra_params_t *params, const adaptra_candidates_t *cands, const adaptra_scenarios_t *scens,
          int pair_div, int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
-         uint64_t *out_hist, void *workspace, size_t workspace_bytes, void *stream, bool small_scratch = false);
+         uint64_t *out_hist, void *workspace, size_t workspace_bytes, void *stream, bool small_scratch = false,
+         const int *gate = nullptr);
 
 // Workspace sections start on 256-byte boundaries.
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }

@@ -18,6 +18,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "adaptra.h"
 #include "adaptra_internal.h"
 
@@ -79,6 +81,8 @@ struct KArgs {
     int n_ktiles;
     int *status;                           // [0..3] input check, [16..32] candidates per ring class, [48] entries of live_list
     int *live_list;                        // search only: the feasible candidates an on-chip kernel can take, in any order
+    const int *gate;                       // guided search only: when set and *gate == 0 (nothing moved in the round
+                                           // before) every kernel of the call exits at once
     int *mk_t;                             // eval: makespan, candidate-major [C][K]
     int *tpad;                             // t_f at [0..63], t_b at [64..127], zero beyond stage S-1
     int kernel_mode;                       // host side only: the kernel selection this call runs under
@@ -281,6 +285,7 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 48 || (VT && S >= 16) ? 2 : (
     // The arguments are read through kargs() where they are needed (see there): kept in SGPRs
     // across the round loop they would crowd out the loop's own scalars.
     extern __shared__ int lds[];
+    if (kargs()->gate && *kargs()->gate == 0) return;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int D = kargs()->ring_slots, M = kargs()->M;
     int *const ring = lds + wv * D * 64 + lane;          // slot i of this lane at ring[i * 64]
@@ -535,6 +540,7 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : (S >= 24 ? 5 : 
     // The arguments are read through kargs() where they are needed (see there), never
     // through the by-value parameter.
     extern __shared__ int lds[];
+    if (kargs()->gate && *kargs()->gate == 0) return;
     constexpr int kPD = S - 1 < kPrefetchStages ? S - 1 : kPrefetchStages;
     const int lane = threadIdx.x & 63;
     const int wv = uni(threadIdx.x >> 6);
@@ -898,8 +904,33 @@ inline int ring_launches(int w_bound, int M, ClassRange out[5]) {
     return 5;
 }
 
+// Dynamic LDS above the default limit of 48 KiB has to be allowed per kernel; `allowed` (one
+// per kernel instantiation and device) remembers the largest size already granted.
+constexpr int kLdsDevices = 64;
+struct LdsAllowed {
+    std::atomic<size_t> bytes[kLdsDevices];
+};
+inline bool lds_needs_grant(size_t lds, const LdsAllowed &allowed, int *dev) {
+    if (lds <= 48 * 1024) return false;
+    if (hipGetDevice(dev) != hipSuccess) *dev = -1;
+    return !(*dev >= 0 && *dev < kLdsDevices && allowed.bytes[*dev].load(std::memory_order_relaxed) >= lds);
+}
+inline void lds_granted(size_t lds, LdsAllowed *allowed, int dev) {
+    if (dev >= 0 && dev < kLdsDevices) allowed->bytes[dev].store(lds, std::memory_order_relaxed);
+}
+#define ADAPTRA_ALLOW_LDS(kernel, lds)                                                                        \
+    do {                                                                                                      \
+        int dev_;                                                                                             \
+        if (lds_needs_grant((lds), lds_allowed, &dev_)) {                                                     \
+            hipError_t e_ = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(lds)); \
+            if (e_ != hipSuccess) return hip_fail(e_);                                                        \
+            lds_granted((lds), &lds_allowed, dev_);                                                           \
+        }                                                                                                     \
+    } while (0)
+
 template <int S, bool BEST, bool VT>
 int launch_scen_lanes_one(KArgs a, int w_bound, hipStream_t st) {
+    static LdsAllowed lds_allowed;
     const long long tasks = a.n_chunks * a.n_ktiles;
     const long long blocks = (tasks + kWavesPerBlock - 1) / kWavesPerBlock;      // grids_fit() has bounded it
     ClassRange ranges[5];
@@ -910,11 +941,9 @@ int launch_scen_lanes_one(KArgs a, int w_bound, hipStream_t st) {
         a.ring_slots = 8 * (a.cls_hi + 1);
         size_t lds = (size_t)kWavesPerBlock * a.ring_slots * 256;
         if (BEST && a.hist && a.hist_in_lds) lds += (size_t)a.S * a.hist_bins * 4;
-        if (lds > 48 * 1024) {      // above the default dynamic-LDS limit: raise it for this kernel
-            hipError_t e = hipFuncSetAttribute((const void *)k_resolve_scen_lanes<S, BEST, VT>,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return hip_fail(e);
-        }
+        // above the default dynamic-LDS limit: raise it for this kernel, once per size asked for
+        // (the call costs tens of microseconds, the guided search launches hundreds of times)
+        ADAPTRA_ALLOW_LDS((k_resolve_scen_lanes<S, BEST, VT>), lds);
         hipLaunchKernelGGL((k_resolve_scen_lanes<S, BEST, VT>), dim3((unsigned)blocks), dim3(kBlock), lds, st, a);
         ADAPTRA_CHECK_LAUNCH();
     }
@@ -923,6 +952,7 @@ int launch_scen_lanes_one(KArgs a, int w_bound, hipStream_t st) {
 
 template <int S, bool BEST, bool VT, bool AHEAD>
 int launch_cand_lanes_one(KArgs a, int w_bound, hipStream_t st) {
+    static LdsAllowed lds_allowed;
     const long long ntiles = (a.pair_div ? 1 : a.K) * ((a.C + 63) / 64);
     long long blocks = (ntiles + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 256 * 32) blocks = 256 * 32;            // the tiles are walked in a loop
@@ -933,11 +963,7 @@ int launch_cand_lanes_one(KArgs a, int w_bound, hipStream_t st) {
         a.cls_hi = ranges[i].hi;
         a.ring_slots = 8 * (a.cls_hi + 1);
         const size_t lds = (size_t)kWavesPerBlock * a.ring_slots * 256;
-        if (lds > 48 * 1024) {
-            hipError_t e = hipFuncSetAttribute((const void *)k_resolve_cand_lanes<S, BEST, VT, AHEAD>,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return hip_fail(e);
-        }
+        ADAPTRA_ALLOW_LDS((k_resolve_cand_lanes<S, BEST, VT, AHEAD>), lds);
         hipLaunchKernelGGL((k_resolve_cand_lanes<S, BEST, VT, AHEAD>), dim3((unsigned)blocks), dim3(kBlock), lds, st, a);
         ADAPTRA_CHECK_LAUNCH();
     }

@@ -11,6 +11,10 @@
 //   k_search_pool      pool[s][k * (moves + 1) + j] = point of scenario k after move j, clamped
 //   k_search_advance   a scenario adopts its best pool entry iff strictly better
 //
+// The host only needs to know when nothing moves any more, so it enqueues kRoundsPerCheck rounds
+// at a time and reads the per-round move counts back once per batch: every kernel of a round
+// (these and the evaluation's) exits at once when the round before it moved nothing.
+//
 // A scenario that did not move in a round is at rest for good: its pool, hence its best entry,
 // would be the same in every later round.  Its pool entries are then written as a vector that
 // Lemma 1 rules out (w_0 < w_1), which the evaluation flags in its pre-pass and never resolves,
@@ -32,12 +36,17 @@ struct SearchArgs {
     long long K, C;               // scenarios; pool entries = K * (n_moves + 1)
     const int *w_start;
     int *cur_w, *cur_mk;          // [S][K], [K]: the outputs double as the state
-    int *counters;                // [0] scenarios that moved in this round, [1] largest w[0] any point has had
+    int *counters;                // [1] largest w[0] any point has had, [kMovedAt + i] scenarios that moved in round i of the batch
+    const int *gate;              // the round before's move count, or null (first round of a batch): 0 = skip this round
+    int *moved;                   // this round's move count
     int *active;                  // [K] 1 while the scenario is still moving
     int skip_resting;             // resting scenarios can be marked (needs a stage 1 and M > 1)
     int *pool;                    // [S][C]
     const int *best_idx, *best_mk;
 };
+
+constexpr int kRoundsPerCheck = 8;      // rounds enqueued between two host read-backs
+constexpr int kMovedAt = 8;             // counters[kMovedAt .. kMovedAt + kRoundsPerCheck)
 
 __device__ __forceinline__ int clamp_w(int w, int M) { return w < 0 ? 0 : (w > M - 1 ? M - 1 : w); }
 
@@ -61,13 +70,17 @@ __device__ __forceinline__ void decode_move(int nb, int S, int j, int *lo, int *
     *lo = a; *hi = a + r;
 }
 
+__global__ void k_search_clear_moved(SearchArgs a) {
+    if (threadIdx.x < kRoundsPerCheck) a.counters[kMovedAt + threadIdx.x] = 0;
+}
+
 __global__ void k_search_pool(SearchArgs a) {
+    if (a.gate && *a.gate == 0) return;
     const long long c = (long long)blockIdx.x * kThreadsPerBlock + threadIdx.x;
     if (c >= a.C) return;
     const int per_point = a.n_moves + 1;
     const long long k = c / per_point;
     const int j = (int)(c % per_point);
-    if (c == 0) a.counters[0] = 0;        // nobody has moved yet in this round
     if (a.skip_resting && !a.active[k]) {               // at rest: an entry that is never resolved
         for (int s = 0; s < a.S; ++s) a.pool[(long long)s * a.C + c] = s == 1 ? 1 : 0;
         return;
@@ -81,13 +94,14 @@ __global__ void k_search_pool(SearchArgs a) {
 }
 
 __global__ void k_search_advance(SearchArgs a) {
+    if (a.gate && *a.gate == 0) return;
     const long long k = (long long)blockIdx.x * kThreadsPerBlock + threadIdx.x;
     if (k >= a.K) return;
     const int bi = a.best_idx[k];
     if (bi >= 0 && a.best_mk[k] < a.cur_mk[k]) {
         for (int s = 0; s < a.S; ++s) a.cur_w[(long long)s * a.K + k] = a.pool[(long long)s * a.C + bi];
         a.cur_mk[k] = a.best_mk[k];
-        atomicAdd(&a.counters[0], 1);
+        atomicAdd(a.moved, 1);
         atomicMax(&a.counters[1], a.cur_w[k]);           // w is non-increasing over the stages of a feasible point
     } else {
         a.active[k] = 0;
@@ -178,29 +192,39 @@ int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *sc
     }
     int rounds = 0;
     long long evaluated = 0, still_moving = a.K;
-    for (;;) {
-        ++rounds;
-        // step 1: every scenario's point and its neighbours
-        hipLaunchKernelGGL(k_search_pool, dim3(blocks_for(a.C, INT32_MAX)), dim3(kThreadsPerBlock), 0, st, a);
+    for (bool settled = false; !settled && rounds < max_iters;) {
+        const int n = max_iters - rounds < kRoundsPerCheck ? max_iters - rounds : kRoundsPerCheck;
+        hipLaunchKernelGGL(k_search_clear_moved, dim3(1), dim3(64), 0, st, a);
         ADAPTRA_CHECK_LAUNCH();
-        // step 2: each pool entry under its own scenario, and the best entry per scenario
-        const int w_bound = w_top + 1 > a.M - 1 ? a.M - 1 : w_top + 1;
-        const adaptra_candidates_t pool{a.C, a.pool, w_bound};
-        const long long live = (a.skip_resting ? still_moving : a.K) * (pl.n_moves + 1);
-        int rc = adaptra_detail::best(&bp, &pool, scens, pl.n_moves + 1, best_idx, best_mk, nullptr, nullptr,
-                                      base + pl.off_best_ws, pl.best_ws_bytes, stream);
-        if (rc) return rc;
-        evaluated += live;
-        // step 3: move
-        hipLaunchKernelGGL(k_search_advance, dim3(kblocks), dim3(kThreadsPerBlock), 0, st, a);
-        ADAPTRA_CHECK_LAUNCH();
-        int back[2] = {0, 0};
+        for (int i = 0; i < n; ++i) {
+            a.gate = i == 0 ? nullptr : a.counters + kMovedAt + i - 1;
+            a.moved = a.counters + kMovedAt + i;
+            // step 1: every scenario's point and its neighbours
+            hipLaunchKernelGGL(k_search_pool, dim3(blocks_for(a.C, INT32_MAX)), dim3(kThreadsPerBlock), 0, st, a);
+            ADAPTRA_CHECK_LAUNCH();
+            // step 2: each pool entry under its own scenario, and the best entry per scenario.  No w
+            // in the pool exceeds the largest w[0] any point had at the last read-back by more than
+            // one per round since.
+            const long long top = (long long)w_top + i + 1;
+            const adaptra_candidates_t pool{a.C, a.pool, (int32_t)(top > a.M - 1 ? a.M - 1 : top)};
+            int rc = adaptra_detail::best(&bp, &pool, scens, pl.n_moves + 1, best_idx, best_mk, nullptr, nullptr,
+                                          base + pl.off_best_ws, pl.best_ws_bytes, stream, false, a.gate);
+            if (rc) return rc;
+            // step 3: move
+            hipLaunchKernelGGL(k_search_advance, dim3(kblocks), dim3(kThreadsPerBlock), 0, st, a);
+            ADAPTRA_CHECK_LAUNCH();
+        }
+        int back[kMovedAt + kRoundsPerCheck] = {};
         hipError_t e = hipMemcpyAsync(back, a.counters, sizeof(back), hipMemcpyDeviceToHost, st);
         if (e != hipSuccess) return hip_fail(e);
         if ((e = hipStreamSynchronize(st)) != hipSuccess) return hip_fail(e);
         w_top = back[1];
-        still_moving = back[0];
-        if (back[0] == 0 || rounds >= max_iters) break;
+        for (int i = 0; i < n && !settled; ++i) {         // rounds behind one that moved nothing were skipped
+            ++rounds;
+            evaluated += (a.skip_resting ? still_moving : a.K) * (pl.n_moves + 1);
+            still_moving = back[kMovedAt + i];
+            settled = still_moving == 0;
+        }
     }
     if (out_rounds) *out_rounds = rounds;
     if (out_evaluated) *out_evaluated = evaluated;
