@@ -68,24 +68,35 @@ __global__ __launch_bounds__(kBlock) void k_prepass(KArgs a) {
     const int S = a.S, M = a.M;
     bool dead = false, mem = false;
     int prev = INT32_MAX, w0 = 0;
-    // One pass over the stages, four at a time: the Lemma 1 and memory tests, and w as bytes for
-    // the ring kernels (wq_stride is a multiple of 4; bytes past S are the padding stages of the
-    // kernel size the pipeline runs in, w = 0).  The bytes of a candidate no ring kernel takes
-    // are never read.
+    // One pass over the stages, sixteen at a time (all their loads issued before the first is
+    // used): the Lemma 1 and memory tests, and w as bytes for the ring kernels (wq_stride is a
+    // multiple of 4; bytes past S are the padding stages of the kernel size the pipeline runs
+    // in, w = 0).  The bytes of a candidate no ring kernel takes are never read.
+    const WSource src = w_source(a, c);
     unsigned *const q = (unsigned *)(a.cand_wq + c * a.wq_stride);
-    for (int s4 = 0; s4 < a.wq_stride; s4 += 4) {
-        unsigned packed = 0;
-        for (int j = 0; j < 4; ++j) {
-            const int s = s4 + j;
-            if (s >= S) break;
-            const int ws = clampw(a.w[(long long)s * a.C + c], M);
-            if (s == 0) w0 = ws;
-            if (prev < ws) dead = true;
-            if (a.mem_cap && ws + 1 > a.mem_cap[s]) mem = true;
-            prev = ws;
-            packed |= (unsigned)(ws & 0xff) << (8 * j);
+    for (int s0 = 0; s0 < a.wq_stride; s0 += 16) {
+        int wv[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) wv[j] = s0 + j < S ? clampw(w_at(src, s0 + j), M) : 0;
+        unsigned packed[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int s = s0 + j, ws = wv[j];
+            if (s < S) {
+                if (s == 0) w0 = ws;
+                if (prev < ws) dead = true;
+                if (a.mem_cap && ws + 1 > a.mem_cap[s]) mem = true;
+                prev = ws;
+            }
+            packed[j / 4] |= (unsigned)(ws & 0xff) << (8 * (j % 4));
         }
-        q[s4 / 4] = packed;
+        if (s0 + 16 <= a.wq_stride && (a.wq_stride & 15) == 0) {
+            *(uint4 *)(q + s0 / 4) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+        } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (s0 + 4 * v < a.wq_stride) q[s0 / 4 + v] = packed[v];
+        }
     }
     int flag = (dead ? ADAPTRA_FLAG_DEADLOCK : 0) | (mem ? ADAPTRA_FLAG_MEMCAP : 0);
     if (flag == 0) flag = ADAPTRA_FLAG_FEASIBLE;
@@ -351,8 +362,9 @@ __global__ __launch_bounds__(kBlock) void k_resolve_general(KArgs a) {
         }
         unsigned long long key = kNoKey;
         if (run) {
+            const WSource src = w_source(a, c);
             for (int s = 0; s < S; ++s) {
-                wl[s * NT] = clampw(a.w[(long long)s * a.C + c], M);
+                wl[s * NT] = clampw(w_at(src, s), M);
                 last[s * NT] = 0;
             }
             const int w0 = wl[0];
@@ -624,10 +636,10 @@ int grid_for(long long n, long long cap = 1 << 20) {
 
 int validate_common(const adaptra_params_t *p, const adaptra_candidates_t *cd,
                     const adaptra_scenarios_t *sc, void *workspace, size_t workspace_bytes,
-                    Workspace *ws, bool with_mkt = true, bool small = false) {
+                    Workspace *ws, bool with_mkt = true, bool small = false, bool derived = false) {
     if (!p || !cd || !sc) return ADAPTRA_EINVAL;
     if (!plan_workspace(p->S, p->M, cd->n, sc->n, ws, with_mkt, small)) return ADAPTRA_EINVAL;
-    if (!p->t_f || !p->t_b || !cd->w) return ADAPTRA_EINVAL;
+    if (!p->t_f || !p->t_b || (!cd->w && !derived)) return ADAPTRA_EINVAL;
     if (p->S > 1 && (!sc->c_fwd || !sc->c_bwd)) return ADAPTRA_EINVAL;
     if ((sc->t_f == nullptr) != (sc->t_b == nullptr)) return ADAPTRA_EINVAL;
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws->total) return ADAPTRA_EWORKSPACE;
@@ -991,10 +1003,12 @@ int adaptra_detail::best(const adaptra_params_t *params, const adaptra_candidate
                          const adaptra_scenarios_t *scens, int pair_div,
                          int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
                          uint64_t *out_hist,
-                         void *workspace, size_t workspace_bytes, void *stream, bool small_scratch, const int *gate) {
+                         void *workspace, size_t workspace_bytes, void *stream, bool small_scratch, const int *gate,
+                         const Neighbourhood *moves) {
     Workspace ws;
-    int rc = validate_common(params, cands, scens, workspace, workspace_bytes, &ws, false, small_scratch);
+    int rc = validate_common(params, cands, scens, workspace, workspace_bytes, &ws, false, small_scratch, moves != nullptr);
     if (rc) return rc;
+    if (moves && (!moves->point || moves->per_point < 1 || moves->K * moves->per_point < cands->n)) return ADAPTRA_EINVAL;
     if (!out_best_idx || !out_best_makespan) return ADAPTRA_EINVAL;
     if (params->hist_bins < 0 || params->hist_bins > 65536) return ADAPTRA_EINVAL;
     if (params->hist_bins > 0 && (!out_hist || params->hist_shift < 0 || params->hist_shift > 30))
@@ -1013,6 +1027,7 @@ int adaptra_detail::best(const adaptra_params_t *params, const adaptra_candidate
     a.pair_div = pair_div;
     a.live_list = (int *)((char *)workspace + ws.off_live);
     a.gate = gate;
+    if (moves) a.moves = *moves;
     if (!grids_fit(a, false)) return ADAPTRA_EINVAL;
     hipLaunchKernelGGL(k_zero_status, dim3(1), dim3(64), 0, st, a);
     ADAPTRA_LAUNCH_CHECK();

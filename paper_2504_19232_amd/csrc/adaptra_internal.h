@@ -16,15 +16,28 @@ constexpr int kThreadsPerBlock = 256;
 // Records the hipError_t for adaptra_last_hip_error and returns ADAPTRA_EHIP.
 int hip_fail(hipError_t e);
 
-// adaptra_best with two more arguments: pair_div > 0 evaluates candidate c under scenario
+// Candidates that are not stored but derived: candidate c is the point of scenario
+// c / per_point after move c % per_point of the guided search's neighbourhood (see
+// neighbourhood_move), or -- for a scenario whose `active` word is 0 -- a vector that Lemma 1
+// rules out, which no kernel ever resolves.  point == nullptr: the candidates are an array.
+struct Neighbourhood {
+    const int *point;             // DEVICE [S][K]
+    const int *active;            // DEVICE [K] or null (every scenario active)
+    long long K;
+    int per_point;                // moves + 1
+    int nb;                       // 0: prefix ranges, 1: all ranges
+};
+
+// adaptra_best with more arguments: pair_div > 0 evaluates candidate c under scenario
 // c / pair_div only (0: every candidate under every scenario); small_scratch plans the
 // workspace with the general kernel's share held to 16 MiB (adaptra_best_static); gate, a
 // DEVICE int, makes every kernel of the call exit at once when it is 0 at that time (the guided
-// search enqueues several rounds between two host read-backs).
+// search enqueues several rounds between two host read-backs); moves, when set, replaces
+// cands->w (which is then not read and may be null).
 int best(const adaptra_params_t *params, const adaptra_candidates_t *cands, const adaptra_scenarios_t *scens,
          int pair_div, int32_t *out_best_idx, int32_t *out_best_makespan, int32_t *out_best_bubble,
          uint64_t *out_hist, void *workspace, size_t workspace_bytes, void *stream, bool small_scratch = false,
-         const int *gate = nullptr);
+         const int *gate = nullptr, const Neighbourhood *moves = nullptr);
 
 // Workspace sections start on 256-byte boundaries.
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }

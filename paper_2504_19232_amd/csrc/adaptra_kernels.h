@@ -83,6 +83,7 @@ struct KArgs {
     int *live_list;                        // search only: the feasible candidates an on-chip kernel can take, in any order
     const int *gate;                       // guided search only: when set and *gate == 0 (nothing moved in the round
                                            // before) every kernel of the call exits at once
+    Neighbourhood moves;                   // guided search only: moves.point set = the candidates are derived, `w` is not read
     int *mk_t;                             // eval: makespan, candidate-major [C][K]
     int *tpad;                             // t_f at [0..63], t_b at [64..127], zero beyond stage S-1
     int kernel_mode;                       // host side only: the kernel selection this call runs under
@@ -90,6 +91,46 @@ struct KArgs {
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ int imax(int a, int b) { return a > b ? a : b; }
+
+// Move j of the guided search's neighbourhood: j = 0 keeps the point; otherwise (j - 1) / 2
+// numbers the stage range [lo, hi] and the parity of j - 1 picks -1 (even) or +1 (odd).
+__device__ __forceinline__ void neighbourhood_move(int nb, int S, int j, int *lo, int *hi, int *sign) {
+    if (j == 0) { *lo = 0; *hi = -1; *sign = 0; return; }
+    int r = (j - 1) >> 1;
+    *sign = ((j - 1) & 1) ? 1 : -1;
+    if (nb == 0) { *lo = 0; *hi = r; return; }
+    int a = 0;
+    while (r >= S - a) { r -= S - a; ++a; }      // ranges are numbered a = 0.., b = a..S-1
+    *lo = a; *hi = a + r;
+}
+// Where a candidate's warm-up vector comes from: w[s] = base[s * stride] + (lo <= s <= hi ?
+// sign : 0), not yet clamped -- an array column, or a scenario's point and a move.
+struct WSource {
+    const int *base;
+    long long stride;
+    int lo, hi, sign;
+    bool rest;                             // the scenario is at rest: w = (0, 1, 0, ...), which Lemma 1 rules out
+};
+__device__ __forceinline__ WSource w_source(const KArgs &a, long long c) {
+    WSource src;
+    if (a.moves.point) {
+        const long long k = c / a.moves.per_point;
+        src.base = a.moves.point + k;
+        src.stride = a.moves.K;
+        src.rest = a.moves.active && !a.moves.active[k];
+        neighbourhood_move(a.moves.nb, a.S, (int)(c % a.moves.per_point), &src.lo, &src.hi, &src.sign);
+    } else {
+        src.base = a.w + c;
+        src.stride = a.C;
+        src.lo = 0; src.hi = -1; src.sign = 0;
+        src.rest = false;
+    }
+    return src;
+}
+__device__ __forceinline__ int w_at(const WSource &src, int s) {
+    if (src.rest) return s == 1;
+    return src.base[(long long)s * src.stride] + (s >= src.lo && s <= src.hi ? src.sign : 0);
+}
 // One count into hist[bin] for every lane that calls (the callers' lanes are the scenarios of
 // one candidate, whose bubbles mostly fall into one or two bins: as single atomics those would
 // queue up on one address).  The lanes sharing the first lane's bin are counted with one

@@ -5,25 +5,31 @@
 // descends on its own; the work of a round is one batched evaluation of the analytical model
 // (Section 3.1) over all scenarios' neighbourhoods at once -- the search of adaptra_best in
 // its paired form, candidate c under scenario c / (moves + 1) -- so the kernels here only
-// build the pool and move the points.
+// set up and move the points.
 //
 //   k_search_init      every scenario's point = w_start clamped, makespan = INT32_MAX
-//   k_search_pool      pool[s][k * (moves + 1) + j] = point of scenario k after move j, clamped
 //   k_search_advance   a scenario adopts its best pool entry iff strictly better
+//
+// The pool -- entry k * (moves + 1) + j = the point of scenario k after move j, clamped -- is
+// never written out: the evaluation's pre-pass derives each entry from the points (S x K ints,
+// cached) where it would otherwise read the candidate array, and k_search_advance derives the
+// winning entry once more.  Stored, the pool of a round was S x K x (moves + 1) ints written
+// and read back (138 MB each way at 32 stages and 1024 scenarios).
 //
 // The host only needs to know when nothing moves any more, so it enqueues kRoundsPerCheck rounds
 // at a time and reads the per-round move counts back once per batch: every kernel of a round
-// (these and the evaluation's) exits at once when the round before it moved nothing.
+// (this file's and the evaluation's) exits at once when the round before it moved nothing.
 //
 // A scenario that did not move in a round is at rest for good: its pool, hence its best entry,
-// would be the same in every later round.  Its pool entries are then written as a vector that
-// Lemma 1 rules out (w_0 < w_1), which the evaluation flags in its pre-pass and never resolves,
-// so the rounds get cheaper as the scenarios settle.
+// would be the same in every later round.  Its pool entries then read as a vector that Lemma 1
+// rules out (w_0 < w_1), which the evaluation flags in its pre-pass and never resolves, so the
+// rounds get cheaper as the scenarios settle.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include "adaptra.h"
 #include "adaptra_internal.h"
+#include "adaptra_kernels.h"
 
 namespace {
 
@@ -40,8 +46,6 @@ struct SearchArgs {
     const int *gate;              // the round before's move count, or null (first round of a batch): 0 = skip this round
     int *moved;                   // this round's move count
     int *active;                  // [K] 1 while the scenario is still moving
-    int skip_resting;             // resting scenarios can be marked (needs a stage 1 and M > 1)
-    int *pool;                    // [S][C]
     const int *best_idx, *best_mk;
 };
 
@@ -58,39 +62,8 @@ __global__ void k_search_init(SearchArgs a) {
     a.active[k] = 1;
 }
 
-// Move j of the neighbourhood: j = 0 keeps the point; otherwise (j - 1) / 2 numbers the stage
-// range [lo, hi] and the parity of j - 1 picks -1 (even) or +1 (odd).
-__device__ __forceinline__ void decode_move(int nb, int S, int j, int *lo, int *hi, int *sign) {
-    if (j == 0) { *lo = 0; *hi = -1; *sign = 0; return; }
-    int r = (j - 1) >> 1;
-    *sign = ((j - 1) & 1) ? 1 : -1;
-    if (nb == 0) { *lo = 0; *hi = r; return; }
-    int a = 0;
-    while (r >= S - a) { r -= S - a; ++a; }      // ranges are numbered a = 0.., b = a..S-1
-    *lo = a; *hi = a + r;
-}
-
 __global__ void k_search_clear_moved(SearchArgs a) {
     if (threadIdx.x < kRoundsPerCheck) a.counters[kMovedAt + threadIdx.x] = 0;
-}
-
-__global__ void k_search_pool(SearchArgs a) {
-    if (a.gate && *a.gate == 0) return;
-    const long long c = (long long)blockIdx.x * kThreadsPerBlock + threadIdx.x;
-    if (c >= a.C) return;
-    const int per_point = a.n_moves + 1;
-    const long long k = c / per_point;
-    const int j = (int)(c % per_point);
-    if (a.skip_resting && !a.active[k]) {               // at rest: an entry that is never resolved
-        for (int s = 0; s < a.S; ++s) a.pool[(long long)s * a.C + c] = s == 1 ? 1 : 0;
-        return;
-    }
-    int lo, hi, sign;
-    decode_move(a.nb, a.S, j, &lo, &hi, &sign);
-    for (int s = 0; s < a.S; ++s) {
-        const int w = a.cur_w[(long long)s * a.K + k] + (s >= lo && s <= hi ? sign : 0);
-        a.pool[(long long)s * a.C + c] = clamp_w(w, a.M);
-    }
 }
 
 __global__ void k_search_advance(SearchArgs a) {
@@ -99,7 +72,12 @@ __global__ void k_search_advance(SearchArgs a) {
     if (k >= a.K) return;
     const int bi = a.best_idx[k];
     if (bi >= 0 && a.best_mk[k] < a.cur_mk[k]) {
-        for (int s = 0; s < a.S; ++s) a.cur_w[(long long)s * a.K + k] = a.pool[(long long)s * a.C + bi];
+        int lo, hi, sign;                               // entry bi is this scenario's point after move bi mod (moves + 1)
+        adaptra_detail::neighbourhood_move(a.nb, a.S, bi % (a.n_moves + 1), &lo, &hi, &sign);
+        for (int s = 0; s < a.S; ++s) {
+            int *const w = &a.cur_w[(long long)s * a.K + k];
+            *w = clamp_w(*w + (s >= lo && s <= hi ? sign : 0), a.M);
+        }
         a.cur_mk[k] = a.best_mk[k];
         atomicAdd(a.moved, 1);
         atomicMax(&a.counters[1], a.cur_w[k]);           // w is non-increasing over the stages of a feasible point
@@ -112,7 +90,7 @@ __global__ void k_search_advance(SearchArgs a) {
 struct SearchPlan {
     int n_moves;
     long long c_max;
-    size_t off_counters, off_active, off_pool, off_best_idx, off_best_mk, off_best_ws, best_ws_bytes, total;
+    size_t off_counters, off_active, off_best_idx, off_best_mk, off_best_ws, best_ws_bytes, total;
 };
 
 bool plan_search(const adaptra_params_t *p, long long K, int nb, SearchPlan *pl) {
@@ -126,7 +104,6 @@ bool plan_search(const adaptra_params_t *p, long long K, int nb, SearchPlan *pl)
     size_t o = 0;
     pl->off_counters = o; o += 256;
     pl->off_active = o;   o += adaptra_detail::align256((size_t)K * 4);
-    pl->off_pool = o;     o += adaptra_detail::align256((size_t)p->S * (size_t)pl->c_max * 4);
     pl->off_best_idx = o; o += adaptra_detail::align256((size_t)K * 4);
     pl->off_best_mk = o;  o += adaptra_detail::align256((size_t)K * 4);
     pl->off_best_ws = o;  o += adaptra_detail::align256(pl->best_ws_bytes);
@@ -160,9 +137,10 @@ int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *sc
     a.cur_w = out_w; a.cur_mk = out_makespan;
     a.counters = (int *)(base + pl.off_counters);
     a.active = (int *)(base + pl.off_active);
-    a.skip_resting = a.S > 1 && a.M > 1;
-    a.pool = (int *)(base + pl.off_pool);
     a.C = pl.c_max;
+    // resting scenarios can be marked where a vector with w_0 < w_1 exists: a stage 1, and M > 1
+    const bool skip_resting = a.S > 1 && a.M > 1;
+    const adaptra_detail::Neighbourhood moves{out_w, skip_resting ? a.active : nullptr, a.K, pl.n_moves + 1, neighbourhood};
     int *best_idx = (int *)(base + pl.off_best_idx), *best_mk = (int *)(base + pl.off_best_mk);
     a.best_idx = best_idx; a.best_mk = best_mk;
     adaptra_params_t bp = *params;
@@ -199,16 +177,13 @@ int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *sc
         for (int i = 0; i < n; ++i) {
             a.gate = i == 0 ? nullptr : a.counters + kMovedAt + i - 1;
             a.moved = a.counters + kMovedAt + i;
-            // step 1: every scenario's point and its neighbours
-            hipLaunchKernelGGL(k_search_pool, dim3(blocks_for(a.C, INT32_MAX)), dim3(kThreadsPerBlock), 0, st, a);
-            ADAPTRA_CHECK_LAUNCH();
-            // step 2: each pool entry under its own scenario, and the best entry per scenario.  No w
-            // in the pool exceeds the largest w[0] any point had at the last read-back by more than
-            // one per round since.
+            // steps 1 and 2: every scenario's point and its neighbours, each under its own scenario,
+            // and the best entry per scenario.  No w in the pool exceeds the largest w[0] any point
+            // had at the last read-back by more than one per round since.
             const long long top = (long long)w_top + i + 1;
-            const adaptra_candidates_t pool{a.C, a.pool, (int32_t)(top > a.M - 1 ? a.M - 1 : top)};
+            const adaptra_candidates_t pool{a.C, nullptr, (int32_t)(top > a.M - 1 ? a.M - 1 : top)};
             int rc = adaptra_detail::best(&bp, &pool, scens, pl.n_moves + 1, best_idx, best_mk, nullptr, nullptr,
-                                          base + pl.off_best_ws, pl.best_ws_bytes, stream, false, a.gate);
+                                          base + pl.off_best_ws, pl.best_ws_bytes, stream, false, a.gate, &moves);
             if (rc) return rc;
             // step 3: move
             hipLaunchKernelGGL(k_search_advance, dim3(kblocks), dim3(kThreadsPerBlock), 0, st, a);
@@ -221,7 +196,7 @@ int adaptra_search(const adaptra_params_t *params, const adaptra_scenarios_t *sc
         w_top = back[1];
         for (int i = 0; i < n && !settled; ++i) {         // rounds behind one that moved nothing were skipped
             ++rounds;
-            evaluated += (a.skip_resting ? still_moving : a.K) * (pl.n_moves + 1);
+            evaluated += (skip_resting ? still_moving : a.K) * (pl.n_moves + 1);
             still_moving = back[kMovedAt + i];
             settled = still_moving == 0;
         }
