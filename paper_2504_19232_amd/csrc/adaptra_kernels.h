@@ -90,6 +90,9 @@ struct KArgs {
 };
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+// The value continues in a register chosen here (an empty asm statement that "rewrites" it).
+__device__ __forceinline__ void pin_vector(int &v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void pin_scalar(unsigned &v) { asm volatile("" : "+s"(v)); }
 __device__ __forceinline__ int imax(int a, int b) { return a > b ? a : b; }
 
 // Move j of the guided search's neighbourhood: j = 0 keeps the point; otherwise (j - 1) / 2
@@ -235,9 +238,9 @@ __device__ __forceinline__ KArgsPtr kargs() {
 // A wavefront-uniform value held in a vector register on purpose: v_add_u32 with two vector
 // operands can issue at twice the rate of the same add with a scalar operand on this chip (see
 // adaptra_probe.hip), so the addends of the recurrence's steady loop live in VGPRs -- where there
-// is room: at 32 stages the S registers are worth more to the cool-down phase's copies (below),
-// which spill without them (measured 41.1 against 44.0 ms on configuration 3; at 8 and 16
-// stages the vector form is 1-2 % ahead).
+// is room: at 32 stages the vector form takes all 128 registers and spills 11 values (outside
+// the steady loop) for no gain (40.06 against 40.12 ms on configuration 3), so the addends stay
+// scalar there; at 8 and 16 stages the vector form is 1-2 % ahead.
 // (Per-lane addends -- per-scenario stage times -- pass through the same empty statement: it
 // also keeps the compiler from re-deriving them from memory inside the loops.)
 template <int S, bool VT>
@@ -664,6 +667,7 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : (S >= 24 ? 5 : 
             const unsigned long long zmask = __ballot(lane >= 1 && lane < S && wq_prev == wq_lanes);
             int L[S], x[S];
             unsigned soff[S];     // biased ring offset of the stage's next forward micro-batch
+            unsigned slot_first[kPD > 1 ? kPD : 1];   // ring addresses of stages 1..kPD-1 for the coming round
             int add_f[S];         // what the stage's next op adds to L[s]: t_f while the pipeline
                                   // fills, t_f + t_b in steady state, t_b once out of forwards
 #pragma unroll
@@ -681,7 +685,9 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : (S >= 24 ? 5 : 
 // m and the stage's offset moves on to slot m+1.
 #define ADAPTRA_F_OP(s, e)                                                      \
     do {                                                                        \
-        const unsigned slot = ring + soff[s];                                   \
+        unsigned slot;                                                          \
+        if constexpr ((s) >= 1 && (s) < kPD) slot = slot_first[(s) < kPD ? (s) : 0]; \
+        else slot = ring + soff[s];                                             \
         if constexpr ((s) == 0) {                                               \
             L[0] += (e);                                                        \
             soff[0] = ring_next(soff[0], bias);                                 \
@@ -699,12 +705,15 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : (S >= 24 ? 5 : 
             x[(s) + kPD <= S - 1 ? (s) + kPD : 0] =                             \
                 *(lds_int *)(ring + soff[(s) + kPD <= S - 1 ? (s) + kPD : 0]);  \
     } while (0)
-// ... and the reads of stages 1..kPD for the next round are issued at the end of the
-// forward sweep, so that they complete under the backward sweep.
+// ... and the reads of stages 1..kPD-1, which no stage of their own round can issue that far
+// ahead, are issued at the end of the forward sweep before, so that they complete under the
+// backward sweep.  Their addresses are the ones those stages write to in the next round
+// (slot_first: kept, not computed again).
 #define ADAPTRA_READ_NEXT_ROUND()                                               \
-    stages_up<1, kPD + 1>(ADAPTRA_STAGE_LAMBDA(sj) {                            \
+    stages_up<1, kPD>(ADAPTRA_STAGE_LAMBDA(sj) {                                \
         constexpr int j = decltype(sj)::value;                                  \
-        x[j] = *(lds_int *)(ring + soff[j]);                                    \
+        slot_first[j] = ring + soff[j];                                         \
+        x[j] = *(lds_int *)slot_first[j];                                       \
     })
 #define ADAPTRA_B_SWEEP()                                                       \
     do {                                                                        \
@@ -812,6 +821,16 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : (S >= 24 ? 5 : 
                 stage_blocks_up<0, S, kDrainBlock>(ADAPTRA_STAGE_LAMBDA(bi) {
                     constexpr int D0 = decltype(bi)::value;
                     constexpr int D1 = D0 + kDrainBlock < S ? D0 + kDrainBlock : S;
+#ifndef ADAPTRA_NO_DRAIN_PIN
+                    // The state enters each copy's loop through a register of the loop's own
+                    // choosing: without this the compiler reconciles the registers of the copy
+                    // before with this loop's on the loop's BACK edge, S vector moves per round.
+                    stages_up<0, S>(ADAPTRA_STAGE_LAMBDA(si) {
+                        constexpr int s = decltype(si)::value;
+                        pin_vector(L[s]);
+                        pin_scalar(soff[s]);
+                    });
+#endif
                     for (; r <= M - 1; ++r) {
                         while (done < S && __builtin_amdgcn_readlane(wq_lanes, done) + r > M - 1) ++done;
                         done = uni(done);      // said again for the compiler, which otherwise loses it across the copies
@@ -825,9 +844,10 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : (S >= 24 ? 5 : 
                             }
                             if constexpr (s + kPD >= D0) ADAPTRA_READ_AHEAD(s);
                         });
-                        stages_up<(D0 > 1 ? D0 : 1), kPD + 1>(ADAPTRA_STAGE_LAMBDA(sj) {      // next round's first reads
+                        stages_up<(D0 > 1 ? D0 : 1), kPD>(ADAPTRA_STAGE_LAMBDA(sj) {      // next round's first reads
                             constexpr int j = decltype(sj)::value;
-                            x[j] = *(lds_int *)(ring + soff[j]);
+                            slot_first[j] = ring + soff[j];
+                            x[j] = *(lds_int *)slot_first[j];
                         });
                         stages_up<0, D0>(ADAPTRA_STAGE_LAMBDA(si) {
                             constexpr int s = decltype(si)::value;
