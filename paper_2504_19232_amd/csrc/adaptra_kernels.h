@@ -787,41 +787,12 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : (S >= 24 ? 5 : 
             // read issued on their behalf; the stages from D1 on run the steady forward step
             // untested; only the block's own stages are tested.  The finished stages' backward
             // durations are added ahead of the steady backward sweep (independent adds).
-            if constexpr (VT) {
-                // per-scenario stage times: one copy of the round for all stages (the compiler
-                // fails on several -- "illegal VGPR to SGPR copy" -- when the per-lane addends
-                // change inside them); a stage that has just run out of forwards gets t_b as its
-                // addend, applied inside the backward sweep
-                int done = 0;
-                for (int r = M - W; r <= M - 1; ++r) {
-                    const int done_before = done;
-                    while (done < S && __builtin_amdgcn_readlane(wq_lanes, done) + r > M - 1) ++done;
-                    stages_up<0, S>(ADAPTRA_STAGE_LAMBDA(si) {
-                        constexpr int s = decltype(si)::value;
-                        if (s >= done) ADAPTRA_F_OP(s, add_f[s]);
-                        ADAPTRA_READ_AHEAD(s);
-                    });
-                    ADAPTRA_READ_NEXT_ROUND();
-                    int carry = 0;
-                    __builtin_amdgcn_s_setprio(kPrioBackward);
-                    stages_down<S - 1, 0>(ADAPTRA_STAGE_LAMBDA(si) {
-                        constexpr int s = decltype(si)::value;
-                        int prev = L[s];
-                        if (s < done) {                                   // B after B
-                            if (s >= done_before) add_f[s] -= ADAPTRA_TF(s);
-                            prev += add_f[s];
-                        }
-                        L[s] = (s == S - 1) ? prev : imax(prev, carry + q[s < S - 1 ? s : 0]);
-                        carry = L[s];
-                    });
-                    __builtin_amdgcn_s_setprio(kPrioForward);
-                }
-            } else {
+            {
                 int done = 0, r = M - W;
+                int converted = 0;     // VT: stages whose addend has been switched to t_b alone
                 stage_blocks_up<0, S, kDrainBlock>(ADAPTRA_STAGE_LAMBDA(bi) {
                     constexpr int D0 = decltype(bi)::value;
                     constexpr int D1 = D0 + kDrainBlock < S ? D0 + kDrainBlock : S;
-#ifndef ADAPTRA_NO_DRAIN_PIN
                     // The state enters each copy's loop through a register of the loop's own
                     // choosing: without this the compiler reconciles the registers of the copy
                     // before with this loop's on the loop's BACK edge, S vector moves per round.
@@ -830,10 +801,18 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : (S >= 24 ? 5 : 
                         pin_vector(L[s]);
                         pin_scalar(soff[s]);
                     });
-#endif
                     for (; r <= M - 1; ++r) {
                         while (done < S && __builtin_amdgcn_readlane(wq_lanes, done) + r > M - 1) ++done;
                         done = uni(done);      // said again for the compiler, which otherwise loses it across the copies
+                        if constexpr (VT) {
+                            // per-lane addends: a stage that has just run out of forwards keeps t_b alone
+                            converted = uni(converted);
+                            stages_up<D0, D1>(ADAPTRA_STAGE_LAMBDA(si) {
+                                constexpr int s = decltype(si)::value;
+                                if (s >= converted && s < done) add_f[s] = in_vgpr<S, VT>(add_f[s] - ADAPTRA_TF(s));
+                            });
+                            converted = done < D1 ? done : D1;
+                        }
                         if (D1 < S && done >= D1) break;      // the next block's copy takes this round
                         stages_up<0, S>(ADAPTRA_STAGE_LAMBDA(si) {
                             constexpr int s = decltype(si)::value;
@@ -851,11 +830,15 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : (S >= 24 ? 5 : 
                         });
                         stages_up<0, D0>(ADAPTRA_STAGE_LAMBDA(si) {
                             constexpr int s = decltype(si)::value;
-                            L[s] += ADAPTRA_TB(s);
+                            if constexpr (VT) L[s] += add_f[s];
+                            else L[s] += ADAPTRA_TB(s);
                         });
                         stages_up<D0, D1>(ADAPTRA_STAGE_LAMBDA(si) {
                             constexpr int s = decltype(si)::value;
-                            if (s < done) L[s] += ADAPTRA_TB(s);
+                            if (s < done) {
+                                if constexpr (VT) L[s] += add_f[s];
+                                else L[s] += ADAPTRA_TB(s);
+                            }
                         });
                         ADAPTRA_B_SWEEP();
                     }
