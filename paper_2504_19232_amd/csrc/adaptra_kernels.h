@@ -19,6 +19,7 @@
 #include <stdint.h>
 
 #include <atomic>
+#include <type_traits>
 
 #include "adaptra.h"
 #include "adaptra_internal.h"
@@ -249,6 +250,20 @@ __device__ __forceinline__ int in_vgpr(int v) {
     return v;
 }
 __device__ __forceinline__ int clampw(int w, int M) { return w < 0 ? 0 : (w > M - 1 ? M - 1 : w); }
+// Byte `k` of `word` plus a wavefront-uniform number, as ONE instruction (an add that selects the
+// byte of its operand).  Written out because the compiler, given two loops that use the bytes of
+// the round-invariant packed w, unpacks all S of them into registers of their own ahead of the
+// loops (32 registers at 32 stages, a wavefront per SIMD less).
+__device__ __forceinline__ unsigned byte_plus(unsigned word, int k, int uniform) {
+    unsigned r;
+    switch (k) {
+    case 0: asm("v_add_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0 src1_sel:DWORD" : "=v"(r) : "v"(word), "s"(uniform)); break;
+    case 1: asm("v_add_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:DWORD" : "=v"(r) : "v"(word), "s"(uniform)); break;
+    case 2: asm("v_add_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2 src1_sel:DWORD" : "=v"(r) : "v"(word), "s"(uniform)); break;
+    default: asm("v_add_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3 src1_sel:DWORD" : "=v"(r) : "v"(word), "s"(uniform)); break;
+    }
+    return r;
+}
 
 // ---------------------------------------------------------------------------------------
 // Wavefront-wide minimum of a 64-bit key: DPP butterflies inside each row of 16 lanes,
@@ -325,7 +340,7 @@ constexpr int kCandLanesStageTimesMax = 32;
 // case the value just computed is taken instead.  Two more instructions per stage and round,
 // and registers for the values in flight.
 template <int S, bool BEST, bool VT, bool AHEAD>
-__global__ __launch_bounds__(kBlock, AHEAD || S >= 48 || (VT && S >= 16) ? 2 : (S >= 24 ? 4 : 6)) void k_resolve_cand_lanes(KArgs) {
+__global__ __launch_bounds__(kBlock, S >= 48 || (VT && S >= 16) ? 2 : (S >= 24 ? 4 : (AHEAD ? 4 : 6))) void k_resolve_cand_lanes(KArgs) {
     // The arguments are read through kargs() where they are needed (see there): kept in SGPRs
     // across the round loop they would crowd out the loop's own scalars.
     extern __shared__ int lds[];
@@ -369,6 +384,15 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 48 || (VT && S >= 16) ? 2 : (
 #pragma unroll
         for (int i = 0; i < (S + 3) / 4; ++i)
             wpk[i] = run ? *(const unsigned *)(kargs()->cand_wq + c * kargs()->wq_stride + 4 * i) : 0u;
+        int r_all;                                       // last round in which every stage of every lane has a forward
+        {                                                // (worked out here, before the state below occupies the registers)
+            int wmax = 0;
+#pragma unroll
+            for (int s = 0; s < S; ++s) wmax = imax(wmax, (int)((wpk[s / 4] >> (8 * (s % 4))) & 0xffu));
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) wmax = imax(wmax, __shfl_xor(wmax, off));
+            r_all = uni(M - 1 - wmax);
+        }
         int cf[S > 1 ? S - 1 : 1], cb[S > 1 ? S - 1 : 1], last[S];
 #pragma unroll
         for (int s = 0; s < S; ++s) last[s] = 0;
@@ -422,7 +446,12 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 48 || (VT && S >= 16) ? 2 : (
             }
         }
         int b = 0;                                       // the ring slot of micro-batch r (r mod D)
-        for (int r = 0; r < M; ++r) {
+        // One round.  kTest: the forward step of a stage counts only if its micro-batch exists,
+        // w[s] + r < M; the rounds in which that holds for every stage of every lane of the
+        // wavefront (the long middle of the schedule) run a copy without the test, three vector
+        // instructions per stage and round less.
+        auto one_round = [&](int r, auto test_tag) {
+            constexpr bool kTest = decltype(test_tag)::value;
             if (r == 0) {
                 // round 0's forwards were the last of the fill phase
             } else if constexpr (AHEAD) {                // forward sweep, ring reads three stages ahead
@@ -430,7 +459,7 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 48 || (VT && S >= 16) ? 2 : (
                 int *slot_of[S];
                 int ahead[S];
                 auto ring_slot = [&](int s) {
-                    unsigned slot = ((wpk[s / 4] >> (8 * (s % 4))) & 0xffu) + (unsigned)b;
+                    unsigned slot = byte_plus(wpk[s / 4], s % 4, b);
                     slot = slot < slot - (unsigned)D ? slot : slot - (unsigned)D;      // mod D (w < D, b < D)
                     return ring + slot * 64;
                 };
@@ -451,7 +480,7 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 48 || (VT && S >= 16) ? 2 : (
                             ahead[s + kAhead] = *slot_of[s + kAhead];
                         }
                         const int ws = (int)((wpk[s / 4] >> (8 * (s % 4))) & 0xffu);
-                        const bool valid = (unsigned)(ws + r) < (unsigned)M;
+                        const bool valid = kTest && byte_plus(wpk[s / 4], s % 4, r) < (unsigned)M;
                         int t_f_s;
                         if constexpr (VT) t_f_s = tfv[s];
                         else t_f_s = tf[j];
@@ -470,7 +499,8 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 48 || (VT && S >= 16) ? 2 : (
                             const int arrived = ws == ws_before ? fin_before : ahead[s];
                             fin = imax(last[s], arrived + cf[s - 1]) + t_f_s;
                         }
-                        last[s] = valid ? fin : last[s];
+                        if constexpr (kTest) last[s] = valid ? fin : last[s];
+                        else last[s] = fin;
                         if (s < S - 1) *slot_of[s] = fin;
                         fin_before = fin;
                     }
@@ -482,9 +512,8 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 48 || (VT && S >= 16) ? 2 : (
 #pragma unroll
                 for (int j = 0; j < kTimesBlock && h + j < S; ++j) {
                     const int s = h + j;
-                    const int ws = (int)((wpk[s / 4] >> (8 * (s % 4))) & 0xffu);
-                    const bool valid = (unsigned)(ws + r) < (unsigned)M;
-                    unsigned slot = (unsigned)(ws + b);
+                    const bool valid = kTest && byte_plus(wpk[s / 4], s % 4, r) < (unsigned)M;
+                    unsigned slot = byte_plus(wpk[s / 4], s % 4, b);
                     slot = slot < slot - (unsigned)D ? slot : slot - (unsigned)D;      // mod D (w < D, b < D)
                     int *const p = ring + slot * 64;
                     int t_f_s;
@@ -493,7 +522,8 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 48 || (VT && S >= 16) ? 2 : (
                     int fin;
                     if (s == 0) fin = last[0] + t_f_s;
                     else fin = imax(last[s], *p + cf[s - 1]) + t_f_s;
-                    last[s] = valid ? fin : last[s];
+                    if constexpr (kTest) last[s] = valid ? fin : last[s];
+                        else last[s] = fin;
                     if (s < S - 1) *p = fin;
                 }
             }
@@ -519,7 +549,11 @@ __global__ __launch_bounds__(kBlock, AHEAD || S >= 48 || (VT && S >= 16) ? 2 : (
             }
             __builtin_amdgcn_s_setprio(kPrioForward);
             b = b + 1 == D ? 0 : b + 1;
-        }
+        };
+        one_round(0, std::true_type{});
+        int r = 1;
+        for (; r <= r_all; ++r) one_round(r, std::false_type{});
+        for (; r < M; ++r) one_round(r, std::true_type{});
         const int mk = last[0];                          // B(0, M-1) is the last op of all
         unsigned long long key = kNoKey;
         if (run) {
