@@ -27,35 +27,21 @@
 namespace adaptra_detail {
 
 constexpr int kNeg = -(1 << 30);          // "no earlier op": below every shifted time
-#ifndef ADAPTRA_CHUNK
-#define ADAPTRA_CHUNK 16
-#endif
-constexpr int kChunk = ADAPTRA_CHUNK;      // candidates one wavefront works through, at most
-#ifndef ADAPTRA_WPB
-#define ADAPTRA_WPB 4
-#endif
-constexpr int kWavesPerBlock = ADAPTRA_WPB;
+constexpr int kChunk = 16;                 // candidates one wavefront works through, at most; the direct
+                                           // output copies a chunk's flags as ONE 16-byte word
+constexpr int kWavesPerBlock = 4;
 constexpr int kBlock = 64 * kWavesPerBlock;
 constexpr int kClassDead = 255;           // deadlocked: never resolved
 constexpr int kClassDeep = 254;           // warm-up depth beyond the LDS ring: general kernel
 constexpr int kNumRingClasses = 16;       // ring of 8 * (class + 1) slots: up to 128 slots = 32 KiB per wavefront
 constexpr int kMaxLdsHistBytes = 16384;
-#ifndef ADAPTRA_PD
-#define ADAPTRA_PD 4
-#endif
 // Wavefront priorities inside the hot kernel (s_setprio): a wavefront in a forward sweep -- LDS
 // traffic and independent instructions -- goes ahead of one in a backward sweep, whose
 // instructions all wait on each other and fill the gaps just as well.  Measured on configuration
 // 3: 49.3 -> 47.2 ms; any two different levels do, the other way round costs 2 ms.
 constexpr int kPrioForward = 2, kPrioBackward = 0;
-#ifndef ADAPTRA_WAVES32
-#define ADAPTRA_WAVES32 4
-#endif
-#ifndef ADAPTRA_DRAIN_BLOCK
-#define ADAPTRA_DRAIN_BLOCK 4
-#endif
-constexpr int kDrainBlock = ADAPTRA_DRAIN_BLOCK;   // stages per copy of the cool-down round (see the hot kernel)
-constexpr int kPrefetchStages = ADAPTRA_PD;        // ring reads run this many stages ahead of their use
+constexpr int kDrainBlock = 4;   // stages per copy of the cool-down round (see the hot kernel)
+constexpr int kPrefetchStages = 4;        // ring reads run this many stages ahead of their use
 constexpr unsigned long long kNoKey = ~0ull;
 
 struct KArgs {
@@ -614,7 +600,7 @@ __global__ __launch_bounds__(kBlock, S >= 48 || (VT && S >= 16) ? 2 : (S >= 24 ?
 // scratch memory -- and four wavefronts per SIMD instead of three are worth 23 % (16 stages:
 // six blocks instead of five, 6 %).
 template <int S, bool BEST, bool VT>
-__global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : (S >= 24 ? 5 : 6)) void k_resolve_scen_lanes(KArgs) {
+__global__ __launch_bounds__(kBlock, S >= 32 ? 4 : (S >= 24 ? 5 : 6)) void k_resolve_scen_lanes(KArgs) {
     // The arguments are read through kargs() where they are needed (see there), never
     // through the by-value parameter.
     extern __shared__ int lds[];
@@ -915,6 +901,7 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? ADAPTRA_WAVES32 : (S >= 24 ? 5 : 
                 // loop they would cost 16 VGPRs there, where the recurrence needs them.
                 const long long C = kargs()->C, P = C * K;
                 const long long at = k * C + c0;                 // 16 candidates from here
+                static_assert(kChunk == 16, "a chunk's flag bytes are copied as one uint4");
                 *(uint4 *)(kargs()->out_feasible + at) = *(const uint4 *)(kargs()->cand_flag + c0);
                 const int M = kargs()->M;
                 // all loads first: a load issued behind the stores below would have to wait for
