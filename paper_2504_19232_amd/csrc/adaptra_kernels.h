@@ -822,7 +822,9 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? 4 : (S >= 24 ? 5 : 6)) void k_res
                         pin_scalar(soff[s]);
                     });
                     for (; r <= M - 1; ++r) {
-                        while (done < S && __builtin_amdgcn_readlane(wq_lanes, done) + r > M - 1) ++done;
+                        // (counted with one ballot over the lanes that hold w; a scalar loop over the
+                        // stages measured 0.3 % slower, 1 % with per-scenario stage times)
+                        done = __popcll(__ballot(wq_lanes + r > M - 1) & (S >= 64 ? ~0ull : (1ull << (S & 63)) - 1ull));
                         done = uni(done);      // said again for the compiler, which otherwise loses it across the copies
                         if constexpr (VT) {
                             // per-lane addends: a stage that has just run out of forwards keeps t_b alone
