@@ -824,7 +824,8 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? 4 : (S >= 24 ? 5 : 6)) void k_res
                     for (; r <= M - 1; ++r) {
                         // (counted with one ballot over the lanes that hold w; a scalar loop over the
                         // stages measured 0.3 % slower, 1 % with per-scenario stage times)
-                        done = __popcll(__ballot(wq_lanes + r > M - 1) & (S >= 64 ? ~0ull : (1ull << (S & 63)) - 1ull));
+                        static_assert(S <= 32, "the stages' lanes are counted in the low half of the ballot");
+                        done = __builtin_popcount((unsigned)__ballot(wq_lanes + r > M - 1) & (S >= 32 ? ~0u : (1u << (S & 31)) - 1u));
                         done = uni(done);      // said again for the compiler, which otherwise loses it across the copies
                         if constexpr (VT) {
                             // per-lane addends: a stage that has just run out of forwards keeps t_b alone
