@@ -627,8 +627,22 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? 4 : (S >= 24 ? 5 : 6)) void k_res
 
     const long long task = (long long)blockIdx.x * kWavesPerBlock + wv;
     const int tile = (int)(task % kargs()->n_ktiles);
-    const long long c0 = (task / kargs()->n_ktiles) * kargs()->chunk;
-    if (c0 < kargs()->C) {
+    // The search (BEST) walks the pre-pass's list of feasible candidates, as the candidate-lanes
+    // kernel does: a wavefront's chunk then holds candidates that all run, however few of the
+    // candidate axis are feasible (3 901 of 65 536 on the benchmarked workload: by index, most
+    // chunks held one or none and the wavefronts' work was set-up).  The list may be much shorter
+    // than the axis the grid was sized for, so the chunk is chosen here: about 8 192 wavefronts'
+    // worth of work as on the host, never so short that the grid's tasks would not cover the list.
+    const long long n_cand = BEST && kargs()->live_list ? (long long)uni(kargs()->status[48]) : kargs()->C;
+    int chunk_here = kargs()->chunk;
+    if (BEST && kargs()->live_list) {
+        long long ch = n_cand * kargs()->n_ktiles / 8192;
+        const long long need = (n_cand * kargs()->chunk + kargs()->C - 1) / kargs()->C;
+        ch = ch < need ? need : ch;
+        chunk_here = uni((int)(ch < 1 ? 1 : (ch > kChunk ? kChunk : ch)));
+    }
+    const long long c0 = (task / kargs()->n_ktiles) * chunk_here;
+    if (c0 < n_cand) {
         const long long K = kargs()->K;
         const long long k = (long long)tile * 64 + lane;
         const bool kvalid = k < K;
@@ -663,8 +677,8 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? 4 : (S >= 24 ? 5 : 6)) void k_res
         }
 
         unsigned long long key = kNoKey;
-        const long long c_left = kargs()->C - c0;
-        const int chunk = kargs()->chunk;
+        const long long c_left = n_cand - c0;
+        const int chunk = chunk_here;
         const int c_end = (int)(c_left < chunk ? c_left : chunk);
         // Direct output (evaluation, chunks of exactly 16 candidates, a single launch): the
         // makespans of the chunk are kept per lane and written at its end, 16 consecutive
@@ -672,7 +686,7 @@ __global__ __launch_bounds__(kBlock, S >= 32 ? 4 : (S >= 24 ? 5 : 6)) void k_res
         // streaming pass over all pairs is not needed and the writes hide under the VALU work.
         __builtin_amdgcn_s_setprio(kPrioForward);
         for (int ci = 0; ci < c_end; ++ci) {
-            const long long c = c0 + ci;
+            const long long c = BEST && kargs()->live_list ? (long long)uni(kargs()->live_list[c0 + ci]) : c0 + ci;
             {
                 const int cls = uni(kargs()->cand_class[c]);
                 if (cls < kargs()->cls_lo || cls > kargs()->cls_hi) continue;
