@@ -355,7 +355,7 @@ __global__ void k_zb_pack(const uint8_t *plans, uint32_t *packed, long long C, i
 //     fin = max(busy[i], ready[slot]) + duration;  busy[i] = fin;  ready[slot] = fin + delay,
 // without a case distinction: a forward of stage 0 finds 0 in its slot, a backward of the last
 // stage its own forward's finish (not later than the stage is busy), and a weight op uses a slot
-// of its own with a "delay" of -2^30, so that what it leaves there never exceeds a busy time.
+// of its own with a "delay" of -2^31, so that what it leaves there never exceeds a busy time.
 // Per op: four LDS reads in one round trip (the duration is a broadcast read), one max, two
 // adds, two LDS writes, and the scalar decoding of the entry.
 struct ZbReplayRows {
@@ -379,7 +379,7 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_replay_scen(ZbArgs a) {
     t.S = S;
     t.busy = zb_lds + lane;                           // [S][64]
     t.ready = t.busy + S * 64;                        // [N + 1][64]; slot N is the weight ops'
-    t.delay = t.ready + (N + 1) * 64;                 // [3][S][64]: link i -> i+1, link i-1 <- i, -2^30
+    t.delay = t.ready + (N + 1) * 64;                 // [3][S][64]: link i -> i+1, link i-1 <- i, -2^31
     int *const dur = zb_lds + (4 * S + N + 1) * 64;   // [3][S]: t_f, t_b, t_w
     t.dur = dur;
     // Block -> (candidate, tile of 64 scenarios).  A lane's results lie C ints apart, so the 4-byte
@@ -401,7 +401,7 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_replay_scen(ZbArgs a) {
         t.busy[i * 64] = 0;
         t.delay[i * 64] = i < S - 1 ? a.cf[(long long)i * a.K + k] : 0;
         t.delay[(S + i) * 64] = i > 0 ? a.cb[(long long)(i - 1) * a.K + k] : 0;
-        t.delay[(2 * S + i) * 64] = -(1 << 30);
+        t.delay[(2 * S + i) * 64] = INT32_MIN;       // finish (>= 0) + this is negative, and does not wrap
     }
     for (int m = 0; m <= N; ++m) t.ready[m * 64] = 0;
     __syncthreads();                                  // the durations (one wavefront: no more than a wait)
