@@ -475,14 +475,66 @@ struct SeedArgs {
     unsigned char *not_absorbed;
 };
 
+// V consecutive scenarios per thread (1 or 4).  With 4 every access of a lane is 16 bytes (4 for
+// the flags), so a wavefront's load or store covers 1 KiB of one row: the kernel walks 2(S-1)
+// input rows and 2S-1 output rows at once, each K ints from the next, i.e. every access of a
+// wavefront is to another page than the one before, and four times the bytes per access is a
+// quarter of the address translations per byte.
+template <int V>
+struct SeedVec { int v[V]; };
+template <int V>
+__device__ __forceinline__ SeedVec<V> seed_load(const int *p) {
+    SeedVec<V> r;
+    if (V % 4 == 0) {
+#pragma unroll
+        for (int q = 0; q < V / 4; ++q) {
+            const int4 t = reinterpret_cast<const int4 *>(p)[q];
+            r.v[(4 * q) % V] = t.x; r.v[(4 * q + 1) % V] = t.y; r.v[(4 * q + 2) % V] = t.z; r.v[(4 * q + 3) % V] = t.w;
+        }
+    } else if (V == 2) {
+        const int2 t = *reinterpret_cast<const int2 *>(p);
+        r.v[0] = t.x; r.v[1 % V] = t.y;
+    } else {
+        r.v[0] = *p;
+    }
+    return r;
+}
+template <int V>
+__device__ __forceinline__ void seed_store(int *p, const SeedVec<V> &r) {
+    if (V % 4 == 0) {
+#pragma unroll
+        for (int q = 0; q < V / 4; ++q)
+            reinterpret_cast<int4 *>(p)[q] = make_int4(r.v[(4 * q) % V], r.v[(4 * q + 1) % V], r.v[(4 * q + 2) % V], r.v[(4 * q + 3) % V]);
+    } else if (V == 2) {
+        *reinterpret_cast<int2 *>(p) = make_int2(r.v[0], r.v[1 % V]);
+    } else {
+        *p = r.v[0];
+    }
+}
+
+// ceil(num / den), exact wherever it is below `clip`, some value >= clip otherwise (also for den
+// = 0); 3 <= clip <= 2^15, num < 2^34.  Algorithm 2 only ever uses the ratio through min(., clip),
+// so a single-precision estimate is enough to be within one of floor(num / den) in the range that
+// matters (relative error below 2^-21, i.e. below 2^-6 up to clip + 1), and two exact products
+// decide between the three values the ceiling can then have.  No integer division, no branch.
+__device__ __forceinline__ int seed_ceil_ratio(unsigned long long num, unsigned den, int clip) {
+    const float nf = fmaf((float)(unsigned)(num >> 32), 4294967296.f, (float)(unsigned)num);
+    const float estimate = nf * __builtin_amdgcn_rcpf((float)den);      // inf or NaN for den = 0: fminf then gives clip
+    const unsigned c = (unsigned)fminf(estimate, (float)clip);          // floor, at most clip
+    const unsigned long long below = (unsigned long long)c * den;       // c - 1 < num / den < c + 2
+    return (int)c + (num > below ? 1 : 0) + (num > below + den ? 1 : 0);
+}
+
+template <int V>
 __global__ __launch_bounds__(kBlock) void k_seed(SeedArgs a) {
-    const long long k = (long long)blockIdx.x * kBlock + threadIdx.x;
+    const long long thread = (long long)blockIdx.x * kBlock + threadIdx.x;
+    const long long k = thread * V;
     const int S = a.S;
     // Algorithm 1: the x_max - 1 units of slack go to the S - 1 links in equal shares, the
     // links nearest stage 0 taking the units left over; stage s holds x_max minus the slack of
     // the s links above it.  One thread per stage.
-    if (k < S && a.w_init) {
-        const int s = (int)k;
+    if (thread < S && a.w_init) {
+        const int s = (int)thread;
         int x = a.x_max;
         if (S > 1) {
             const int share = (a.x_max - 1) / (S - 1), left_over = (a.x_max - 1) % (S - 1);
@@ -490,57 +542,75 @@ __global__ __launch_bounds__(kBlock) void k_seed(SeedArgs a) {
         }
         a.w_init[s] = x - 1;
     }
-    if (k >= a.K) return;
-    auto tau = [&](int i) -> long long {       // t_f + t_b of stage i as this scenario sees it
-        return a.tfs ? (long long)a.tfs[(long long)i * a.K + k] + a.tbs[(long long)i * a.K + k]
-                     : (long long)a.t_f[i] + a.t_b[i];
+    if (k >= a.K) return;                       // V divides K when V > 1: a thread's scenarios all exist
+    const long long K = a.K;
+    // t_f + t_b of stage i as each of this thread's scenarios sees it (two non-negative int32: 32 bits unsigned)
+    auto tau = [&](int i, unsigned (&out)[V]) {
+        if (a.tfs) {
+            const SeedVec<V> f = seed_load<V>(a.tfs + (long long)i * K + k), b = seed_load<V>(a.tbs + (long long)i * K + k);
+#pragma unroll
+            for (int v = 0; v < V; ++v) out[v] = (unsigned)f.v[v] + (unsigned)b.v[v];
+        } else {
+            const unsigned t = (unsigned)a.t_f[i] + (unsigned)a.t_b[i];
+#pragma unroll
+            for (int v = 0; v < V; ++v) out[v] = t;
+        }
     };
-    // One pass over the links, last to first, serves both outputs: the delays are read once,
-    // four links at a time so that their loads are in flight together (a link's slack needs
-    // the one below it only through the running sum x).
+    // One pass over the links, last to first, serves both outputs, so the delays are read once
+    // (a link's slack needs the one below it only through the running sum x).
     const int *__restrict__ const cf = a.cf + k, *__restrict__ const cb = a.cb + k;
     int *__restrict__ const w_adapted = a.w_adapted ? a.w_adapted + k : nullptr;
     unsigned char *__restrict__ const not_absorbed = a.not_absorbed ? a.not_absorbed + k : nullptr;
-    const long long K = a.K;
-    int x = 1;
-    if (w_adapted) w_adapted[(long long)(S - 1) * K] = 0;
-    const int clip = a.M - 2 * S;
-    long long tau_next = S > 1 ? tau(S - 1) : 0;
-    constexpr int kLinks = 4;
-    for (int i0 = S - 2; i0 >= 0; i0 -= kLinks) {
-        long long load_i[kLinks], tau_i[kLinks];
+    SeedVec<V> x;
 #pragma unroll
-        for (int j = 0; j < kLinks; ++j) {
-            const int i = i0 - j;
-            if (i < 0) break;
-            tau_i[j] = tau(i);
-            load_i[j] = tau_i[j] + cf[(long long)i * K] + cb[(long long)i * K];
-        }
+    for (int v = 0; v < V; ++v) x.v[v] = 0;     // w = x - 1 of the last stage
+    if (w_adapted) seed_store<V>(w_adapted + (long long)(S - 1) * K, x);
 #pragma unroll
-        for (int j = 0; j < kLinks; ++j) {
-            const int i = i0 - j;
-            if (i < 0) break;
-            const long long num = load_i[j], den = tau_next;
+    for (int v = 0; v < V; ++v) x.v[v] = 1;
+    const int clip = a.M - 2 * S;               // at most 2^15 (the limit on M)
+    unsigned tau_next[V];
+    if (S > 1) tau(S - 1, tau_next);
+    for (int i = S - 2; i >= 0; --i) {
+        unsigned tau_i[V];
+        tau(i, tau_i);
+        const SeedVec<V> f = seed_load<V>(cf + (long long)i * K), b = seed_load<V>(cb + (long long)i * K);
+        // Eq. (1) with the current schedule's slack, which may be anything a difference of two int32 can be
+        const long long slack_cur = not_absorbed ? (long long)a.w_cur[i] - a.w_cur[i + 1] : 0;
+        const unsigned slack_abs = (unsigned)(slack_cur < 0 ? -slack_cur : slack_cur);
+        unsigned long long flags = 0;
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const unsigned den = tau_next[v];
+            const unsigned long long num = (unsigned long long)tau_i[v] + ((unsigned)f.v[v] + (unsigned)b.v[v]);
             if (w_adapted) {
-                long long d = clip;
-                if (den != 0) {
-                    // ceil(num / den); both are sums of non-negative int32 values, and whenever they fit
-                    // 32 bits (always, under adaptra_check_inputs' bound) a 32-bit division does
-                    const long long up = num + den - 1;
-                    long long ratio = ((unsigned long long)(up | den) >> 32) == 0 ? (long long)((unsigned)up / (unsigned)den) : up / den;
-                    if (ratio < 2) ratio = 2;
-                    if (ratio < d) d = ratio;
+                int d = clip;                   // a ratio of at least 2 never gets below a clip of 2 or less
+                if (clip > 2) {
+                    const int ratio = seed_ceil_ratio(num, den, clip);
+                    d = ratio < 2 ? 2 : (ratio < clip ? ratio : clip);
                 }
                 if (d < 0) d = 0;
-                const long long nx = x + d;
-                x = nx > a.M ? a.M : (int)nx;
-                w_adapted[(long long)i * K] = x - 1;
+                const int nx = x.v[v] + d;
+                x.v[v] = nx > a.M ? a.M : nx;
             }
             if (not_absorbed) {
-                const long long rhs = ((long long)a.w_cur[i] - a.w_cur[i + 1]) * den;
-                not_absorbed[(long long)i * K] = num <= rhs ? 0 : 1;
+                // num <= slack_cur * den; with a negative slack the product is negative unless den = 0
+                const bool absorbed = slack_cur >= 0 ? num <= (unsigned long long)slack_abs * den : (num | den) == 0;
+                flags |= (absorbed ? 0ull : 1ull) << (8 * v);
             }
-            tau_next = tau_i[j];
+            tau_next[v] = tau_i[v];
+        }
+        if (w_adapted) {
+            SeedVec<V> w;
+#pragma unroll
+            for (int v = 0; v < V; ++v) w.v[v] = x.v[v] - 1;
+            seed_store<V>(w_adapted + (long long)i * K, w);
+        }
+        if (not_absorbed) {
+            // little-endian: byte v = scenario k + v
+            if (V == 8) *reinterpret_cast<unsigned long long *>(not_absorbed + (long long)i * K) = flags;
+            else if (V == 4) *reinterpret_cast<unsigned *>(not_absorbed + (long long)i * K) = (unsigned)flags;
+            else if (V == 2) *reinterpret_cast<unsigned short *>(not_absorbed + (long long)i * K) = (unsigned short)flags;
+            else not_absorbed[(long long)i * K] = (unsigned char)flags;
         }
     }
 }
@@ -1061,7 +1131,12 @@ int adaptra_seed(const adaptra_params_t *params, const adaptra_scenarios_t *scen
     a.t_f = params->t_f; a.t_b = params->t_b; a.cf = scens->c_fwd; a.cb = scens->c_bwd;
     a.tfs = scens->t_f; a.tbs = scens->t_b;
     a.w_cur = w_current; a.w_init = out_w_init; a.w_adapted = out_w_adapted; a.not_absorbed = out_not_absorbed;
-    hipLaunchKernelGGL(k_seed, dim3(grid_for(a.K, INT32_MAX)), dim3(kBlock), 0, (hipStream_t)stream, a);
+    // four scenarios per thread where every row then starts on a 16-byte boundary (4 for the flags)
+    const uintptr_t align16 = (uintptr_t)a.cf | (uintptr_t)a.cb | (uintptr_t)a.tfs | (uintptr_t)a.tbs | (uintptr_t)a.w_adapted;
+    if (a.K % 4 == 0 && (align16 & 15) == 0 && ((uintptr_t)a.not_absorbed & 3) == 0)
+        hipLaunchKernelGGL((k_seed<4>), dim3(grid_for(a.K / 4, INT32_MAX)), dim3(kBlock), 0, (hipStream_t)stream, a);
+    else
+        hipLaunchKernelGGL((k_seed<1>), dim3(grid_for(a.K, INT32_MAX)), dim3(kBlock), 0, (hipStream_t)stream, a);
     ADAPTRA_LAUNCH_CHECK();
     return ADAPTRA_OK;
 }

@@ -476,6 +476,46 @@ def test_analytic_seed_edge_cases(lib):
         b.adaptra_seed(prob, 0)                  # x_max must be >= 1 for Algorithm 1
 
 
+@pytest.mark.parametrize("M,K", [(7, 4000), (9, 4001), (40, 4002), (32768, 12000)])
+def test_analytic_seed_ratios_at_their_boundaries(lib, M, K):
+    """Algorithm 2's ceiling ratio where an inexact division would show: load = q * tau_next + e
+    with e in {-1, 0, 1}, q from 0 to beyond the clip M - 2S, tau_next from 1 to 2^32 - 2 and
+    loads up to 2^33 (per-scenario stage times, so that every scenario has a divisor of its own);
+    zero divisors; Eq. (1) under slacks of either sign.  K not a multiple of 4 takes the kernel's
+    one-scenario-per-thread form, the others its four-per-thread form."""
+    import torch
+    from oracle import seed as oseed
+    S, big = 3, 2 ** 31 - 1
+    rng = np.random.default_rng(1000 + M)
+    clip = M - 2 * S
+    tfs = np.zeros((S, K), np.int64); tbs = np.zeros((S, K), np.int64)
+    cf = np.zeros((S - 1, K), np.int64); cb = np.zeros((S - 1, K), np.int64)
+    den = np.floor(2.0 ** rng.uniform(0, 32, (S, K))).astype(np.int64).clip(1, 2 * big)
+    den[:, rng.random(K) < 0.02] = 0                       # zero divisors (all stages of a scenario)
+    den[1, rng.random(K) < 0.02] = 0
+    tfs[:] = den // 2; tbs[:] = den - den // 2
+    for i in range(S - 1):
+        q = np.where(rng.random(K) < 0.5, rng.integers(0, 6, K),
+                     np.where(rng.random(K) < 0.5, max(clip, 0) + rng.integers(-2, 3, K), rng.integers(0, max(clip, 4) + 3, K)))
+        load = np.maximum(q, 0) * den[i + 1] + rng.integers(-1, 2, K)
+        load = load.clip(den[i], den[i] + 2 * big)         # load = tau_i + c_fwd + c_bwd with both delays in int32
+        rest = load - den[i]
+        cf[i] = rest // 2; cb[i] = rest - rest // 2
+    wl = workloads.random_workload(5, S, M, 8, K)
+    wl.c_fwd = cf.astype(np.int32); wl.c_bwd = cb.astype(np.int32)
+    prob = lib.Problem.from_workload(wl, t_f_scen=tfs.astype(np.int32), t_b_scen=tbs.astype(np.int32))
+    for w_cur in ([5, 3, 0], [0, 4, 4], [-big, big, -big]):
+        w_dev = torch.tensor(w_cur, dtype=torch.int32, device="cuda:0")
+        _, w_ad, na = lib.adaptra_seed(prob, 1, w_current=w_dev, want_init=False, want_not_absorbed=True)
+        torch.cuda.synchronize()
+        w_ad, na = w_ad.cpu().numpy(), na.cpu().numpy()
+        for k in range(K):
+            x = oseed.adapted_plan(S, M, tfs[:, k], tbs[:, k], cf[:, k], cb[:, k])
+            assert list(w_ad[:, k]) == oseed.to_w(x), k
+            ab = oseed.absorbed(S, tfs[:, k], tbs[:, k], w_cur, cf[:, k], cb[:, k])
+            assert list(na[:, k]) == [0 if a else 1 for a in ab], k
+
+
 def test_algorithm2_pick_against_the_exhaustive_search(lib, oracle):
     """Algorithm 2's vectors are valid candidates: evaluating them (diagonal of the
     scenario x scenario grid) can never beat adaptra_best over a candidate set that contains them."""
