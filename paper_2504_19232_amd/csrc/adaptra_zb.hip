@@ -321,6 +321,123 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
     }
 }
 
+// Recording with the STAGES on the lanes: G lanes (8 or 16, a power of two >= S) per candidate,
+// 64 / G candidates per wavefront.  The recording runs every candidate under ONE scenario, so
+// with a lane per pair it is a few lone wavefronts whose 3 S N steps nothing overlaps.  With a
+// lane per (candidate, stage) a stage's whole state -- cursors, the heads of its two queues,
+// its busy-until time, its durations and delays -- is in that lane's registers under static
+// names, the earliest next action of a candidate is a minimum over G neighbouring lanes (DPP),
+// a post goes to the neighbouring lane by a DPP shift, and only the queues behind the heads
+// are in LDS ([micro-batch][lane]).  And the stages of a candidate advance TOGETHER: if t is
+// the candidate's earliest next action, nothing that has not been posted yet can become ready
+// before t + L, L = the least (duration + link delay) of any op that posts, because the op that
+// will post it starts at t or later.  So every stage whose next action lies before t + L takes
+// it in the same step -- its decision (Algorithm 3) can no longer be overturned -- and the ops
+// of one step do not depend on each other (what one of them posts is ready at t + L at the
+// earliest).  Same policy and same schedules as k_zb<1, ., .>, in about a fifth of the steps on
+// 1F1B-like warm-ups; the order written for k_zb_replay_scen is topological as before (ops of
+// one step in stage order).
+template <int kCtrl>
+__device__ __forceinline__ unsigned zb_dpp(unsigned keep, unsigned v) {
+    return (unsigned)__builtin_amdgcn_update_dpp((int)keep, (int)v, kCtrl, 0xf, 0xf, false);
+}
+template <int G>
+__device__ __forceinline__ unsigned zb_group_umin(unsigned v) {
+    v = umin(v, zb_dpp<0xB1>(~0u, v));                            // quad_perm [1,0,3,2]: lane ^ 1
+    v = umin(v, zb_dpp<0x4E>(~0u, v));                            // quad_perm [2,3,0,1]: lane ^ 2
+    v = umin(v, zb_dpp<0x141>(~0u, v));                           // row_half_mirror: the two quads of 8 lanes
+    if (G == 16) v = umin(v, zb_dpp<0x140>(~0u, v));              // row_mirror: the two halves of a row
+    return v;
+}
+
+template <int G>
+__global__ __launch_bounds__(kZbBlock) void k_zb_record_stages(ZbArgs a) {
+    static_assert(G == 8 || G == 16, "a group of lanes is half a DPP row or a whole one");
+    extern __shared__ int zb_lds[];
+    constexpr unsigned kNever = ~0u;                              // as a ready time: nothing of that type is available
+    const int S = a.S, N = a.N, lane = threadIdx.x;
+    const int i = lane % G;                                       // this lane's stage (none if i >= S)
+    const long long c_lane = (long long)blockIdx.x * (kZbBlock / G) + lane / G;
+    const bool exists = c_lane < a.C && i < S;
+    const long long c = c_lane < a.C ? c_lane : a.C - 1;
+    const int is = i < S ? i : S - 1;
+    const bool first = i == 0, last = i == S - 1, posts_f = i < S - 1, posts_b = i > 0 && i < S;
+    const long long k = a.plan_scenario;
+    const int t_f = a.t_f[is], t_b = a.t_b[is], t_w = a.t_w[is];
+    const int delay_f = posts_f ? a.cf[(long long)is * a.K + k] : 0;         // link i -> i + 1
+    const int delay_b = posts_b ? a.cb[(long long)(is - 1) * a.K + k] : 0;   // link i - 1 <- i
+    int wi = a.w[(long long)is * a.C + c];
+    wi = wi < 0 ? 0 : (wi > N - 1 ? N - 1 : wi);
+    const int x = wi + 1;                                         // warm-up quota
+    // look-ahead of the candidate; any smaller value is valid too, and 2^30 keeps t + L in 32 bits
+    const unsigned own_f = posts_f ? (unsigned)t_f + (unsigned)delay_f : kNever;
+    const unsigned own_b = posts_b ? (unsigned)t_b + (unsigned)delay_b : kNever;
+    const unsigned look = umin(zb_group_umin<G>(umin(own_f, own_b)), 1u << 30);
+    int *const qF = zb_lds + lane;                                // [N][64]: ready time of forward m of this stage
+    int *const qB = qF + N * 64;                                  // [N][64]: of backward m
+    uint8_t *const plan = a.plans + (c * S + is) * 3ll * N;       // this stage's op types
+    // Ops started per type; ready times received so far; the ready time of the next forward and
+    // backward, kNever while none is available.  Stage 0's forwards are all ready at time 0; the
+    // last stage's backwards follow its own forwards (ready while it is still busy with them).
+    int nF = 0, nB = 0, nW = 0, recvF = 0, recvB = 0, busy = 0;
+    unsigned headF = first && i < S ? 0u : kNever, headB = kNever;
+    auto next_key = [&]() {
+        const unsigned headW = nW < nB ? 0u : kNever;             // ready since its backward finished
+        const unsigned soonest = nF < x ? headF : umin(headB, umin(headF, headW));   // warm-up: forwards only
+        return soonest > (unsigned)busy ? soonest : (unsigned)busy;                  // kNever stays kNever
+    };
+    unsigned key = next_key();
+    int recorded = 0;                                             // ops of this candidate written to the order so far
+    const int total = 3 * S * N;
+    const int group_shift = lane & ~(G - 1) & 31;
+    const unsigned below_me = (1u << i) - 1, group_bits = (1u << G) - 1;
+    for (int step = 0; step < total; ++step) {
+        const unsigned t = zb_group_umin<G>(key);                 // the candidate's earliest next action
+        if (__ballot(t != kNever) == 0) break;                    // every candidate of the wavefront is through (or stuck)
+        const bool act = key != kNever && key - t < look;         // final: nothing unposted is ready before t + look
+        const int ty = nF < x ? 0 : (headB <= key ? 1 : (headF <= key ? 0 : 2));     // B > F > W among those ready
+        const int m = ty == 0 ? nF : (ty == 1 ? nB : nW);
+        const int fin = (int)key + (ty == 0 ? t_f : (ty == 1 ? t_b : t_w));
+        // position in the order: the candidate's ops of this step in stage order
+        const unsigned long long acting = __ballot(act);
+        const unsigned in_group = ((unsigned)(lane < 32 ? acting : acting >> 32) >> group_shift) & group_bits;
+        if (act) {
+            if (exists) {
+                plan[nF + nB + nW] = (uint8_t)ty;
+                if (a.order)
+                    a.order[c * a.order_stride + recorded + __popc(in_group & below_me)] =
+                        (uint16_t)(i | ty << 6 | (ty == 2 ? N : m) << 8);
+            }
+            busy = fin;
+            nF += ty == 0; nB += ty == 1; nW += ty == 2;
+            // the op's own queue moves on to its next entry, if that has been posted
+            if (ty == 0) headF = first ? (nF < N ? 0u : kNever) : (nF < recvF ? (unsigned)qF[nF * 64] : kNever);
+            if (ty == 1 && !last) headB = nB < recvB ? (unsigned)qB[nB * 64] : kNever;
+            if (last) headB = nB < nF ? 0u : kNever;
+        }
+        recorded += __popc(in_group);
+        // what the op makes available next door: F(i,m) -> F(i+1,m), B(i,m) -> B(i-1,m)
+        const unsigned post_f = act && ty == 0 ? (unsigned)(fin + delay_f) : kNever;
+        const unsigned post_b = act && ty == 1 ? (unsigned)(fin + delay_b) : kNever;
+        unsigned got_f = zb_dpp<0x111>(kNever, post_f);           // row_shr:1, from the lane of stage i - 1
+        unsigned got_b = zb_dpp<0x101>(kNever, post_b);           // row_shl:1, from the lane of stage i + 1
+        if (first || i >= S) got_f = kNever;                      // that lane belongs to another candidate
+        if (i >= S - 1) got_b = kNever;
+        if (got_f != kNever) {
+            qF[recvF * 64] = (int)got_f;
+            if (headF == kNever) headF = got_f;                   // the queue was empty: nF == recvF
+            ++recvF;
+        }
+        if (got_b != kNever) {
+            qB[recvB * 64] = (int)got_b;
+            if (headB == kNever) headB = got_b;
+            ++recvB;
+        }
+        key = next_key();
+    }
+    if (a.order && first && c_lane < a.C) a.plan_ok[c] = recorded == total;
+}
+
 // Plans from one byte per op, [C][S][3N], to 2 bits per op, 16 ops per word from op 8 q on, kNone
 // behind the end of a stage's ops, laid out [chunk of 64 candidates][S][word][candidate].
 __global__ void k_zb_pack(const uint8_t *plans, uint32_t *packed, long long C, int S, int N) {
@@ -477,6 +594,8 @@ __global__ void k_zb_check_reset(int *found) {
 struct ZbPlan {
     bool narrow;                  // generation (PHASE 0, 1) in the one-word form of the cursors
     bool scen_lanes;              // replay with the scenarios on the lanes (k_zb_replay_scen)
+    int record_group;             // lanes per candidate of the recording with the stages on the lanes (0: a lane per candidate)
+    size_t lds_record;
     unsigned threads, threads_replay;
     long long order_stride;
     size_t lds, lds_replay, lds_scen, off_counters, off_scratch, off_plans, off_packed, off_order, off_plan_ok, total;
@@ -519,6 +638,16 @@ bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
     p->lds_scen = (((size_t)4 * S + (size_t)N + 1) * 64 + 3 * (size_t)S) * 4;
     p->scen_lanes = K >= kScenReplayFrom && N <= 255 && p->lds_scen <= (160u << 10) &&
                     ((C + kXcds - 1) / kXcds) * kXcds * ((K + kZbBlock - 1) / kZbBlock) <= INT32_MAX;
+    // The recording with the stages on the lanes is the quicker one while all its wavefronts
+    // are resident at once (its queues, 2 N rows of 64 lanes, are what limits that).
+    p->record_group = S <= 8 ? 8 : (S <= 16 ? 16 : 0);
+    p->lds_record = (size_t)2 * N * kZbBlock * 4;
+    if (p->record_group) {
+        const long long blocks = (C * p->record_group + kZbBlock - 1) / kZbBlock;
+        long long per_cu = p->lds_record <= (160u << 10) ? (long long)((160u << 10) / p->lds_record) : 0;
+        if (per_cu > 32) per_cu = 32;
+        if (blocks > kCus * per_cu) p->record_group = 0;
+    }
     p->off_order = o;   o += adaptra_detail::align256(p->scen_lanes ? (size_t)C * (size_t)p->order_stride * 2 : 0);
     p->off_plan_ok = o; o += adaptra_detail::align256(p->scen_lanes ? (size_t)C : 0);
     p->total = o;
@@ -614,7 +743,18 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
     const size_t lds_queues = p.lds + (size_t)2 * a.S * a.N * kZbBlock * 4;
     const bool queues_in_lds = (a.C + kZbBlock - 1) / kZbBlock <= kCus && lds_queues <= (160u << 10);
     int rc;
-    if (queues_in_lds)
+    if (p.record_group) {
+        if (p.lds_record > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute(p.record_group == 8 ? (const void *)k_zb_record_stages<8> : (const void *)k_zb_record_stages<16>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_record);
+            if (e != hipSuccess) return adaptra_detail::hip_fail(e);
+        }
+        const unsigned blocks = (unsigned)((a.C * p.record_group + kZbBlock - 1) / kZbBlock);
+        if (p.record_group == 8) hipLaunchKernelGGL(k_zb_record_stages<8>, dim3(blocks), dim3(kZbBlock), p.lds_record, st, a);
+        else hipLaunchKernelGGL(k_zb_record_stages<16>, dim3(blocks), dim3(kZbBlock), p.lds_record, st, a);
+        ADAPTRA_CHECK_LAUNCH();
+        rc = ADAPTRA_OK;
+    } else if (queues_in_lds)
         rc = p.narrow ? launch_zb<1, true, true>(a, 1, kCus * kZbBlock, lds_queues, st) : launch_zb<1, false, true>(a, 1, kCus * kZbBlock, lds_queues, st);
     else
         rc = p.narrow ? launch_zb<1, true>(a, 1, p.threads, p.lds, st) : launch_zb<1, false>(a, 1, p.threads, p.lds, st);
