@@ -117,6 +117,12 @@ struct ZbArgs {
     uint16_t *order;              // [C][order_stride] or null: stage | type << 6 | slot << 8 of every op in the order
                                   // PHASE 1 started them -- a topological order of the plan's dependency graph; slot
                                   // = micro-batch, N for a weight op (k_zb_replay_scen; N <= 255)
+    uint4 *order_folded;          // [C][order_stride] or null: the same order without the weight ops, written by
+                                  // k_zb_record_stages for k_zb_replay_folded, every field ready for use: .x = 256 stage
+                                  // | 256 (type S + stage) << 16 of a forward or backward op, .y = the time the stage
+                                  // spent on weight ops since its last forward or backward op (they run back to back
+                                  // from the moment it is free), .z = the op's duration, .w = 256 micro-batch
+    int *tail_w;                  // [C][S]: the time of a stage's weight ops behind its last backward op
     uint8_t *plan_ok;             // [C]: the recording ran to its end
     long long order_stride;       // entries per candidate, a multiple of 16
     unsigned threads;             // of the launch = stride of the queues
@@ -387,7 +393,8 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_record_stages(ZbArgs a) {
         return soonest > (unsigned)busy ? soonest : (unsigned)busy;                  // kNever stays kNever
     };
     unsigned key = next_key();
-    int recorded = 0;                                             // ops of this candidate written to the order so far
+    int recorded = 0;                                             // forward and backward ops of this candidate written to the order so far
+    int weight_time = 0;                                          // spent on weight ops since this stage's last forward or backward op
     const int total = 3 * S * N;
     const int group_shift = lane & ~(G - 1) & 31;
     const unsigned below_me = (1u << i) - 1, group_bits = (1u << G) - 1;
@@ -396,18 +403,23 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_record_stages(ZbArgs a) {
         if (__ballot(t != kNever) == 0) break;                    // every candidate of the wavefront is through (or stuck)
         const bool act = key != kNever && key - t < look;         // final: nothing unposted is ready before t + look
         const int ty = nF < x ? 0 : (headB <= key ? 1 : (headF <= key ? 0 : 2));     // B > F > W among those ready
-        const int m = ty == 0 ? nF : (ty == 1 ? nB : nW);
+        const int m = ty == 0 ? nF : nB;                          // of a forward or backward op
         const int fin = (int)key + (ty == 0 ? t_f : (ty == 1 ? t_b : t_w));
-        // position in the order: the candidate's ops of this step in stage order
-        const unsigned long long acting = __ballot(act);
+        // position in the order: the candidate's forward and backward ops of this step in stage
+        // order.  Weight ops get no entry: a weight op starts the moment its stage is free (its
+        // backward op ran on the same stage before), so all a replay has to know is how long the
+        // stage spent on them before its next forward or backward op.
+        const unsigned long long acting = __ballot(act && ty < 2);
         const unsigned in_group = ((unsigned)(lane < 32 ? acting : acting >> 32) >> group_shift) & group_bits;
         if (act) {
             if (exists) {
                 plan[nF + nB + nW] = (uint8_t)ty;
-                if (a.order)
-                    a.order[c * a.order_stride + recorded + __popc(in_group & below_me)] =
-                        (uint16_t)(i | ty << 6 | (ty == 2 ? N : m) << 8);
+                if (a.order_folded && ty < 2)
+                    a.order_folded[c * a.order_stride + recorded + __popc(in_group & below_me)] =
+                        make_uint4((unsigned)(i << 8 | (ty * S + i) << 24), (unsigned)weight_time,
+                                   (unsigned)(ty == 0 ? t_f : t_b), (unsigned)(m << 8));
             }
+            weight_time = ty == 2 ? weight_time + t_w : 0;
             busy = fin;
             nF += ty == 0; nB += ty == 1; nW += ty == 2;
             // the op's own queue moves on to its next entry, if that has been posted
@@ -435,7 +447,12 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_record_stages(ZbArgs a) {
         }
         key = next_key();
     }
-    if (a.order && first && c_lane < a.C) a.plan_ok[c] = recorded == total;
+    if (a.order_folded) {
+        const unsigned long long unfinished = __ballot(i < S && !(nF == N && nB == N && nW == N));
+        const unsigned in_group = ((unsigned)(lane < 32 ? unfinished : unfinished >> 32) >> group_shift) & group_bits;
+        if (exists) a.tail_w[c * S + i] = weight_time;
+        if (first && c_lane < a.C) a.plan_ok[c] = in_group == 0;
+    }
 }
 
 // Plans from one byte per op, [C][S][3N], to 2 bits per op, 16 ops per word from op 8 q on, kNone
@@ -554,6 +571,95 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_replay_scen(ZbArgs a) {
     }
 }
 
+// The same replay on an order without weight ops (ZbArgs::order_folded).  W(i,m) depends on
+// B(i,m) alone, which ran on the same stage before it, so a weight op starts the moment its stage
+// is free and only pushes the stage's busy-until time; the recording has added up what a stage
+// spends on weight ops between two of its other ops (the same in every scenario), and the op after
+// them is  fin = max(busy[i] + weight time, ready[m]) + duration.  A third fewer ops, no slot and
+// no delay row for weight ops; the makespan is the latest busy-until time, the weight ops behind
+// a stage's last backward op (ZbArgs::tail_w) included.
+__global__ __launch_bounds__(kZbBlock) void k_zb_replay_folded(ZbArgs a) {
+    extern __shared__ int zb_lds[];
+    const int S = a.S, N = a.N, lane = threadIdx.x;
+    int *const busy = zb_lds + lane;                  // [S][64]
+    int *const ready = busy + S * 64;                 // [N][64]
+    int *const delay = ready + N * 64;                // [2][S][64]: link i -> i+1, link i-1 <- i
+    int *const dur = zb_lds + (3 * S + N) * 64;       // [3][S]: t_f, t_b, t_w
+    // block -> (candidate, tile of 64 scenarios) as in k_zb_replay_scen
+    const long long n_tiles = (a.K + kZbBlock - 1) / kZbBlock;
+    const long long per_xcd = (a.C + kXcds - 1) / kXcds;
+    const long long in_xcd = blockIdx.x / kXcds;
+    const long long c = (blockIdx.x % kXcds) * per_xcd + in_xcd / n_tiles;
+    if (in_xcd / n_tiles >= per_xcd || c >= a.C) return;
+    const long long k_lane = (in_xcd % n_tiles) * kZbBlock + lane;
+    const bool live = k_lane < a.K;
+    const long long k = live ? k_lane : a.K - 1;
+    for (int i = lane; i < 3 * S; i += kZbBlock) dur[i] = i < S ? a.t_f[i] : (i < 2 * S ? a.t_b[i - S] : a.t_w[i - 2 * S]);
+    for (int i = 0; i < S; ++i) {
+        busy[i * 64] = 0;
+        delay[i * 64] = i < S - 1 ? a.cf[(long long)i * a.K + k] : 0;
+        delay[(S + i) * 64] = i > 0 ? a.cb[(long long)(i - 1) * a.K + k] : 0;
+    }
+    for (int m = 0; m < N; ++m) ready[m * 64] = 0;
+    __syncthreads();
+    typedef const __attribute__((address_space(4))) unsigned *ScalarWords;
+    // Everything uniform comes out of the entry ready for use: the byte offsets of the three rows
+    // ([index][lane] ints: 256 bytes a row) and the two times, which are scalar operands of the adds.
+    auto at = [](int *rows, unsigned bytes) { return reinterpret_cast<int *>(reinterpret_cast<char *>(rows) + bytes); };
+    auto run = [&](unsigned offsets, unsigned weight_time, unsigned length, unsigned m256) {
+        int *const busy_i = at(busy, offsets & 0xffffu), *const ready_m = at(ready, m256);
+        const int b = *busy_i + (int)weight_time, r = *ready_m, d = *at(delay, offsets >> 16);
+        const int fin = imax2(b, r) + (int)length;
+        *busy_i = fin;
+        *ready_m = fin + d;
+    };
+    struct Four { unsigned word[16]; };               // four entries
+    auto run4 = [&](const Four &e) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) run(e.word[4 * j], e.word[4 * j + 1], e.word[4 * j + 2], e.word[4 * j + 3]);
+    };
+    auto load4 = [&](Four &e, ScalarWords from) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) e.word[j] = from[j];
+    };
+    // The candidate is the block's: the address of its row goes through scalar registers and is
+    // read as constant memory (written by the launch before this one), so that the entries come
+    // by scalar loads with scalar address arithmetic.
+    const unsigned long long row_address = (unsigned long long)(a.order_folded + c * a.order_stride);
+    const ScalarWords order = (ScalarWords)(
+        (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)row_address) |
+        (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(row_address >> 32)) << 32);
+    const int total = 2 * S * N;
+    const bool recorded = __builtin_amdgcn_readfirstlane((int)a.plan_ok[c]) != 0;   // else the entries are not a plan: nothing is run
+    // 16 entries per round in four groups; a group's entries are fetched two groups before they
+    // run, without copies between the buffers
+    Four e0, e1, e2, e3;
+    int base = recorded ? 0 : total;
+    load4(e0, order);
+    load4(e1, order + 16);
+    for (; base + 16 <= total; base += 16) {
+        load4(e2, order + 4 * (base + 8));
+        load4(e3, order + 4 * (base + 12));
+        run4(e0);
+        run4(e1);
+        load4(e0, order + 4 * (base + 16));           // still inside the candidate's padded row
+        load4(e1, order + 4 * (base + 20));
+        run4(e2);
+        run4(e3);
+    }
+    for (; base < total; ++base) run(order[4 * base], order[4 * base + 1], order[4 * base + 2], order[4 * base + 3]);
+    int makespan = 0;
+    for (int i = 0; i < S; ++i) makespan = imax2(makespan, busy[i * 64] + a.tail_w[c * S + i]);
+    if (!recorded) makespan = kInf;                   // the recording stopped: so does every replay of it
+    if (live) {
+        const long long P = a.C * a.K, item = k * a.C + c;
+        a.out_makespan[item] = makespan;
+        if (a.out_bubble)
+            for (int i = 0; i < S; ++i)
+                a.out_bubble[(long long)i * P + item] = makespan == kInf ? kInf : makespan - N * (dur[i] + dur[S + i] + dur[2 * S + i]);
+    }
+}
+
 __global__ void k_zb_reset(unsigned long long *counters) {
     if (threadIdx.x < 2) counters[threadIdx.x] = 0;
 }
@@ -598,6 +704,8 @@ struct ZbPlan {
     size_t lds_record;
     unsigned threads, threads_replay;
     long long order_stride;
+    bool folded;                  // recording with the stages on the lanes + replay without weight ops
+    size_t lds_folded, off_tail;
     size_t lds, lds_replay, lds_scen, off_counters, off_scratch, off_plans, off_packed, off_order, off_plan_ok, total;
 };
 
@@ -648,7 +756,11 @@ bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
         if (per_cu > 32) per_cu = 32;
         if (blocks > kCus * per_cu) p->record_group = 0;
     }
-    p->off_order = o;   o += adaptra_detail::align256(p->scen_lanes ? (size_t)C * (size_t)p->order_stride * 2 : 0);
+    p->folded = p->scen_lanes && p->record_group != 0;
+    p->lds_folded = (((size_t)3 * S + (size_t)N) * 64 + 3 * (size_t)S) * 4;
+    if (p->folded) p->order_stride = (2ll * S * N + 15) / 16 * 16 + 8;         // the loads run eight entries ahead
+    p->off_order = o;   o += adaptra_detail::align256(p->scen_lanes ? (size_t)C * (size_t)p->order_stride * (p->folded ? 16 : 2) : 0);
+    p->off_tail = o;    o += adaptra_detail::align256(p->folded ? (size_t)C * S * 4 : 0);
     p->off_plan_ok = o; o += adaptra_detail::align256(p->scen_lanes ? (size_t)C : 0);
     p->total = o;
     return true;
@@ -732,7 +844,9 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
     unsigned long long *counters = (unsigned long long *)((char *)workspace + p.off_counters);
     hipLaunchKernelGGL(k_zb_reset, dim3(1), dim3(64), 0, st, counters);
     ADAPTRA_CHECK_LAUNCH();
-    a.order = p.scen_lanes && plan_scenario >= 0 ? (uint16_t *)((char *)workspace + p.off_order) : nullptr;
+    a.order = p.scen_lanes && !p.folded && plan_scenario >= 0 ? (uint16_t *)((char *)workspace + p.off_order) : nullptr;
+    a.order_folded = p.folded && plan_scenario >= 0 ? (uint4 *)((char *)workspace + p.off_order) : nullptr;
+    a.tail_w = (int *)((char *)workspace + p.off_tail);
     a.plan_ok = (uint8_t *)workspace + p.off_plan_ok;
     a.order_stride = p.order_stride;
     a.next_unit = counters;
@@ -759,6 +873,16 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
     else
         rc = p.narrow ? launch_zb<1, true>(a, 1, p.threads, p.lds, st) : launch_zb<1, false>(a, 1, p.threads, p.lds, st);
     if (rc) return rc;
+    if (p.folded) {
+        if (p.lds_folded > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute((const void *)k_zb_replay_folded, hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_folded);
+            if (e != hipSuccess) return adaptra_detail::hip_fail(e);
+        }
+        const long long blocks = (a.C + kXcds - 1) / kXcds * kXcds * ((a.K + kZbBlock - 1) / kZbBlock);
+        hipLaunchKernelGGL(k_zb_replay_folded, dim3((unsigned)blocks), dim3(kZbBlock), p.lds_folded, st, a);
+        ADAPTRA_CHECK_LAUNCH();
+        return ADAPTRA_OK;
+    }
     if (p.scen_lanes) {
         if (p.lds_scen > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute((const void *)k_zb_replay_scen, hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_scen);
