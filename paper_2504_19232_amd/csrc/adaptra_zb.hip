@@ -577,14 +577,19 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_replay_scen(ZbArgs a) {
 // spends on weight ops between two of its other ops (the same in every scenario), and the op after
 // them is  fin = max(busy[i] + weight time, ready[m]) + duration.  A third fewer ops, no slot and
 // no delay row for weight ops; the makespan is the latest busy-until time, the weight ops behind
-// a stage's last backward op (ZbArgs::tail_w) included.
+// a stage's last backward op (ZbArgs::tail_w) included.  This replay only follows a recording by
+// k_zb_record_stages, i.e. at most 16 stages: a lane's 2 S link delays then fit 32 registers,
+// which the compiler indexes with the op's (uniform) row number, and LDS holds only the rows
+// that are written: S + N of them (0.28 -> 0.24 ms on 2^20 pairs against all rows in LDS; the
+// busy-until times in registers as well would exceed the 32 registers the compiler keeps
+// indexable and go to scratch memory).
 __global__ __launch_bounds__(kZbBlock) void k_zb_replay_folded(ZbArgs a) {
     extern __shared__ int zb_lds[];
     const int S = a.S, N = a.N, lane = threadIdx.x;
     int *const busy = zb_lds + lane;                  // [S][64]
     int *const ready = busy + S * 64;                 // [N][64]
-    int *const delay = ready + N * 64;                // [2][S][64]: link i -> i+1, link i-1 <- i
-    int *const dur = zb_lds + (3 * S + N) * 64;       // [3][S]: t_f, t_b, t_w
+    int *const dur = zb_lds + (S + N) * 64;           // [3][S]: t_f, t_b, t_w
+    int delay_r[32];                                  // link i -> i+1 at i, link i-1 <- i at S + i; set below under static indices
     // block -> (candidate, tile of 64 scenarios) as in k_zb_replay_scen
     const long long n_tiles = (a.K + kZbBlock - 1) / kZbBlock;
     const long long per_xcd = (a.C + kXcds - 1) / kXcds;
@@ -595,10 +600,13 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_replay_folded(ZbArgs a) {
     const bool live = k_lane < a.K;
     const long long k = live ? k_lane : a.K - 1;
     for (int i = lane; i < 3 * S; i += kZbBlock) dur[i] = i < S ? a.t_f[i] : (i < 2 * S ? a.t_b[i - S] : a.t_w[i - 2 * S]);
-    for (int i = 0; i < S; ++i) {
-        busy[i * 64] = 0;
-        delay[i * 64] = i < S - 1 ? a.cf[(long long)i * a.K + k] : 0;
-        delay[(S + i) * 64] = i > 0 ? a.cb[(long long)(i - 1) * a.K + k] : 0;
+    for (int i = 0; i < S; ++i) busy[i * 64] = 0;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+        int d = 0;
+        if (j < S - 1) d = a.cf[(long long)j * a.K + k];
+        else if (j > S && j < 2 * S) d = a.cb[(long long)(j - S - 1) * a.K + k];
+        delay_r[j] = d;
     }
     for (int m = 0; m < N; ++m) ready[m * 64] = 0;
     __syncthreads();
@@ -606,8 +614,9 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_replay_folded(ZbArgs a) {
     // ([index][lane] ints: 256 bytes a row) and the two times, which are scalar operands of the adds.
     auto at = [](int *rows, unsigned bytes) { return reinterpret_cast<int *>(reinterpret_cast<char *>(rows) + bytes); };
     auto run = [&](unsigned offsets, unsigned weight_time, unsigned length, unsigned m256) {
+        const int row = (int)(offsets >> 24);
         int *const busy_i = at(busy, offsets & 0xffffu), *const ready_m = at(ready, m256);
-        const int b = *busy_i + (int)weight_time, r = *ready_m, d = *at(delay, offsets >> 16);
+        const int b = *busy_i + (int)weight_time, r = *ready_m, d = delay_r[row];
         const int fin = imax2(b, r) + (int)length;
         *busy_i = fin;
         *ready_m = fin + d;
@@ -742,7 +751,7 @@ bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
         if (blocks > kCus * per_cu) p->record_group = 0;
     }
     p->folded = p->scen_lanes && p->record_group != 0;
-    p->lds_folded = (((size_t)3 * S + (size_t)N) * 64 + 3 * (size_t)S) * 4;
+    p->lds_folded = (((size_t)S + (size_t)N) * 64 + 3 * (size_t)S) * 4;
     if (p->folded) p->order_stride = (2ll * S * N + 63) / 64 * 64 + 64;        // the loads run 64 entries ahead
     p->off_order = o;   o += adaptra_detail::align256(p->scen_lanes ? (size_t)C * (size_t)p->order_stride * (p->folded ? 16 : 2) : 0);
     p->off_tail = o;    o += adaptra_detail::align256(p->folded ? (size_t)C * S * 4 : 0);
