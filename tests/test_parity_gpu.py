@@ -577,7 +577,12 @@ ZB_CASES = [(1, 1, 1, 3, 2), (2, 2, 3, 9, 5), (3, 4, 8, 40, 21), (4, 8, 16, 70, 
             (15, 19, 9, 30, 5, 40),       # 19 stages pad to 24: a stage-index field wider than needed
             # fixed plans are replayed with the scenarios on the lanes from 8 scenarios on, up to 255 micro-batches
             (16, 2, 255, 20, 9), (17, 3, 256, 12, 9), (18, 5, 40, 9, 8), (19, 5, 40, 9, 7),
-            (20, 64, 255, 3, 8)]          # the largest per-wavefront state of that replay (129 KiB of LDS)
+            (20, 64, 255, 3, 8),          # the largest per-wavefront state of that replay (129 KiB of LDS)
+            # up to 16 stages plans are recorded with the stages on the lanes (groups of 8 or 16 lanes) and
+            # replayed without weight ops: 11 stages in groups of 16, two tiles of scenarios, several blocks of
+            # candidates, an order whose length is no multiple of the replay's 64-entry blocks; 7 stages likewise
+            (21, 11, 20, 300, 70), (22, 7, 33, 130, 9), (23, 16, 31, 40, 64),
+            (24, 8, 255, 9, 8)]           # that recording's largest queues (one wavefront per CU)
 
 
 @pytest.mark.parametrize("case", ZB_CASES, ids=["S%d_N%d_C%d_K%d" % c[1:5] + ("_x%d" % c[5] if len(c) > 5 else "") for c in ZB_CASES])
