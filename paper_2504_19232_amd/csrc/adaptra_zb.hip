@@ -352,13 +352,34 @@ __device__ __forceinline__ unsigned zb_group_umin(unsigned v) {
     v = umin(v, zb_dpp<0xB1>(~0u, v));                            // quad_perm [1,0,3,2]: lane ^ 1
     v = umin(v, zb_dpp<0x4E>(~0u, v));                            // quad_perm [2,3,0,1]: lane ^ 2
     v = umin(v, zb_dpp<0x141>(~0u, v));                           // row_half_mirror: the two quads of 8 lanes
-    if (G == 16) v = umin(v, zb_dpp<0x140>(~0u, v));              // row_mirror: the two halves of a row
+    if (G >= 16) v = umin(v, zb_dpp<0x140>(~0u, v));              // row_mirror: the two halves of a row
+    if (G >= 32) v = umin(v, (unsigned)__builtin_amdgcn_ds_swizzle((int)v, 0x401F));                           // lane ^ 16
+    if (G == 64) v = umin(v, (unsigned)__builtin_amdgcn_ds_bpermute((int)((threadIdx.x ^ 32) << 2), (int)v));  // lane ^ 32
     return v;
 }
-
+// v of the lane before / after this one (another row of 16 lanes from 32-lane groups on: through
+// the LDS crossbar); `none` where a DPP row ends -- the caller drops what crosses a group's end anyway
 template <int G>
+__device__ __forceinline__ unsigned zb_from_previous_lane(unsigned v, unsigned none) {
+    if (G <= 16) return zb_dpp<0x111>(none, v);                   // row_shr:1
+    return (unsigned)__builtin_amdgcn_ds_bpermute((int)(((threadIdx.x - 1) & 63) << 2), (int)v);
+}
+template <int G>
+__device__ __forceinline__ unsigned zb_from_next_lane(unsigned v, unsigned none) {
+    if (G <= 16) return zb_dpp<0x101>(none, v);                   // row_shl:1
+    return (unsigned)__builtin_amdgcn_ds_bpermute((int)(((threadIdx.x + 1) & 63) << 2), (int)v);
+}
+// the bits of a wavefront-wide vote that belong to this lane's group of G lanes, lowest stage first
+template <int G>
+__device__ __forceinline__ unsigned long long zb_group_bits(unsigned long long vote) {
+    if (G == 64) return vote;
+    const unsigned half = (unsigned)(threadIdx.x < 32 ? vote : vote >> 32);
+    return (half >> (threadIdx.x & ~(G - 1) & 31)) & (G == 32 ? ~0u : (1u << (G & 31)) - 1);
+}
+
+template <int G, bool FOLDED>
 __global__ __launch_bounds__(kZbBlock) void k_zb_record_stages(ZbArgs a) {
-    static_assert(G == 8 || G == 16, "a group of lanes is half a DPP row or a whole one");
+    static_assert(G == 8 || G == 16 || G == 32 || G == 64, "a group of lanes is half a DPP row, a row, two or all four");
     extern __shared__ int zb_lds[];
     constexpr unsigned kNever = ~0u;                              // as a ready time: nothing of that type is available
     const int S = a.S, N = a.N, lane = threadIdx.x;
@@ -393,31 +414,33 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_record_stages(ZbArgs a) {
         return soonest > (unsigned)busy ? soonest : (unsigned)busy;                  // kNever stays kNever
     };
     unsigned key = next_key();
-    int recorded = 0;                                             // forward and backward ops of this candidate written to the order so far
+    int recorded = 0;                                             // ops of this candidate written to the order so far (FOLDED: forward and backward ops)
     int weight_time = 0;                                          // spent on weight ops since this stage's last forward or backward op
     const int total = 3 * S * N;
-    const int group_shift = lane & ~(G - 1) & 31;
-    const unsigned below_me = (1u << i) - 1, group_bits = (1u << G) - 1;
+    const unsigned long long below_me = (1ull << i) - 1;
     for (int step = 0; step < total; ++step) {
         const unsigned t = zb_group_umin<G>(key);                 // the candidate's earliest next action
         if (__ballot(t != kNever) == 0) break;                    // every candidate of the wavefront is through (or stuck)
         const bool act = key != kNever && key - t < look;         // final: nothing unposted is ready before t + look
         const int ty = nF < x ? 0 : (headB <= key ? 1 : (headF <= key ? 0 : 2));     // B > F > W among those ready
-        const int m = ty == 0 ? nF : nB;                          // of a forward or backward op
+        const int m = ty == 0 ? nF : (ty == 1 ? nB : nW);
         const int fin = (int)key + (ty == 0 ? t_f : (ty == 1 ? t_b : t_w));
-        // position in the order: the candidate's forward and backward ops of this step in stage
-        // order.  Weight ops get no entry: a weight op starts the moment its stage is free (its
+        // Position in the order: the candidate's ops of this step in stage order.  In the FOLDED
+        // order weight ops get no entry: a weight op starts the moment its stage is free (its
         // backward op ran on the same stage before), so all a replay has to know is how long the
         // stage spent on them before its next forward or backward op.
-        const unsigned long long acting = __ballot(act && ty < 2);
-        const unsigned in_group = ((unsigned)(lane < 32 ? acting : acting >> 32) >> group_shift) & group_bits;
+        const unsigned long long in_group = zb_group_bits<G>(__ballot(act && (!FOLDED || ty < 2)));
         if (act) {
             if (exists) {
                 plan[nF + nB + nW] = (uint8_t)ty;
-                if (a.order_folded && ty < 2)
-                    a.order_folded[c * a.order_stride + recorded + __popc(in_group & below_me)] =
-                        make_uint4((unsigned)(i << 8 | (ty * S + i) << 24), (unsigned)weight_time,
-                                   (unsigned)(ty == 0 ? t_f : t_b), (unsigned)(m << 8));
+                const long long at = c * a.order_stride + recorded + __popcll(in_group & below_me);
+                if (FOLDED) {
+                    if (a.order_folded && ty < 2)
+                        a.order_folded[at] = make_uint4((unsigned)(i << 8 | (ty * S + i) << 24), (unsigned)weight_time,
+                                                        (unsigned)(ty == 0 ? t_f : t_b), (unsigned)(m << 8));
+                } else if (a.order) {
+                    a.order[at] = (uint16_t)(i | ty << 6 | (ty == 2 ? N : m) << 8);
+                }
             }
             weight_time = ty == 2 ? weight_time + t_w : 0;
             busy = fin;
@@ -427,12 +450,12 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_record_stages(ZbArgs a) {
             if (ty == 1 && !last) headB = nB < recvB ? (unsigned)qB[nB * 64] : kNever;
             if (last) headB = nB < nF ? 0u : kNever;
         }
-        recorded += __popc(in_group);
+        recorded += __popcll(in_group);
         // what the op makes available next door: F(i,m) -> F(i+1,m), B(i,m) -> B(i-1,m)
         const unsigned post_f = act && ty == 0 ? (unsigned)(fin + delay_f) : kNever;
         const unsigned post_b = act && ty == 1 ? (unsigned)(fin + delay_b) : kNever;
-        unsigned got_f = zb_dpp<0x111>(kNever, post_f);           // row_shr:1, from the lane of stage i - 1
-        unsigned got_b = zb_dpp<0x101>(kNever, post_b);           // row_shl:1, from the lane of stage i + 1
+        unsigned got_f = zb_from_previous_lane<G>(post_f, kNever);   // from the lane of stage i - 1
+        unsigned got_b = zb_from_next_lane<G>(post_b, kNever);       // from the lane of stage i + 1
         if (first || i >= S) got_f = kNever;                      // that lane belongs to another candidate
         if (i >= S - 1) got_b = kNever;
         if (got_f != kNever) {
@@ -447,11 +470,10 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_record_stages(ZbArgs a) {
         }
         key = next_key();
     }
-    if (a.order_folded) {
-        const unsigned long long unfinished = __ballot(i < S && !(nF == N && nB == N && nW == N));
-        const unsigned in_group = ((unsigned)(lane < 32 ? unfinished : unfinished >> 32) >> group_shift) & group_bits;
-        if (exists) a.tail_w[c * S + i] = weight_time;
-        if (first && c_lane < a.C) a.plan_ok[c] = in_group == 0;
+    if (FOLDED ? a.order_folded != nullptr : a.order != nullptr) {
+        const unsigned long long unfinished = zb_group_bits<G>(__ballot(i < S && !(nF == N && nB == N && nW == N)));
+        if (FOLDED && exists) a.tail_w[c * S + i] = weight_time;
+        if (first && c_lane < a.C) a.plan_ok[c] = unfinished == 0;
     }
 }
 
@@ -742,7 +764,7 @@ bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
                     ((C + kXcds - 1) / kXcds) * kXcds * ((K + kZbBlock - 1) / kZbBlock) <= INT32_MAX;
     // The recording with the stages on the lanes is the quicker one while all its wavefronts
     // are resident at once (its queues, 2 N rows of 64 lanes, are what limits that).
-    p->record_group = S <= 8 ? 8 : (S <= 16 ? 16 : 0);
+    p->record_group = S <= 8 ? 8 : (S <= 16 ? 16 : (S <= 32 ? 32 : 64));
     p->lds_record = (size_t)2 * N * kZbBlock * 4;
     if (p->record_group) {
         const long long blocks = (C * p->record_group + kZbBlock - 1) / kZbBlock;
@@ -750,7 +772,7 @@ bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
         if (per_cu > 32) per_cu = 32;
         if (blocks > kCus * per_cu) p->record_group = 0;
     }
-    p->folded = p->scen_lanes && p->record_group != 0;
+    p->folded = p->scen_lanes && p->record_group != 0 && S <= 16;   // the folded replay keeps 2 S delays in 32 registers
     p->lds_folded = (((size_t)S + (size_t)N) * 64 + 3 * (size_t)S) * 4;
     if (p->folded) p->order_stride = (2ll * S * N + 63) / 64 * 64 + 64;        // the loads run 64 entries ahead
     p->off_order = o;   o += adaptra_detail::align256(p->scen_lanes ? (size_t)C * (size_t)p->order_stride * (p->folded ? 16 : 2) : 0);
@@ -769,6 +791,18 @@ int launch_zb(ZbArgs a, long long scenarios, unsigned full, size_t lds, hipStrea
     const long long units = (a.C + kZbBlock - 1) / kZbBlock * scenarios;   // one wavefront each, at most `full` threads at a time
     a.threads = (unsigned)(units < (long long)(full / kZbBlock) ? units : (long long)(full / kZbBlock)) * kZbBlock;
     hipLaunchKernelGGL((k_zb<PHASE, NARROW, QLDS>), dim3(a.threads / kZbBlock), dim3(kZbBlock), lds, st, a);
+    ADAPTRA_CHECK_LAUNCH();
+    return ADAPTRA_OK;
+}
+
+template <int G, bool FOLDED>
+int launch_record(const ZbArgs &a, size_t lds, hipStream_t st) {
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_zb_record_stages<G, FOLDED>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return adaptra_detail::hip_fail(e);
+    }
+    const unsigned blocks = (unsigned)((a.C * G + kZbBlock - 1) / kZbBlock);
+    hipLaunchKernelGGL((k_zb_record_stages<G, FOLDED>), dim3(blocks), dim3(kZbBlock), lds, st, a);
     ADAPTRA_CHECK_LAUNCH();
     return ADAPTRA_OK;
 }
@@ -852,16 +886,13 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
     const bool queues_in_lds = (a.C + kZbBlock - 1) / kZbBlock <= kCus && lds_queues <= (160u << 10);
     int rc;
     if (p.record_group) {
-        if (p.lds_record > 48 * 1024) {
-            hipError_t e = hipFuncSetAttribute(p.record_group == 8 ? (const void *)k_zb_record_stages<8> : (const void *)k_zb_record_stages<16>,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_record);
-            if (e != hipSuccess) return adaptra_detail::hip_fail(e);
+        const bool f = p.folded;
+        switch (p.record_group) {
+            case 8:  rc = f ? launch_record<8, true>(a, p.lds_record, st) : launch_record<8, false>(a, p.lds_record, st); break;
+            case 16: rc = f ? launch_record<16, true>(a, p.lds_record, st) : launch_record<16, false>(a, p.lds_record, st); break;
+            case 32: rc = launch_record<32, false>(a, p.lds_record, st); break;
+            default: rc = launch_record<64, false>(a, p.lds_record, st); break;
         }
-        const unsigned blocks = (unsigned)((a.C * p.record_group + kZbBlock - 1) / kZbBlock);
-        if (p.record_group == 8) hipLaunchKernelGGL(k_zb_record_stages<8>, dim3(blocks), dim3(kZbBlock), p.lds_record, st, a);
-        else hipLaunchKernelGGL(k_zb_record_stages<16>, dim3(blocks), dim3(kZbBlock), p.lds_record, st, a);
-        ADAPTRA_CHECK_LAUNCH();
-        rc = ADAPTRA_OK;
     } else if (queues_in_lds)
         rc = p.narrow ? launch_zb<1, true, true>(a, 1, kCus * kZbBlock, lds_queues, st) : launch_zb<1, false, true>(a, 1, kCus * kZbBlock, lds_queues, st);
     else
