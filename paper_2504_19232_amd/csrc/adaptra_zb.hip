@@ -599,19 +599,20 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_replay_scen(ZbArgs a) {
 // spends on weight ops between two of its other ops (the same in every scenario), and the op after
 // them is  fin = max(busy[i] + weight time, ready[m]) + duration.  A third fewer ops, no slot and
 // no delay row for weight ops; the makespan is the latest busy-until time, the weight ops behind
-// a stage's last backward op (ZbArgs::tail_w) included.  This replay only follows a recording by
-// k_zb_record_stages, i.e. at most 16 stages: a lane's 2 S link delays then fit 32 registers,
-// which the compiler indexes with the op's (uniform) row number, and LDS holds only the rows
-// that are written: S + N of them (0.28 -> 0.24 ms on 2^20 pairs against all rows in LDS; the
+// a stage's last backward op (ZbArgs::tail_w) included.  Up to 16 stages (DELAY_REGS) a lane's 2 S
+// link delays fit 32 registers, which the compiler indexes with the op's (uniform) row number,
+// and LDS holds only the rows that are written: S + N of them (0.28 -> 0.24 ms on 2^20 pairs against all rows in LDS; the
 // busy-until times in registers as well would exceed the 32 registers the compiler keeps
 // indexable and go to scratch memory).
+template <bool DELAY_REGS>
 __global__ __launch_bounds__(kZbBlock) void k_zb_replay_folded(ZbArgs a) {
     extern __shared__ int zb_lds[];
     const int S = a.S, N = a.N, lane = threadIdx.x;
     int *const busy = zb_lds + lane;                  // [S][64]
     int *const ready = busy + S * 64;                 // [N][64]
-    int *const dur = zb_lds + (S + N) * 64;           // [3][S]: t_f, t_b, t_w
-    int delay_r[32];                                  // link i -> i+1 at i, link i-1 <- i at S + i; set below under static indices
+    int *const delay = ready + N * 64;                // [2][S][64] unless DELAY_REGS: link i -> i+1, link i-1 <- i
+    int *const dur = zb_lds + ((DELAY_REGS ? S : 3 * S) + N) * 64;   // [3][S]: t_f, t_b, t_w
+    int delay_r[32];                                  // DELAY_REGS (S <= 16): link i -> i+1 at i, link i-1 <- i at S + i; set below under static indices
     // block -> (candidate, tile of 64 scenarios) as in k_zb_replay_scen
     const long long n_tiles = (a.K + kZbBlock - 1) / kZbBlock;
     const long long per_xcd = (a.C + kXcds - 1) / kXcds;
@@ -623,12 +624,19 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_replay_folded(ZbArgs a) {
     const long long k = live ? k_lane : a.K - 1;
     for (int i = lane; i < 3 * S; i += kZbBlock) dur[i] = i < S ? a.t_f[i] : (i < 2 * S ? a.t_b[i - S] : a.t_w[i - 2 * S]);
     for (int i = 0; i < S; ++i) busy[i * 64] = 0;
+    if (DELAY_REGS) {
 #pragma unroll
-    for (int j = 0; j < 32; ++j) {
-        int d = 0;
-        if (j < S - 1) d = a.cf[(long long)j * a.K + k];
-        else if (j > S && j < 2 * S) d = a.cb[(long long)(j - S - 1) * a.K + k];
-        delay_r[j] = d;
+        for (int j = 0; j < 32; ++j) {
+            int d = 0;
+            if (j < S - 1) d = a.cf[(long long)j * a.K + k];
+            else if (j > S && j < 2 * S) d = a.cb[(long long)(j - S - 1) * a.K + k];
+            delay_r[j] = d;
+        }
+    } else {
+        for (int i = 0; i < S; ++i) {
+            delay[i * 64] = i < S - 1 ? a.cf[(long long)i * a.K + k] : 0;
+            delay[(S + i) * 64] = i > 0 ? a.cb[(long long)(i - 1) * a.K + k] : 0;
+        }
     }
     for (int m = 0; m < N; ++m) ready[m * 64] = 0;
     __syncthreads();
@@ -638,7 +646,7 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_replay_folded(ZbArgs a) {
     auto run = [&](unsigned offsets, unsigned weight_time, unsigned length, unsigned m256) {
         const int row = (int)(offsets >> 24);
         int *const busy_i = at(busy, offsets & 0xffffu), *const ready_m = at(ready, m256);
-        const int b = *busy_i + (int)weight_time, r = *ready_m, d = delay_r[row];
+        const int b = *busy_i + (int)weight_time, r = *ready_m, d = DELAY_REGS ? delay_r[row] : *at(delay, offsets >> 16);
         const int fin = imax2(b, r) + (int)length;
         *busy_i = fin;
         *ready_m = fin + d;
@@ -772,8 +780,8 @@ bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
         if (per_cu > 32) per_cu = 32;
         if (blocks > kCus * per_cu) p->record_group = 0;
     }
-    p->folded = p->scen_lanes && p->record_group != 0 && S <= 16;   // the folded replay keeps 2 S delays in 32 registers
-    p->lds_folded = (((size_t)S + (size_t)N) * 64 + 3 * (size_t)S) * 4;
+    p->folded = p->scen_lanes && p->record_group != 0;
+    p->lds_folded = (((size_t)(S <= 16 ? S : 3 * S) + (size_t)N) * 64 + 3 * (size_t)S) * 4;   // up to 16 stages the delays are in registers
     if (p->folded) p->order_stride = (2ll * S * N + 63) / 64 * 64 + 64;        // the loads run 64 entries ahead
     p->off_order = o;   o += adaptra_detail::align256(p->scen_lanes ? (size_t)C * (size_t)p->order_stride * (p->folded ? 16 : 2) : 0);
     p->off_tail = o;    o += adaptra_detail::align256(p->folded ? (size_t)C * S * 4 : 0);
@@ -890,8 +898,8 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
         switch (p.record_group) {
             case 8:  rc = f ? launch_record<8, true>(a, p.lds_record, st) : launch_record<8, false>(a, p.lds_record, st); break;
             case 16: rc = f ? launch_record<16, true>(a, p.lds_record, st) : launch_record<16, false>(a, p.lds_record, st); break;
-            case 32: rc = launch_record<32, false>(a, p.lds_record, st); break;
-            default: rc = launch_record<64, false>(a, p.lds_record, st); break;
+            case 32: rc = f ? launch_record<32, true>(a, p.lds_record, st) : launch_record<32, false>(a, p.lds_record, st); break;
+            default: rc = f ? launch_record<64, true>(a, p.lds_record, st) : launch_record<64, false>(a, p.lds_record, st); break;
         }
     } else if (queues_in_lds)
         rc = p.narrow ? launch_zb<1, true, true>(a, 1, kCus * kZbBlock, lds_queues, st) : launch_zb<1, false, true>(a, 1, kCus * kZbBlock, lds_queues, st);
@@ -899,12 +907,15 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
         rc = p.narrow ? launch_zb<1, true>(a, 1, p.threads, p.lds, st) : launch_zb<1, false>(a, 1, p.threads, p.lds, st);
     if (rc) return rc;
     if (p.folded) {
+        const bool regs = a.S <= 16;
         if (p.lds_folded > 48 * 1024) {
-            hipError_t e = hipFuncSetAttribute((const void *)k_zb_replay_folded, hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_folded);
+            hipError_t e = regs ? hipFuncSetAttribute((const void *)k_zb_replay_folded<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_folded)
+                                : hipFuncSetAttribute((const void *)k_zb_replay_folded<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_folded);
             if (e != hipSuccess) return adaptra_detail::hip_fail(e);
         }
         const long long blocks = (a.C + kXcds - 1) / kXcds * kXcds * ((a.K + kZbBlock - 1) / kZbBlock);
-        hipLaunchKernelGGL(k_zb_replay_folded, dim3((unsigned)blocks), dim3(kZbBlock), p.lds_folded, st, a);
+        if (regs) hipLaunchKernelGGL(k_zb_replay_folded<true>, dim3((unsigned)blocks), dim3(kZbBlock), p.lds_folded, st, a);
+        else hipLaunchKernelGGL(k_zb_replay_folded<false>, dim3((unsigned)blocks), dim3(kZbBlock), p.lds_folded, st, a);
         ADAPTRA_CHECK_LAUNCH();
         return ADAPTRA_OK;
     }

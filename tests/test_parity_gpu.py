@@ -582,7 +582,10 @@ ZB_CASES = [(1, 1, 1, 3, 2), (2, 2, 3, 9, 5), (3, 4, 8, 40, 21), (4, 8, 16, 70, 
             # replayed without weight ops: 11 stages in groups of 16, two tiles of scenarios, several blocks of
             # candidates, an order whose length is no multiple of the replay's 64-entry blocks; 7 stages likewise
             (21, 11, 20, 300, 70), (22, 7, 33, 130, 9), (23, 16, 31, 40, 64),
-            (24, 8, 255, 9, 8)]           # that recording's largest queues (one wavefront per CU)
+            (24, 8, 255, 9, 8),           # that recording's largest queues (one wavefront per CU)
+            # more stage-lane wavefronts than are resident at once (263 of 85 KiB each): recorded with a lane per
+            # candidate and replayed with the weight ops in the order
+            (25, 3, 170, 2100, 20)]
 
 
 @pytest.mark.parametrize("case", ZB_CASES, ids=["S%d_N%d_C%d_K%d" % c[1:5] + ("_x%d" % c[5] if len(c) > 5 else "") for c in ZB_CASES])
