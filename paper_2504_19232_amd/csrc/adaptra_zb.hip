@@ -111,7 +111,7 @@ struct ZbArgs {
     long long plan_scenario;      // -1: every pair generates under its own scenario
     int *out_makespan, *out_bubble;
     int *scratch;                 // queues [S][2][N][threads]
-    uint8_t *plans;               // [C][S][3N], op types in the order a stage ran them (written by PHASE 1)
+    uint8_t *plans;               // [C][S][3N], op types in the order a stage ran them (written by PHASE 1), or null
     const uint32_t *packed;       // [ceil(C/64)][S][packed_words(N)][64 candidates], the same at 2 bits per op (see
                                   // packed_words), read by PHASE 2: the lanes of a wavefront read neighbouring words
     uint16_t *order;              // [C][order_stride] or null: stage | type << 6 | slot << 8 of every op in the order
@@ -432,7 +432,7 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_record_stages(ZbArgs a) {
         const unsigned long long in_group = zb_group_bits<G>(__ballot(act && (!FOLDED || ty < 2)));
         if (act) {
             if (exists) {
-                plan[nF + nB + nW] = (uint8_t)ty;
+                if (a.plans) plan[nF + nB + nW] = (uint8_t)ty;
                 const long long at = c * a.order_stride + recorded + __popcll(in_group & below_me);
                 if (FOLDED) {
                     if (a.order_folded && ty < 2)
@@ -874,7 +874,8 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
     a.plan_scenario = plan_scenario;
     a.out_makespan = out_makespan; a.out_bubble = out_bubble;
     a.scratch = (int *)((char *)workspace + p.off_scratch);
-    a.plans = (uint8_t *)workspace + p.off_plans;
+    // each stage's op types are read by the replay with the candidates on the lanes only
+    a.plans = p.scen_lanes && p.record_group ? nullptr : (uint8_t *)workspace + p.off_plans;
     uint32_t *packed = (uint32_t *)((char *)workspace + p.off_packed);
     a.packed = packed;
     unsigned long long *counters = (unsigned long long *)((char *)workspace + p.off_counters);
