@@ -43,7 +43,10 @@
 // wavefronts can hide.
 //
 // Fixed plans (generated once per candidate under one scenario, then run under all of them) need
-// none of this when replayed: see k_zb_replay_scen, which puts the scenarios on the lanes.
+// none of this when replayed: k_zb_replay_folded and k_zb_replay_scen put the scenarios on the
+// lanes and run a recorded order.  Their recording is a launch of few pairs, for which
+// k_zb_record_stages spreads a candidate's stages over neighbouring lanes instead (k_zb<1, ., .>
+// where that launch would not fit the chip at once).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -141,10 +144,10 @@ constexpr long long kScenReplayFrom = 8;   // scenarios from which a replay puts
 constexpr int kXcds = 8;              // accelerator dies of an MI355X; workgroup b is dispatched to die b mod 8
 constexpr int kCus = 256;             // compute units of an MI355X
 
-// Next action of a stage from its own fields (Algorithm 3): the time it can act, or kInf if
+// Next action of a stage from its own fields (Algorithm 3): the time it can act, or 2^31 or more if
 // nothing it may run has been posted yet.
 template <int PHASE, bool NARROW>
-__device__ __forceinline__ int next_action(int busy, const Cursors<NARROW> &c, unsigned headF, unsigned headB) {
+__device__ __forceinline__ unsigned next_action(int busy, const Cursors<NARROW> &c, unsigned headF, unsigned headB) {
     const unsigned headW = c.nW() < c.nB() ? 0u : ~0u;           // ready since its backward finished
     unsigned first;
     if (PHASE == 2) {
@@ -153,7 +156,7 @@ __device__ __forceinline__ int next_action(int busy, const Cursors<NARROW> &c, u
     } else {
         first = c.nF() < c.hi() ? headF : umin(headB, umin(headF, headW));   // warm-up: forwards only
     }
-    return is_empty(first) ? kInf : imax2(busy, (int)first);
+    return first > (unsigned)busy ? first : (unsigned)busy;      // "nothing posted" stays at or above 2^31: behind every time
 }
 
 // PHASE 0: generate with the policy and write the outputs; 1: generate under the plan scenario
@@ -208,7 +211,7 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
         }
         __syncthreads();
         // set-up: nothing posted except the forwards of stage 0 (available at time 0)
-        for (int i = S; i < Spad; ++i) act[i * 64] = kInf;
+        for (int i = S; i < Spad; ++i) act[i * 64] = -1;            // read as unsigned: behind every time
         for (int i = 0; i < S; ++i) {
             int wi = a.w[(long long)i * a.C + c];
             wi = wi < 0 ? 0 : (wi > N - 1 ? N - 1 : wi);
@@ -219,7 +222,7 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
             cur.store(st);
             st[Cur::kHeadF] = (int)headF;
             st[Cur::kHeadB] = (int)headB;
-            act[i * 64] = next_action<PHASE>(0, cur, headF, headB);
+            act[i * 64] = (int)next_action<PHASE>(0, cur, headF, headB);
         }
 
         const int total = 3 * S * N;
@@ -240,17 +243,20 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
                 }
             }
             // the stage whose next action is earliest, ties to the lower stage
-            int i = 0, t = kInf;
+            int i = 0;
+            unsigned t_min = ~0u;
             for (int b = 0; b < Spad; b += 8) {
-                int tb = act[b * 64], jb = 0;
+                unsigned tb = (unsigned)act[b * 64];
+                int jb = 0;
 #pragma unroll
                 for (int j = 1; j < 8; ++j) {
-                    const int tj = act[(b + j) * 64];
+                    const unsigned tj = (unsigned)act[(b + j) * 64];
                     if (tj < tb) { tb = tj; jb = j; }
                 }
-                if (tb < t) { t = tb; i = b + jb; }
+                if (tb < t_min) { t_min = tb; i = b + jb; }
             }
-            if (t == kInf) { makespan = kInf; break; }          // cannot happen for valid input
+            if ((int)t_min < 0) { makespan = kInf; break; }     // nothing can act: cannot happen for valid input
+            const int t = (int)t_min;
             // Everything whose address depends on the stage alone is read now, in one round trip:
             // the stage's fields, its three durations and two delays, the cursors of the two
             // producing stages.
@@ -302,14 +308,14 @@ __global__ __launch_bounds__(kZbBlock) void k_zb(ZbArgs a) {
             cur.store(st);
             st[Cur::kHeadF] = (int)headF;
             st[Cur::kHeadB] = (int)headB;
-            act[i * 64] = next_action<PHASE>(fin, cur, headF, headB);
+            act[i * 64] = (int)next_action<PHASE>(fin, cur, headF, headB);
             if (posts) {
                 const int r = fin + (ty == 0 ? delay_i.x : delay_i.y);
                 const unsigned slot = ty == 0 ? headF_j : headB_j;
                 if (is_empty(slot)) {                           // r becomes the head: the receiver may act earlier
                     if (ty == 0) headF_j = (unsigned)r; else headB_j = (unsigned)r;
                     sj[ty == 0 ? Cur::kHeadF : Cur::kHeadB] = r;
-                    act[j * 64] = next_action<PHASE>((int)~slot, cur_j, headF_j, headB_j);
+                    act[j * 64] = (int)next_action<PHASE>((int)~slot, cur_j, headF_j, headB_j);
                 } else {
                     queue[__umul24(__umul24((unsigned)(j * 2 + ty), (unsigned)N) + (unsigned)m, nt)] = r;
                 }
