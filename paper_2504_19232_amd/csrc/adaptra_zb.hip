@@ -605,20 +605,28 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_replay_scen(ZbArgs a) {
 // spends on weight ops between two of its other ops (the same in every scenario), and the op after
 // them is  fin = max(busy[i] + weight time, ready[m]) + duration.  A third fewer ops, no slot and
 // no delay row for weight ops; the makespan is the latest busy-until time, the weight ops behind
-// a stage's last backward op (ZbArgs::tail_w) included.  Up to 16 stages (DELAY_REGS) a lane's 2 S
-// link delays fit 32 registers, which the compiler indexes with the op's (uniform) row number,
-// and LDS holds only the rows that are written: S + N of them (0.28 -> 0.24 ms on 2^20 pairs against all rows in LDS; the
-// busy-until times in registers as well would exceed the 32 registers the compiler keeps
-// indexable and go to scratch memory).
-template <bool DELAY_REGS>
+// a stage's last backward op (ZbArgs::tail_w) included.
+// REGS = 16 or 32 (at most that many stages): a lane's busy-until times and link delays are in
+// registers, arrays that the compiler indexes with the op's (uniform) stage or row number
+// (s_set_gpr_idx), and LDS holds only the N ready times -- no round trip for them, and two to
+// four times the wavefronts per CU.  The compiler keeps such an array in registers if it has at
+// most 32 elements and every access under a run-time index is a plain load or store of its own
+// (they are set below under static indices; a conditional between two of them is written as two
+// loads and a select): at 16 stages both directions' delays share one array under the row
+// number, at 32 each direction has its own.  REGS = 0 (up to 64 stages): all rows in LDS.
+template <int REGS>
 __global__ __launch_bounds__(kZbBlock) void k_zb_replay_folded(ZbArgs a) {
+    static_assert(REGS == 0 || REGS == 16 || REGS == 32, "register arrays of 16 or 32 stages, or none");
+    constexpr int kRegs = REGS ? REGS : 1, kBack = REGS == 32 ? 32 : 1, kDelays = REGS ? 32 : 1;
     extern __shared__ int zb_lds[];
     const int S = a.S, N = a.N, lane = threadIdx.x;
-    int *const busy = zb_lds + lane;                  // [S][64]
-    int *const ready = busy + S * 64;                 // [N][64]
-    int *const delay = ready + N * 64;                // [2][S][64] unless DELAY_REGS: link i -> i+1, link i-1 <- i
-    int *const dur = zb_lds + ((DELAY_REGS ? S : 3 * S) + N) * 64;   // [3][S]: t_f, t_b, t_w
-    int delay_r[32];                                  // DELAY_REGS (S <= 16): link i -> i+1 at i, link i-1 <- i at S + i; set below under static indices
+    int *const ready = zb_lds + lane;                 // [N][64]
+    int *const busy = ready + N * 64;                 // REGS = 0: [S][64]
+    int *const delay = busy + S * 64;                 // REGS = 0: [2][S][64]: link i -> i+1, link i-1 <- i
+    int *const dur = zb_lds + ((REGS ? 0 : 3 * S) + N) * 64;   // [3][S]: t_f, t_b, t_w
+    int busy_r[kRegs];
+    int delay_r[kDelays];                             // REGS = 16: link i -> i+1 at i, link i-1 <- i at S + i; 32: link i -> i+1 at i
+    int back_r[kBack];                                // REGS = 32: link i-1 <- i at i
     // block -> (candidate, tile of 64 scenarios) as in k_zb_replay_scen
     const long long n_tiles = (a.K + kZbBlock - 1) / kZbBlock;
     const long long per_xcd = (a.C + kXcds - 1) / kXcds;
@@ -629,32 +637,47 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_replay_folded(ZbArgs a) {
     const bool live = k_lane < a.K;
     const long long k = live ? k_lane : a.K - 1;
     for (int i = lane; i < 3 * S; i += kZbBlock) dur[i] = i < S ? a.t_f[i] : (i < 2 * S ? a.t_b[i - S] : a.t_w[i - 2 * S]);
-    for (int i = 0; i < S; ++i) busy[i * 64] = 0;
-    if (DELAY_REGS) {
+    if (REGS) {
+#pragma unroll
+        for (int i = 0; i < kRegs; ++i) busy_r[i] = 0;
 #pragma unroll
         for (int j = 0; j < 32; ++j) {
-            int d = 0;
-            if (j < S - 1) d = a.cf[(long long)j * a.K + k];
-            else if (j > S && j < 2 * S) d = a.cb[(long long)(j - S - 1) * a.K + k];
-            delay_r[j] = d;
+            const int forward = j < S - 1 ? a.cf[(long long)j * a.K + k] : 0;
+            if (REGS == 16) {
+                delay_r[j % kDelays] = j > S && j < 2 * S ? a.cb[(long long)(j - S - 1) * a.K + k] : forward;
+            } else {
+                delay_r[j % kDelays] = forward;
+                back_r[j % kBack] = j > 0 && j < S ? a.cb[(long long)(j - 1) * a.K + k] : 0;
+            }
         }
     } else {
         for (int i = 0; i < S; ++i) {
+            busy[i * 64] = 0;
             delay[i * 64] = i < S - 1 ? a.cf[(long long)i * a.K + k] : 0;
             delay[(S + i) * 64] = i > 0 ? a.cb[(long long)(i - 1) * a.K + k] : 0;
         }
     }
     for (int m = 0; m < N; ++m) ready[m * 64] = 0;
     __syncthreads();
-    // Everything uniform comes out of the entry ready for use: the byte offsets of the three rows
-    // ([index][lane] ints: 256 bytes a row) and the two times, which are scalar operands of the adds.
+    // Everything uniform comes out of the entry ready for use: the byte offsets of the LDS rows
+    // ([index][lane] ints: 256 bytes a row), stage and row number, and the two times, which are
+    // scalar operands of the adds.
     auto at = [](int *rows, unsigned bytes) { return reinterpret_cast<int *>(reinterpret_cast<char *>(rows) + bytes); };
     auto run = [&](unsigned offsets, unsigned weight_time, unsigned length, unsigned m256) {
-        const int row = (int)(offsets >> 24);
-        int *const busy_i = at(busy, offsets & 0xffffu), *const ready_m = at(ready, m256);
-        const int b = *busy_i + (int)weight_time, r = *ready_m, d = DELAY_REGS ? delay_r[row] : *at(delay, offsets >> 16);
-        const int fin = imax2(b, r) + (int)length;
-        *busy_i = fin;
+        const int i = (int)((offsets >> 8) & 0xffu), row = (int)(offsets >> 24);
+        int *const ready_m = at(ready, m256), *const busy_i = at(busy, offsets & 0xffffu);
+        int d, b;
+        if (REGS == 16) {
+            d = delay_r[row % kDelays];
+        } else if (REGS == 32) {
+            const int forward = delay_r[i % kDelays], backward = back_r[i % kBack];
+            d = row < S ? forward : backward;
+        } else {
+            d = *at(delay, offsets >> 16);
+        }
+        b = REGS ? busy_r[i % kRegs] : *busy_i;
+        const int fin = imax2(b + (int)weight_time, *ready_m) + (int)length;
+        if (REGS) busy_r[i % kRegs] = fin; else *busy_i = fin;
         *ready_m = fin + d;
     };
     // Lane j of the wavefront holds entry base + j of the order (one 16-byte load per lane and 64
@@ -679,7 +702,13 @@ __global__ __launch_bounds__(kZbBlock) void k_zb_replay_folded(ZbArgs a) {
     }
     for (int j = 0; base + j < total; ++j) run_lane(cur, j);
     int makespan = 0;
-    for (int i = 0; i < S; ++i) makespan = imax2(makespan, busy[i * 64] + a.tail_w[c * S + i]);
+    if (REGS) {
+#pragma unroll
+        for (int i = 0; i < kRegs; ++i)
+            if (i < S) makespan = imax2(makespan, busy_r[i] + a.tail_w[c * S + i]);
+    } else {
+        for (int i = 0; i < S; ++i) makespan = imax2(makespan, busy[i * 64] + a.tail_w[c * S + i]);
+    }
     if (!recorded) makespan = kInf;                   // the recording stopped: so does every replay of it
     if (live) {
         const long long P = a.C * a.K, item = k * a.C + c;
@@ -787,7 +816,7 @@ bool plan_zb(int S, int N, long long C, long long K, ZbPlan *p) {
         if (blocks > kCus * per_cu) p->record_group = 0;
     }
     p->folded = p->scen_lanes && p->record_group != 0;
-    p->lds_folded = (((size_t)(S <= 16 ? S : 3 * S) + (size_t)N) * 64 + 3 * (size_t)S) * 4;   // up to 16 stages the delays are in registers
+    p->lds_folded = (((size_t)(S <= 32 ? 0 : 3 * S) + (size_t)N) * 64 + 3 * (size_t)S) * 4;   // up to 32 stages only the ready times are in LDS
     if (p->folded) p->order_stride = (2ll * S * N + 63) / 64 * 64 + 64;        // the loads run 64 entries ahead
     p->off_order = o;   o += adaptra_detail::align256(p->scen_lanes ? (size_t)C * (size_t)p->order_stride * (p->folded ? 16 : 2) : 0);
     p->off_tail = o;    o += adaptra_detail::align256(p->folded ? (size_t)C * S * 4 : 0);
@@ -805,6 +834,17 @@ int launch_zb(ZbArgs a, long long scenarios, unsigned full, size_t lds, hipStrea
     const long long units = (a.C + kZbBlock - 1) / kZbBlock * scenarios;   // one wavefront each, at most `full` threads at a time
     a.threads = (unsigned)(units < (long long)(full / kZbBlock) ? units : (long long)(full / kZbBlock)) * kZbBlock;
     hipLaunchKernelGGL((k_zb<PHASE, NARROW, QLDS>), dim3(a.threads / kZbBlock), dim3(kZbBlock), lds, st, a);
+    ADAPTRA_CHECK_LAUNCH();
+    return ADAPTRA_OK;
+}
+
+template <int REGS>
+int launch_replay_folded(const ZbArgs &a, long long blocks, size_t lds, hipStream_t st) {
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_zb_replay_folded<REGS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return adaptra_detail::hip_fail(e);
+    }
+    hipLaunchKernelGGL((k_zb_replay_folded<REGS>), dim3((unsigned)blocks), dim3(kZbBlock), lds, st, a);
     ADAPTRA_CHECK_LAUNCH();
     return ADAPTRA_OK;
 }
@@ -914,17 +954,10 @@ int adaptra_zb_eval(const adaptra_params_t *params, const int32_t *t_w, const ad
         rc = p.narrow ? launch_zb<1, true>(a, 1, p.threads, p.lds, st) : launch_zb<1, false>(a, 1, p.threads, p.lds, st);
     if (rc) return rc;
     if (p.folded) {
-        const bool regs = a.S <= 16;
-        if (p.lds_folded > 48 * 1024) {
-            hipError_t e = regs ? hipFuncSetAttribute((const void *)k_zb_replay_folded<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_folded)
-                                : hipFuncSetAttribute((const void *)k_zb_replay_folded<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_folded);
-            if (e != hipSuccess) return adaptra_detail::hip_fail(e);
-        }
         const long long blocks = (a.C + kXcds - 1) / kXcds * kXcds * ((a.K + kZbBlock - 1) / kZbBlock);
-        if (regs) hipLaunchKernelGGL(k_zb_replay_folded<true>, dim3((unsigned)blocks), dim3(kZbBlock), p.lds_folded, st, a);
-        else hipLaunchKernelGGL(k_zb_replay_folded<false>, dim3((unsigned)blocks), dim3(kZbBlock), p.lds_folded, st, a);
-        ADAPTRA_CHECK_LAUNCH();
-        return ADAPTRA_OK;
+        return a.S <= 16 ? launch_replay_folded<16>(a, blocks, p.lds_folded, st)
+             : a.S <= 32 ? launch_replay_folded<32>(a, blocks, p.lds_folded, st)
+                         : launch_replay_folded<0>(a, blocks, p.lds_folded, st);
     }
     if (p.scen_lanes) {
         if (p.lds_scen > 48 * 1024) {
